@@ -1,0 +1,209 @@
+/* moe_oracle.c — TEST INFRASTRUCTURE, not a product path.
+ *
+ * Plain, slow, single-threaded CPU statement of what one MoE layer computes when
+ * a speculative-decoding verification step pushes T = K+1 tokens through it
+ * (paper: Section 1, the "2 of 8 experts per token, up to 6 for three drafts"
+ * example; Section 2.1, router + experts; Section 2.2, verification of the K
+ * drafts in one target step; Section 2.4, unique experts grow with K).
+ *
+ * Verification is iso-accuracy (Section 2.2): every token must get exactly what
+ * decoding it alone would give.  So the oracle is simply the textbook definition
+ * of a top-k softmax-gated SwiGLU mixture applied row by row — no grouping, no
+ * blocking, no reuse across tokens.  The paper does not spell the operator out;
+ * the benchmark definition does: bias-free linear router, top-k on the logits,
+ * gates = softmax over the selected logits, expert = w2 . (silu(w1 x) * (w3 x)),
+ * optional always-on shared experts with gate 1.
+ *
+ * Precision: the file is compiled twice, REAL=float (the "plain fp32" oracle the
+ * parity bar is stated against) and REAL=double (accuracy reference).  In BOTH
+ * builds the router logits are accumulated in double: a product of an fp32
+ * activation and a bf16 weight is exact in double, so the logit, and with it the
+ * integer top-k decision, does not depend on summation order beyond ~1e-13
+ * relative — this is the precision the HIP router also decides in.
+ *
+ * Only tests/, the smoke check and the bench's cpu_baseline leg may call this.
+ * Shares no code with the HIP library.  Parity pins: see tests/test_oracle_pins.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifndef REAL
+#define REAL float
+#endif
+
+static REAL real_exp(REAL v) { return sizeof(REAL) == sizeof(float) ? (REAL)expf((float)v) : (REAL)exp((double)v); }
+
+/* bf16 is the upper half of an IEEE fp32: widening is exact. */
+static float bf16_widen(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+int oracle_real_bytes(void) { return (int)sizeof(REAL); }
+
+/* Router logits, top-k and gates for T tokens (Section 2.1: a small gating network
+ * selects a few experts per token; each token selects independently, Section 1).
+ *   logit[t,e] = sum_j hidden[t,j] * router_w[e,j]          (double, j ascending)
+ *   ids[t,0..top_k) = repeated arg-max of logit[t,.]; equal values -> lower expert index
+ *   gates[t,i] = exp(l_i - l_0) / sum_i exp(l_i - l_0),  l_i = (REAL)logit[t, ids[t,i]]
+ * logits_out may be NULL; otherwise [T,E] doubles.  Returns 0, or -1 on bad sizes. */
+int oracle_route(const float* hidden, const uint16_t* router_w, int T, int d, int E, int top_k,
+                 int32_t* ids, float* gates, double* logits_out) {
+  if (T < 1 || d < 1 || E < 1 || top_k < 1 || top_k > E) return -1;
+  double* logit = (double*)malloc(sizeof(double) * (size_t)E);
+  char* taken = (char*)malloc((size_t)E);
+  REAL* p = (REAL*)malloc(sizeof(REAL) * (size_t)top_k);
+  for (int t = 0; t < T; ++t) {
+    for (int e = 0; e < E; ++e) {
+      double s = 0.0;
+      for (int j = 0; j < d; ++j) s += (double)hidden[(size_t)t * d + j] * (double)bf16_widen(router_w[(size_t)e * d + j]);
+      logit[e] = s;
+      if (logits_out) logits_out[(size_t)t * E + e] = s;
+    }
+    memset(taken, 0, (size_t)E);
+    for (int i = 0; i < top_k; ++i) {
+      int best = -1;
+      for (int e = 0; e < E; ++e)
+        if (!taken[e] && (best < 0 || logit[e] > logit[best])) best = e;
+      taken[best] = 1;
+      ids[(size_t)t * top_k + i] = best;
+    }
+    REAL l0 = (REAL)logit[ids[(size_t)t * top_k]];
+    REAL sum = 0;
+    for (int i = 0; i < top_k; ++i) {
+      p[i] = real_exp((REAL)logit[ids[(size_t)t * top_k + i]] - l0);
+      sum += p[i];
+    }
+    for (int i = 0; i < top_k; ++i) gates[(size_t)t * top_k + i] = (float)(p[i] / sum);
+  }
+  free(logit);
+  free(taken);
+  free(p);
+  return 0;
+}
+
+/* Union of activated experts and the per-expert token lists (Section 1 and 2.2: the
+ * in-flight tokens collectively activate a larger set; that set is what is fetched).
+ *   unique[0..n_unique) ascending distinct ids; count[e]; offset[e] = sum_{e'<e} count[e'];
+ *   assign[offset[e] ..) = flat assignment indices a = t*top_k + i with ids[a] == e, ascending. */
+int oracle_union(const int32_t* ids, int T, int top_k, int E, int32_t* unique, int32_t* n_unique,
+                 int32_t* count, int32_t* offset, int32_t* assign) {
+  int A = T * top_k, n = 0, pos = 0;
+  for (int e = 0; e < E; ++e) {
+    int c = 0;
+    offset[e] = pos;
+    for (int a = 0; a < A; ++a)
+      if (ids[a] == e) {
+        assign[pos++] = a;
+        ++c;
+      }
+    count[e] = c;
+    if (c > 0) unique[n++] = e;
+  }
+  offset[E] = pos;
+  for (int i = n; i < E; ++i) unique[i] = -1;
+  *n_unique = n;
+  return pos == A ? 0 : -1; /* an id outside [0,E) leaves assignments unplaced */
+}
+
+/* One SwiGLU expert on one token: y = w2 . ( silu(w1 x) * (w3 x) ), silu(z) = z / (1 + exp(-z)).
+ * w1, w3: [ffn, d]; w2: [d, ffn]; all bf16 row-major.  h: scratch [ffn].  Index-ascending sums in REAL. */
+void oracle_expert_ffn(const float* x, const uint16_t* w1, const uint16_t* w3, const uint16_t* w2, int d, int ffn,
+                       REAL* h, REAL* y) {
+  for (int r = 0; r < ffn; ++r) {
+    REAL g = 0, u = 0;
+    const uint16_t* a = w1 + (size_t)r * d;
+    const uint16_t* b = w3 + (size_t)r * d;
+    for (int j = 0; j < d; ++j) g += (REAL)bf16_widen(a[j]) * (REAL)x[j];
+    for (int j = 0; j < d; ++j) u += (REAL)bf16_widen(b[j]) * (REAL)x[j];
+    h[r] = (g / ((REAL)1 + real_exp(-g))) * u;
+  }
+  for (int c = 0; c < d; ++c) {
+    REAL s = 0;
+    const uint16_t* a = w2 + (size_t)c * ffn;
+    for (int r = 0; r < ffn; ++r) s += (REAL)bf16_widen(a[r]) * h[r];
+    y[c] = s;
+  }
+}
+
+/* Gate-weighted combine given a routing (ids, gates):
+ *   out[t] = sum_{i<top_k} gates[t,i] * FFN_{ids[t,i]}(x_t)   (slot order)
+ *            + sum_{s<n_shared} FFN_shared_s(x_t)             (gate 1, index order)
+ * Each (token, slot) pair is evaluated on its own: no sharing of work between tokens. */
+int oracle_combine(const float* hidden, int T, int d, int ffn, int E, int top_k, int n_shared,
+                   const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
+                   const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2,
+                   const int32_t* ids, const float* gates, float* out) {
+  REAL* h = (REAL*)malloc(sizeof(REAL) * (size_t)ffn);
+  REAL* y = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  REAL* acc = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  const size_t per = (size_t)ffn * d;
+  int rc = 0;
+  for (int t = 0; t < T && rc == 0; ++t) {
+    const float* x = hidden + (size_t)t * d;
+    for (int c = 0; c < d; ++c) acc[c] = 0;
+    for (int i = 0; i < top_k; ++i) {
+      int e = ids[(size_t)t * top_k + i];
+      if (e < 0 || e >= E) { rc = -1; break; }
+      oracle_expert_ffn(x, w1 + e * per, w3 + e * per, w2 + e * per, d, ffn, h, y);
+      REAL g = (REAL)gates[(size_t)t * top_k + i];
+      for (int c = 0; c < d; ++c) acc[c] += g * y[c];
+    }
+    for (int s = 0; s < n_shared; ++s) {
+      oracle_expert_ffn(x, sw1 + s * per, sw3 + s * per, sw2 + s * per, d, ffn, h, y);
+      for (int c = 0; c < d; ++c) acc[c] += y[c];
+    }
+    for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = (float)acc[c];
+  }
+  free(h);
+  free(y);
+  free(acc);
+  return rc;
+}
+
+/* The whole layer: route, then combine.  ids/gates are outputs. */
+int oracle_layer(const float* hidden, int T, int d, int ffn, int E, int top_k, int n_shared,
+                 const uint16_t* router_w, const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
+                 const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2,
+                 int32_t* ids, float* gates, float* out) {
+  int rc = oracle_route(hidden, router_w, T, d, E, top_k, ids, gates, NULL);
+  if (rc) return rc;
+  return oracle_combine(hidden, T, d, ffn, E, top_k, n_shared, w1, w3, w2, sw1, sw3, sw2, ids, gates, out);
+}
+
+/* Dense masked form of the same layer: EVERY expert is evaluated for every token and
+ * multiplied by M[t,e] = gate if e was selected, else 0; summed in expert-index order.
+ * Differs from oracle_combine only in summation order; used to cross-check it. */
+int oracle_dense_masked(const float* hidden, int T, int d, int ffn, int E, int top_k, int n_shared,
+                        const uint16_t* w1, const uint16_t* w3, const uint16_t* w2,
+                        const uint16_t* sw1, const uint16_t* sw3, const uint16_t* sw2,
+                        const int32_t* ids, const float* gates, float* out) {
+  REAL* h = (REAL*)malloc(sizeof(REAL) * (size_t)ffn);
+  REAL* y = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  REAL* acc = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  const size_t per = (size_t)ffn * d;
+  for (int t = 0; t < T; ++t) {
+    const float* x = hidden + (size_t)t * d;
+    for (int c = 0; c < d; ++c) acc[c] = 0;
+    for (int e = 0; e < E; ++e) {
+      REAL m = 0;
+      for (int i = 0; i < top_k; ++i)
+        if (ids[(size_t)t * top_k + i] == e) m = (REAL)gates[(size_t)t * top_k + i];
+      oracle_expert_ffn(x, w1 + e * per, w3 + e * per, w2 + e * per, d, ffn, h, y);
+      for (int c = 0; c < d; ++c) acc[c] += m * y[c];
+    }
+    for (int s = 0; s < n_shared; ++s) {
+      oracle_expert_ffn(x, sw1 + s * per, sw3 + s * per, sw2 + s * per, d, ffn, h, y);
+      for (int c = 0; c < d; ++c) acc[c] += y[c];
+    }
+    for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = (float)acc[c];
+  }
+  free(h);
+  free(y);
+  free(acc);
+  return 0;
+}

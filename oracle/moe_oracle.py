@@ -1,0 +1,197 @@
+"""ctypes front end of oracle/moe_oracle.c — TEST INFRASTRUCTURE, not a product path.
+
+Only tests/, the smoke check and the bench's cpu_baseline leg may import this.
+It marshals numpy arrays into the plain C oracle and nothing else; the HIP
+library is never imported here.
+
+Two builds of the same C source exist: precision="f32" (the plain fp32 oracle the
+parity bar is stated against) and precision="f64" (accuracy reference).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "moe_oracle.c")
+_LIBS = {}
+
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def lib_path(precision: str) -> str:
+    return os.path.join(_HERE, f"liboracle_{precision}.so")
+
+
+def build(force: bool = True) -> None:
+    """Compile both precisions with gcc (no fast-math, no contraction: sums stay in source order)."""
+    for prec, real in (("f32", "float"), ("f64", "double")):
+        out = lib_path(prec)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+               f"-DREAL={real}", _SRC, "-o", out, "-lm"]
+        subprocess.run(cmd, check=True)
+
+
+def _load(path: str, precision: str):
+    """dlopen one build of the oracle and declare its signatures."""
+    L = ctypes.CDLL(path)
+    L.oracle_real_bytes.restype = ctypes.c_int
+    L.oracle_route.restype = ctypes.c_int
+    L.oracle_route.argtypes = [_f32p, _u16p] + [ctypes.c_int] * 4 + [_i32p, _f32p, _f64p]
+    L.oracle_union.restype = ctypes.c_int
+    L.oracle_union.argtypes = [_i32p] + [ctypes.c_int] * 3 + [_i32p] * 5
+    L.oracle_expert_ffn.restype = None
+    L.oracle_expert_ffn.argtypes = [_f32p, _u16p, _u16p, _u16p, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_void_p, ctypes.c_void_p]
+    comb = [_f32p] + [ctypes.c_int] * 6 + [_u16p] * 6 + [_i32p, _f32p, _f32p]
+    L.oracle_combine.restype = ctypes.c_int
+    L.oracle_combine.argtypes = comb
+    L.oracle_dense_masked.restype = ctypes.c_int
+    L.oracle_dense_masked.argtypes = comb
+    L.oracle_layer.restype = ctypes.c_int
+    L.oracle_layer.argtypes = [_f32p] + [ctypes.c_int] * 6 + [_u16p] * 7 + [_i32p, _f32p, _f32p]
+    assert L.oracle_real_bytes() == (4 if precision == "f32" else 8)
+    return L
+
+
+def _lib(precision: str):
+    if precision not in ("f32", "f64"):
+        raise ValueError(precision)
+    if precision not in _LIBS:
+        build(force=False)
+        _LIBS[precision] = _load(lib_path(precision), precision)
+    return _LIBS[precision]
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_f32p)
+
+
+def _u16(a):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16:
+        a = a.view(np.uint16)
+    return a, a.ctypes.data_as(_u16p)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(_i32p)
+
+
+def route(hidden, router_w, top_k, precision="f32"):
+    """-> ids[T,top_k] int32, gates[T,top_k] fp32, logits[T,E] fp64."""
+    hidden, hp = _f32(hidden)
+    router_w, rp = _u16(router_w)
+    T, d = hidden.shape
+    E = router_w.shape[0]
+    assert router_w.shape == (E, d)
+    ids = np.empty((T, top_k), np.int32)
+    gates = np.empty((T, top_k), np.float32)
+    logits = np.empty((T, E), np.float64)
+    rc = _lib(precision).oracle_route(hp, rp, T, d, E, top_k, ids.ctypes.data_as(_i32p),
+                                      gates.ctypes.data_as(_f32p), logits.ctypes.data_as(_f64p))
+    if rc:
+        raise ValueError("oracle_route: bad sizes")
+    return ids, gates, logits
+
+
+def union(ids, n_experts, precision="f32"):
+    """-> dict(unique[E] (-1 padded), n_unique, count[E], offset[E+1], assign[T*top_k])."""
+    ids, ip = _i32(ids)
+    T, top_k = ids.shape
+    E = n_experts
+    unique = np.empty(E, np.int32)
+    n = np.zeros(1, np.int32)
+    count = np.empty(E, np.int32)
+    offset = np.empty(E + 1, np.int32)
+    assign = np.full(T * top_k, -1, np.int32)
+    rc = _lib(precision).oracle_union(ip, T, top_k, E, *(a.ctypes.data_as(_i32p) for a in (unique, n, count, offset, assign)))
+    if rc:
+        raise ValueError("oracle_union: expert id out of range")
+    return dict(unique=unique, n_unique=int(n[0]), count=count, offset=offset, assign=assign)
+
+
+def expert_ffn(x, w1, w3, w2, precision="f32"):
+    """One SwiGLU expert on one token: x[d], w1/w3[ffn,d], w2[d,ffn] (bf16 bits) -> y[d] (fp64 array of REAL values)."""
+    x, xp = _f32(x)
+    w1, p1 = _u16(w1)
+    w3, p3 = _u16(w3)
+    w2, p2 = _u16(w2)
+    ffn, d = w1.shape
+    assert w3.shape == (ffn, d) and w2.shape == (d, ffn) and x.shape == (d,)
+    dt = np.float32 if precision == "f32" else np.float64
+    h = np.empty(ffn, dt)
+    y = np.empty(d, dt)
+    _lib(precision).oracle_expert_ffn(xp, p1, p3, p2, d, ffn, h.ctypes.data, y.ctypes.data)
+    return y.astype(np.float64), h.astype(np.float64)
+
+
+def _combine_like(fn_name, hidden, W, ids, gates, top_k, n_shared, precision):
+    hidden, hp = _f32(hidden)
+    T, d = hidden.shape
+    w1, p1 = _u16(W["w1"])
+    w3, p3 = _u16(W["w3"])
+    w2, p2 = _u16(W["w2"])
+    E, ffn, _ = w1.shape
+    assert w1.shape == (E, ffn, d) and w3.shape == (E, ffn, d) and w2.shape == (E, d, ffn)
+    sw1, q1 = _u16(W.get("sw1") if n_shared else None)
+    sw3, q3 = _u16(W.get("sw3") if n_shared else None)
+    sw2, q2 = _u16(W.get("sw2") if n_shared else None)
+    if n_shared:
+        assert sw1.shape == (n_shared, ffn, d) and sw2.shape == (n_shared, d, ffn)
+    ids, ip = _i32(ids)
+    gates, gp = _f32(gates)
+    assert ids.shape == (T, top_k) and gates.shape == (T, top_k)
+    out = np.empty((T, d), np.float32)
+    fn = getattr(_lib(precision), fn_name)
+    rc = fn(hp, T, d, ffn, E, top_k, n_shared, p1, p3, p2, q1, q3, q2, ip, gp, out.ctypes.data_as(_f32p))
+    if rc:
+        raise ValueError(f"{fn_name}: expert id out of range")
+    return out
+
+
+def combine(hidden, W, ids, gates, n_shared=0, precision="f32"):
+    """out[T,d] for a GIVEN routing (ids, gates)."""
+    return _combine_like("oracle_combine", hidden, W, ids, gates, np.asarray(ids).shape[1], n_shared, precision)
+
+
+def dense_masked(hidden, W, ids, gates, n_shared=0, precision="f32"):
+    return _combine_like("oracle_dense_masked", hidden, W, ids, gates, np.asarray(ids).shape[1], n_shared, precision)
+
+
+def layer(hidden, W, top_k, n_shared=0, precision="f32"):
+    """Route + combine.  W: dict with router_w, w1, w3, w2 (and sw1, sw3, sw2).  -> out, ids, gates."""
+    hidden, hp = _f32(hidden)
+    T, d = hidden.shape
+    rw, pr = _u16(W["router_w"])
+    w1, p1 = _u16(W["w1"])
+    w3, p3 = _u16(W["w3"])
+    w2, p2 = _u16(W["w2"])
+    E, ffn, _ = w1.shape
+    assert rw.shape == (E, d) and w1.shape == (E, ffn, d) and w3.shape == (E, ffn, d) and w2.shape == (E, d, ffn)
+    sw1, q1 = _u16(W.get("sw1") if n_shared else None)
+    sw3, q3 = _u16(W.get("sw3") if n_shared else None)
+    sw2, q2 = _u16(W.get("sw2") if n_shared else None)
+    if n_shared:
+        assert sw1.shape == (n_shared, ffn, d) and sw3.shape == (n_shared, ffn, d) and sw2.shape == (n_shared, d, ffn)
+    ids = np.empty((T, top_k), np.int32)
+    gates = np.empty((T, top_k), np.float32)
+    out = np.empty((T, d), np.float32)
+    rc = _lib(precision).oracle_layer(hp, T, d, ffn, E, top_k, n_shared, pr, p1, p3, p2, q1, q3, q2,
+                                      ids.ctypes.data_as(_i32p), gates.ctypes.data_as(_f32p),
+                                      out.ctypes.data_as(_f32p))
+    if rc:
+        raise ValueError("oracle_layer: bad sizes")
+    return out, ids, gates

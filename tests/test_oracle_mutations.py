@@ -1,0 +1,68 @@
+"""The pins must be able to fail: plant plausible mistakes in a COPY of the oracle's C source
+(on the CPU), load the mutant in place of the real library, and check that at least one pin
+catches each of them.  No GPU involved."""
+import os
+import subprocess
+
+import pytest
+
+from oracle import moe_oracle as orc
+import test_oracle_pins as pins
+
+MUTANTS = {
+    "swap_w1_w3_roles": ("h[r] = (g / ((REAL)1 + real_exp(-g))) * u;", "h[r] = (u / ((REAL)1 + real_exp(-u))) * g;"),
+    "silu_sign": ("real_exp(-g))) * u;", "real_exp(g))) * u;"),
+    "drop_up_projection": ("real_exp(-g))) * u;", "real_exp(-g)));"),
+    "transposed_w2": ("const uint16_t* a = w2 + (size_t)c * ffn;\n    for (int r = 0; r < ffn; ++r) s += (REAL)bf16_widen(a[r]) * h[r];",
+                      "for (int r = 0; r < ffn; ++r) s += (REAL)bf16_widen(w2[(size_t)r * d + c]) * h[r];"),
+    "drop_gate": ("acc[c] += g * y[c];", "acc[c] += y[c];"),
+    "drop_shared": ("for (int s = 0; s < n_shared; ++s) {\n      oracle_expert_ffn(x, sw1 + s * per, sw3 + s * per, sw2 + s * per, d, ffn, h, y);\n      for (int c = 0; c < d; ++c) acc[c] += y[c];\n    }\n    for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = (float)acc[c];\n  }\n  free(h);\n  free(y);\n  free(acc);\n  return rc;",
+                    "for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = (float)acc[c];\n  }\n  free(h);\n  free(y);\n  free(acc);\n  return rc;"),
+    "tie_to_higher_index": ("logit[e] > logit[best]", "logit[e] >= logit[best]"),
+    "argmin_instead_of_argmax": ("logit[e] > logit[best]", "logit[e] < logit[best]"),
+    "gates_not_normalised": ("(float)(p[i] / sum);", "(float)(p[i]);"),
+    "gates_wrong_sign": ("- l0);\n      sum += p[i];", "- l0);\n      p[i] = (REAL)1 / p[i];\n      sum += p[i];"),
+    "router_wrong_row": ("router_w[(size_t)e * d + j]", "router_w[(size_t)((e + 1) % E) * d + j]"),
+    "expert_offset_wrong": ("oracle_expert_ffn(x, w1 + e * per, w3 + e * per, w2 + e * per, d, ffn, h, y);\n      REAL g",
+                            "oracle_expert_ffn(x, w1 + e * per, w3 + e * per, w2, d, ffn, h, y);\n      REAL g"),
+    "union_skips_last_expert": ("for (int e = 0; e < E; ++e) {\n    int c = 0;", "for (int e = 0; e < E - 1; ++e) {\n    int c = 0;"),
+    "token_uses_row0": ("const float* x = hidden + (size_t)t * d;\n    for (int c = 0; c < d; ++c) acc[c] = 0;\n    for (int i = 0; i < top_k; ++i) {",
+                        "const float* x = hidden;\n    for (int c = 0; c < d; ++c) acc[c] = 0;\n    for (int i = 0; i < top_k; ++i) {"),
+}
+
+PIN_CALLS = [
+    lambda: pins.test_route_brute_force("f64", 8, 2),
+    lambda: pins.test_route_ties_go_to_lower_index_and_uniform_gates("f64"),
+    lambda: pins.test_route_topk_equals_E_is_permutation_and_row_permutation_equivariance("f64"),
+    lambda: pins.test_gates_closed_forms("f64"),
+    lambda: pins.test_union_structure_and_paper_example(),
+    lambda: pins.test_expert_ffn_closed_form_selection_matrices("f64"),
+    lambda: pins.test_top1_layer_is_three_library_gemvs("f64"),
+    lambda: pins.test_combine_closed_form_gate_weighting_and_shared("f64"),
+    lambda: pins.test_zero_w1_gives_zero_and_dense_masked_agrees("f64"),
+    lambda: pins.test_batch_invariance_and_token_permutation("f64"),
+]
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
+    old, new = MUTANTS[name]
+    src = open(os.path.join(os.path.dirname(orc.__file__), "moe_oracle.c")).read()
+    assert src.count(old) >= 1, f"mutation site for {name} not found"
+    mutated = src.replace(old, new, 1)
+    c = tmp_path / "mutant.c"
+    so = tmp_path / "mutant.so"
+    c.write_text(mutated)
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-DREAL=double",
+                    str(c), "-o", str(so), "-lm"], check=True)
+    mutant = orc._load(str(so), "f64")
+    orc._lib("f64")
+    monkeypatch.setitem(orc._LIBS, "f64", mutant)
+    caught = False
+    for call in PIN_CALLS:
+        try:
+            call()
+        except (AssertionError, ValueError):
+            caught = True
+            break
+    assert caught, f"no pin noticed the planted mistake '{name}'"
