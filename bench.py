@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE verification path on one MI355X.
+
+A "step" is one pass of the whole hot path (route -> group -> gate/up -> down -> combine, i.e. one
+moe_verify_layer call) over one batch of T = K+1 synthetic tokens on a Mixtral-8x7B-shaped layer.
+Step i uses K = i mod 9 (so every sweep K = 0..8 is timed equally often) and layer i mod L of L
+distinct resident layers, so consecutive steps never re-read weights that could still sit in the
+256 MB last-level cache.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line:  metric / value = unique-expert GB/s over the whole timed region (sum of
+unique-expert weight bytes / wall time), per-K latency and GB/s tables, the roofline object for the
+dominant kernel (gate/up projection, 2/3 of the bytes), and the CPU oracle timed beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=180)
+    ap.add_argument("--warmup", type=int, default=18)
+    ap.add_argument("--rho", type=float, default=0.5)
+    ap.add_argument("--layers", type=int, default=8, help="distinct resident layers rotated through")
+    ap.add_argument("--config", default="mixtral-8x7b-shaped")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fixed-k", type=int, default=-1, help="time a single K instead of cycling 0..8")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build is single-GPU (no sharding, no collectives); --gpus {args.gpus} is not supported",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_20675_amd import binding, synth
+
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    L, K_steps, W_steps = args.layers, args.steps, args.warmup
+    T_MAX = 9
+
+    # ---- resident inputs -------------------------------------------------------------------
+    layers_dev = [synth.layer_weights_device(cfg, l) for l in range(L)]
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX)
+    lw = [ctx.weights(w) for w in layers_dev]
+    total = W_steps + K_steps
+
+    def k_of(i):
+        return args.fixed_k if args.fixed_k >= 0 else i % T_MAX
+
+    hid = []
+    for i in range(total):
+        T = k_of(i) + 1
+        hid.append(torch.from_numpy(synth.hidden_host(cfg, i % L, i, T, args.rho)).cuda())
+    outs = [torch.empty((T_MAX, cfg.d), dtype=torch.float32, device="cuda") for _ in range(2)]
+    nu = torch.zeros((total,), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(i):
+        T = k_of(i) + 1
+        ctx.moe_verify_layer(lw[i % L], hid[i], outs[i & 1][:T], n_unique=nu[i:i + 1])
+
+    # ---- warm-up, then the timed region ------------------------------------------------------
+    for i in range(W_steps):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for j in range(K_steps):
+        step(W_steps + j)
+        ev[j + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    nu_h = nu.cpu().numpy()[W_steps:]
+    step_ms = np.array([ev[j].elapsed_time(ev[j + 1]) for j in range(K_steps)])
+    ks = np.array([k_of(W_steps + j) for j in range(K_steps)])
+    ubytes = (nu_h.astype(np.int64) + cfg.n_shared) * cfg.expert_bytes
+    value = ubytes.sum() / wall / 1e9
+    by_k = {}
+    for k in sorted(set(ks.tolist())):
+        m = ks == k
+        lat = np.median(step_ms[m]) * 1e3
+        gbs = np.median(ubytes[m] / (step_ms[m] * 1e-3)) / 1e9
+        by_k[str(k)] = {"latency_us": round(float(lat), 1), "p10_us": round(float(np.percentile(step_ms[m], 10) * 1e3), 1),
+                        "p90_us": round(float(np.percentile(step_ms[m], 90) * 1e3), 1),
+                        "mean_unique": round(float(nu_h[m].mean()), 2), "unique_GBps": round(float(gbs), 1),
+                        "frac_hbm_peak": round(float(gbs / HBM_PEAK_GBS), 4)}
+    k0 = by_k.get("0", {}).get("latency_us")
+    if k0:
+        for k in by_k:
+            by_k[k]["t_verify_over_t0"] = round(by_k[k]["latency_us"] / k0, 3)
+
+    # ---- roofline of the dominant kernel: same steps again with per-kernel events ------------
+    ctx.moe_ctx_profile(True)
+    for j in range(K_steps):
+        step(W_steps + j)
+    torch.cuda.synchronize()
+    kms, n_prof = ctx.moe_ctx_profile_read()
+    ctx.moe_ctx_profile(False)
+    gu_bytes_per_launch = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * 2 * cfg.d * cfg.ffn * 2
+    gu_ms = kms["gateup"] / max(n_prof, 1)
+    achieved = gu_bytes_per_launch / (gu_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_us": round(gu_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(gu_bytes_per_launch),
+                "kernel_us_per_step": {k: round(v / max(n_prof, 1) * 1e3, 2) for k, v in kms.items()}}
+    dn_bytes = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * cfg.d * cfg.ffn * 2
+    roofline["down_kernel_GBps"] = round(dn_bytes / (kms["down"] / max(n_prof, 1) * 1e-3) / 1e9, 1)
+
+    # ---- the box's plain read-stream rate, as a second denominator ---------------------------
+    sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    probe = [layers_dev[l][n] for l in range(min(L, 4)) for n in ("w1", "w3")]
+    for t in probe[:2]:
+        binding.moe_stream_read_probe(t, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in probe:
+        binding.moe_stream_read_probe(t, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbs = sum(t.numel() * 2 for t in probe) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # ---- CPU oracle beside it (bounded sample, single thread) ---------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as orc
+        Wh = synth.layer_weights_host(cfg, 0)
+        sample_T = (1, 5) if cfg is synth.MIXTRAL else (1, 9)
+        cbytes, csec = 0, 0.0
+        for T in sample_T:
+            x = synth.hidden_host(cfg, 0, 10_000 + T, T, args.rho)
+            c0 = time.perf_counter()
+            _, rids, _ = orc.layer(x, Wh, cfg.top_k, cfg.n_shared, "f32")
+            csec += time.perf_counter() - c0
+            cbytes += (orc.union(rids, cfg.n_experts)["n_unique"] + cfg.n_shared) * cfg.expert_bytes
+        cpu = {"value": round(cbytes / csec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"fp32 oracle, layer 0, rho={args.rho}, one layer-step each at T in {list(sample_T)}; "
+                         f"{csec:.1f} s of CPU time; host has {os.cpu_count()} logical cores",
+               "ms_per_step": round(csec / len(sample_T) * 1e3, 1)}
+
+    res = {
+        "metric": "unique-expert GB/s (MoE verify step, sum of unique-expert weight bytes / time); latency/layer vs K in by_K",
+        "value": round(float(value), 1), "unit": "GB/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": round(wall / K_steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} MoE layer d={cfg.d} E={cfg.n_experts} top{cfg.top_k} ffn={cfg.ffn} "
+                               f"shared={cfg.n_shared}, bf16 weights, T=K+1 with K "
+                               + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
+                               + f", rho={args.rho}, {L} rotating resident layers"},
+        "frac_hbm_peak": round(float(value / HBM_PEAK_GBS), 4),
+        "by_K": by_k, "roofline": roofline, "stream_read_GBps": round(stream_gbs, 1), "cpu_baseline": cpu,
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

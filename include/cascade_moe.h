@@ -1,0 +1,196 @@
+/* cascade_moe.h — C ABI of the MI355X (gfx950) MoE verification path and of the host-side
+ * utility-driven choice of the speculation length K.
+ *
+ * What the device calls compute (paper: Section 1, Section 2.1, Section 2.2, Section 2.4):
+ * one decode iteration of speculative decoding pushes T = K+1 tokens (one accepted, K drafted)
+ * through every MoE layer; each token independently selects top_k of E experts, the layer has to
+ * fetch the UNION of the selected experts, and the cost of the step is the HBM traffic for those
+ * unique experts' weights.  Each call below is one step of that path.  The operator itself is the
+ * usual one: bias-free linear router, top-k on the logits, gates = softmax over the selected
+ * logits, expert = w2 . (silu(w1 x) * (w3 x)), optional always-on shared experts with gate 1.
+ *
+ * What the host calls compute (paper: Section 4, Definition of speculation utility, Eq. 3 and
+ * Theorem 1; Section 5.3 test-and-set; 5.4 disabling speculation; 5.5 adaptive back-off; 5.6
+ * hill-climbing search; Section 6 hyper-parameters).
+ *
+ * Conventions
+ *  - C11, no C++ types, no exceptions; every call returns a moe_status (or a plain value).
+ *  - "DEVICE" pointers are HIP device pointers owned by the caller; "HOST" pointers are ordinary
+ *    host memory.  bf16 tensors are passed as uint16_t bit patterns, row-major, dense.
+ *  - Device calls only ENQUEUE work on `stream` (a hipStream_t passed as void*, NULL = the default
+ *    stream).  They never synchronise, never copy to the host and never allocate; outputs are
+ *    valid once the caller has synchronised the stream.  Argument validation is synchronous.
+ *  - A moe_ctx owns the device workspace for one layer geometry.  It is not thread-safe: use one
+ *    ctx per stream, and do not overlap calls on the same ctx from different streams.
+ *  - The library never falls back to the CPU: without a usable GPU every device call fails with
+ *    MOE_ERR_HIP.
+ */
+#ifndef CASCADE_MOE_H
+#define CASCADE_MOE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1,       /* NULL required pointer, T out of range, bad enum, ...        */
+  MOE_ERR_UNSUPPORTED_SHAPE = -2, /* geometry outside what the kernels are built for             */
+  MOE_ERR_WORKSPACE = -3,         /* device workspace could not be allocated                     */
+  MOE_ERR_HIP = -4,               /* a HIP runtime call or kernel launch failed                  */
+  MOE_ERR_UNIMPLEMENTED = -5
+} moe_status;
+
+/* Static description of a status code; never freed. */
+const char* moe_strerror(moe_status s);
+int moe_abi_version(void);
+
+/* Geometry of one MoE layer (paper: Table 1 lists the shapes the method was evaluated on).
+ * Supported: d % 32 == 0, ffn % 32 == 0, 1 <= top_k <= min(n_experts, 16), n_experts <= 256,
+ * 0 <= n_shared <= 8, 1 <= max_tokens <= 16 (T = K+1 tokens in flight, K <= 15). */
+typedef struct {
+  int32_t d;          /* hidden size                                   */
+  int32_t ffn;        /* expert intermediate size                      */
+  int32_t n_experts;  /* E, routed experts                             */
+  int32_t top_k;      /* experts selected per token                    */
+  int32_t n_shared;   /* always-on shared experts (same ffn), may be 0 */
+  int32_t max_tokens; /* largest T that will be passed                 */
+} moe_shape;
+
+typedef struct moe_ctx moe_ctx; /* opaque: shape + device workspace */
+
+/* Create / destroy a context on the CURRENT HIP device.  The only calls that allocate or free
+ * device memory.  *out is set to NULL on failure. */
+moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out);
+moe_status moe_ctx_destroy(moe_ctx* ctx);
+/* Bytes of device workspace held by the context. */
+int64_t moe_ctx_workspace_bytes(const moe_ctx* ctx);
+
+/* Step 1 — router logits, top-k, gates, and the union of activated experts (Section 2.1: a small
+ * gating network selects a few experts per token; Section 1 / 2.2: the in-flight tokens together
+ * activate a larger set of experts).
+ *   logit[t,e] = sum_j hidden[t,j] * router_w[e,j], accumulated in fp64 (products are exact there)
+ *   ids[t,0..top_k)   the top_k largest logits of token t in descending order; equal -> lower e
+ *   gates[t,i]        softmax over the selected logits (fp32), sums to 1 per token
+ *   unique_experts[E] ascending distinct ids in the first *n_unique entries, -1 after them
+ * hidden [T,d] fp32, router_w [E,d] bf16: DEVICE, read-only.  ids [T,top_k] int32, gates
+ * [T,top_k] fp32, unique_experts [E] int32, n_unique [1] int32: DEVICE outputs; any of the four
+ * may be NULL if not wanted.  1 <= T <= shape.max_tokens. */
+moe_status moe_route(moe_ctx* ctx, const float* hidden, const uint16_t* router_w, int32_t T,
+                     int32_t* ids, float* gates, int32_t* unique_experts, int32_t* n_unique, void* stream);
+
+/* Step 2 — per-expert token lists for a given routing (Section 2.2 / 2.4: the set of unique
+ * experts is what must be fetched; tokens are grouped so each unique expert is visited once).
+ *   expert_count[e]   number of (token, slot) pairs routed to e
+ *   expert_offset[e]  exclusive prefix sum of expert_count, expert_offset[E] = T*top_k
+ *   assign[..]        flat pair indices a = t*top_k + i grouped by expert (ascending e), ascending
+ *                     a inside each group
+ * ids [T,top_k]: DEVICE input, every id in [0,E).  unique_experts [E], n_unique [1], expert_count
+ * [E], expert_offset [E+1], assign [T*top_k]: DEVICE int32 outputs, each may be NULL. */
+moe_status moe_group(moe_ctx* ctx, const int32_t* ids, int32_t T, int32_t* unique_experts, int32_t* n_unique,
+                     int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream);
+
+/* One layer's weights: DEVICE pointers, caller-owned, bf16 row-major, alive until the stream drains.
+ * sw1/sw3/sw2 are required iff shape.n_shared > 0. */
+typedef struct {
+  const uint16_t* router_w; /* [E, d]              */
+  const uint16_t* w1;       /* [E, ffn, d]  gate   */
+  const uint16_t* w3;       /* [E, ffn, d]  up     */
+  const uint16_t* w2;       /* [E, d, ffn]  down   */
+  const uint16_t* sw1;      /* [n_shared, ffn, d]  */
+  const uint16_t* sw3;      /* [n_shared, ffn, d]  */
+  const uint16_t* sw2;      /* [n_shared, d, ffn]  */
+} moe_layer_weights;
+
+/* Steps 1-5 — the whole verification step of one MoE layer (Section 2.2: the target model
+ * verifies all K+1 tokens in one step; Section 2.4: expert-layer latency follows the number of
+ * unique experts).  Route, group, then for every UNIQUE expert stream w1/w3/w2 from HBM once and
+ * apply it to the tokens routed to it, and combine:
+ *   out[t] = sum_i gates[t,i] * FFN_{ids[t,i]}(hidden[t])  +  sum_s FFN_shared_s(hidden[t])
+ * with fp32 accumulation.  Row t of `out` equals what a T = 1 call on hidden[t] alone gives
+ * (verification is iso-accuracy) up to fp32 summation order.
+ * hidden [T,d] fp32 DEVICE in; out [T,d] fp32 DEVICE out.  ids_opt [T,top_k], gates_opt
+ * [T,top_k], unique_opt [E], n_unique_opt [1]: optional DEVICE outputs (NULL = not wanted). */
+moe_status moe_verify_layer(moe_ctx* ctx, const moe_layer_weights* w, const float* hidden, int32_t T, float* out,
+                            int32_t* ids_opt, float* gates_opt, int32_t* unique_opt, int32_t* n_unique_opt,
+                            void* stream);
+
+/* L layers back to back on one stream without host synchronisation: layer l reads hidden[l] and
+ * writes out[l] (independent per-layer inputs; the method's cost model needs no chaining).
+ * layers: HOST array of L structs (copied during the call).  hidden, out: DEVICE [L,T,d].
+ * n_unique_per_layer_opt: DEVICE [L] int32 or NULL. */
+moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32_t L, const float* hidden,
+                            int32_t T, float* out, int32_t* n_unique_per_layer_opt, void* stream);
+
+/* Measurement aid: per-kernel timing.  While enabled, every moe_verify_layer / moe_verify_stack
+ * layer records HIP events on its stream around each of its five kernels (route, group, gate-up,
+ * down, combine); this adds event packets between the kernels, so whole-step latency is measured
+ * with profiling OFF.  moe_ctx_profile_read waits for the recorded events, adds the elapsed times
+ * into ms_sum[0..4] (HOST, milliseconds, same kernel order), stores the number of layer-steps in
+ * *steps (HOST) and forgets the events.  Both calls may allocate/free event objects. */
+moe_status moe_ctx_profile(moe_ctx* ctx, int32_t enable);
+moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);
+
+/* Measurement aid: sum `bytes` (multiple of 16) of DEVICE memory at `src` with plain coalesced
+ * 128-bit loads and write one fp32 per workgroup to `sink` (DEVICE, >= 4096 floats).  Used only
+ * to report the box's achievable read-stream bandwidth next to the published HBM peak. */
+moe_status moe_stream_read_probe(const void* src, int64_t bytes, float* sink, void* stream);
+
+/* ----------------------------------------------------------------------------------------
+ * Host side — pure C, no device.
+ * -------------------------------------------------------------------------------------- */
+
+/* Speculation utility (Section 4, Definition and Eq. 3): benefit / cost with benefit = tokens
+ * emitted per iteration (ETR, counts the always-emitted token, so 1 without speculation) and
+ * cost = t_verify / t_base.  By Theorem 1, time per output token = t_base / utility.
+ * Returns NaN if t_verify <= 0 or t_base <= 0 (or either is NaN). */
+double cascade_utility(double tokens_per_iter, double t_verify, double t_base);
+
+/* Hyper-parameters of the test-and-set policy (Section 5.3 and Section 6: t = 4, up to M = 4
+ * trials, S = 16; Section 7.4: K_start = 3; Section 5.3: baseline from the first 4 iterations,
+ * refreshed about every 100).  cascade_default_params fills the paper's values. */
+typedef struct {
+  int32_t t_trial;      /* iterations per trial                                  (4)   */
+  int32_t max_trials;   /* M, trials per test phase                              (4)   */
+  int32_t s_set;        /* S, set-phase length                                   (16)  */
+  int32_t k_max;        /* largest K ever proposed                               (8)   */
+  int32_t k_start;      /* K of a request's first trial                          (3)   */
+  int32_t base_iters;   /* no-speculation iterations that measure t_base         (4)   */
+  int32_t base_refresh; /* re-measure t_base after about this many iterations    (100) */
+  int32_t s_max;        /* cap on the backed-off set length, 0 = uncapped        (0)   */
+  double converge_frac; /* early exit when successive utilities differ by less   (0.10)*/
+  int32_t backoff;      /* 1 = adaptive back-off (Section 5.5) on                (1)   */
+  int32_t hillclimb;    /* 1 = hill-climbing search (Section 5.6) on             (1)   */
+} cascade_params;
+void cascade_default_params(cascade_params* p);
+
+typedef struct cascade_ctrl cascade_ctrl; /* per-request controller state, HOST */
+cascade_ctrl* cascade_ctrl_create(const cascade_params* p); /* NULL on bad parameters; p == NULL -> defaults */
+void cascade_ctrl_destroy(cascade_ctrl* c);
+
+/* K to use for the coming iteration, 0 (speculation off) .. k_max.  Does not change state. */
+int32_t cascade_next_k(const cascade_ctrl* c);
+/* Report one finished iteration: the K that was used (must equal cascade_next_k), the tokens it
+ * emitted (1 .. k_used+1, Section 2.2) and its duration (> 0, any unit, consistent across calls).
+ * MOE_ERR_INVALID_ARG leaves the state unchanged. */
+moe_status cascade_observe(cascade_ctrl* c, int32_t k_used, int32_t tokens_emitted, double t_iter);
+
+/* Read-only view of the controller for logging. */
+typedef struct {
+  int32_t phase;         /* 0 baseline measurement, 1 test, 2 set */
+  int32_t cur_k;         /* same as cascade_next_k                */
+  int32_t s_cur;         /* current (backed-off) set-phase length */
+  int32_t trials_done;   /* trials finished in the current test phase */
+  int64_t iters;         /* iterations observed so far            */
+  int64_t trial_iters;   /* of which inside test phases           */
+  double t_base;         /* current no-speculation iteration time (NaN before it is known) */
+  double last_utility;   /* utility of the last finished trial or speculative set phase (NaN if none) */
+} cascade_state;
+void cascade_get_state(const cascade_ctrl* c, cascade_state* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASCADE_MOE_H */

@@ -121,7 +121,7 @@ class Controller:
         return 0 if self.phase == BASELINE else self.cur_k
 
     def observe(self, k_used: int, tokens: int, t_iter: float) -> None:
-        if k_used != self.next_k() or not (1 <= tokens <= k_used + 1) or not (t_iter > 0.0):
+        if k_used != self.next_k() or not (1 <= tokens <= k_used + 1) or not (t_iter > 0.0) or math.isinf(t_iter):
             raise ValueError("bad observation")
         self.iters += 1
         if self.phase == BASELINE:

@@ -1,0 +1,314 @@
+"""Thin ctypes binding of libcascade_moe.so (declared in include/cascade_moe.h).
+
+Argument marshalling only: every step of the MoE verification path runs in the HIP
+kernels of the library, and the policy (utility, test-and-set loop) in its C code.
+torch is used for device memory and streams.  There is no fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_double, c_float, c_int32, c_int64, c_uint16, c_void_p
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcascade_moe.so")
+
+MOE_OK = 0
+STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAPE", -3: "MOE_ERR_WORKSPACE",
+                -4: "MOE_ERR_HIP", -5: "MOE_ERR_UNIMPLEMENTED"}
+
+EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
+           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_stream_read_probe",
+           "moe_ctx_profile", "moe_ctx_profile_read",
+           "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
+           "cascade_next_k", "cascade_observe", "cascade_get_state")
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {STATUS_NAMES.get(status, status)} ({_strerror(status)})")
+
+
+class MoeShape(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("d", "ffn", "n_experts", "top_k", "n_shared", "max_tokens")]
+
+
+class MoeLayerWeights(ctypes.Structure):
+    _fields_ = [(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")]
+
+
+class CascadeParams(ctypes.Structure):
+    _fields_ = [("t_trial", c_int32), ("max_trials", c_int32), ("s_set", c_int32), ("k_max", c_int32),
+                ("k_start", c_int32), ("base_iters", c_int32), ("base_refresh", c_int32), ("s_max", c_int32),
+                ("converge_frac", c_double), ("backoff", c_int32), ("hillclimb", c_int32)]
+
+
+class CascadeState(ctypes.Structure):
+    _fields_ = [("phase", c_int32), ("cur_k", c_int32), ("s_cur", c_int32), ("trials_done", c_int32),
+                ("iters", c_int64), ("trial_iters", c_int64), ("t_base", c_double), ("last_utility", c_double)]
+
+
+_LIB = None
+
+
+def lib():
+    """dlopen the library once and declare every signature."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built. Run: python -c 'import __graft_entry__ as g; g.build()'")
+    L = ctypes.CDLL(LIB_PATH)
+    L.moe_strerror.restype = ctypes.c_char_p
+    L.moe_strerror.argtypes = [ctypes.c_int]
+    L.moe_abi_version.restype = ctypes.c_int
+    L.moe_ctx_create.restype = ctypes.c_int
+    L.moe_ctx_create.argtypes = [POINTER(MoeShape), POINTER(c_void_p)]
+    L.moe_ctx_destroy.restype = ctypes.c_int
+    L.moe_ctx_destroy.argtypes = [c_void_p]
+    L.moe_ctx_workspace_bytes.restype = c_int64
+    L.moe_ctx_workspace_bytes.argtypes = [c_void_p]
+    L.moe_route.restype = ctypes.c_int
+    L.moe_route.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_group.restype = ctypes.c_int
+    L.moe_group.argtypes = [c_void_p, c_void_p, c_int32] + [c_void_p] * 6
+    L.moe_verify_layer.restype = ctypes.c_int
+    L.moe_verify_layer.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_void_p, c_int32, c_void_p,
+                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_verify_stack.restype = ctypes.c_int
+    L.moe_verify_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_int32, c_void_p, c_int32, c_void_p,
+                                   c_void_p, c_void_p]
+    L.moe_ctx_profile.restype = ctypes.c_int
+    L.moe_ctx_profile.argtypes = [c_void_p, c_int32]
+    L.moe_ctx_profile_read.restype = ctypes.c_int
+    L.moe_ctx_profile_read.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
+    L.moe_stream_read_probe.restype = ctypes.c_int
+    L.moe_stream_read_probe.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
+    L.cascade_utility.restype = c_double
+    L.cascade_utility.argtypes = [c_double, c_double, c_double]
+    L.cascade_default_params.restype = None
+    L.cascade_default_params.argtypes = [POINTER(CascadeParams)]
+    L.cascade_ctrl_create.restype = c_void_p
+    L.cascade_ctrl_create.argtypes = [POINTER(CascadeParams)]
+    L.cascade_ctrl_destroy.restype = None
+    L.cascade_ctrl_destroy.argtypes = [c_void_p]
+    L.cascade_next_k.restype = c_int32
+    L.cascade_next_k.argtypes = [c_void_p]
+    L.cascade_observe.restype = ctypes.c_int
+    L.cascade_observe.argtypes = [c_void_p, c_int32, c_int32, c_double]
+    L.cascade_get_state.restype = None
+    L.cascade_get_state.argtypes = [c_void_p, POINTER(CascadeState)]
+    _LIB = L
+    return L
+
+
+def _strerror(status: int) -> str:
+    try:
+        return lib().moe_strerror(status).decode()
+    except Exception:
+        return "?"
+
+
+def _check(status: int, what: str):
+    if status != MOE_OK:
+        raise MoeError(status, what)
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return c_void_p(stream.cuda_stream)
+
+
+def _want(t, dtype, shape, name):
+    import torch
+    if t is None:
+        return
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype
+            and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: expected contiguous CUDA tensor {dtype} {tuple(shape)}, got "
+                         f"{getattr(t, 'dtype', None)} {tuple(getattr(t, 'shape', ()))}")
+
+
+def _want_bf16(t, shape, name):
+    import torch
+    if t is None:
+        return
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.element_size() == 2
+            and t.dtype in (torch.int16, torch.uint16, torch.bfloat16) and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name}: expected contiguous CUDA 16-bit tensor {tuple(shape)}")
+
+
+class LayerWeights:
+    """Device pointers of one layer's bf16 weights (tensors stay owned by the caller)."""
+
+    def __init__(self, shape: "MoeShape", router_w, w1, w3, w2, sw1=None, sw3=None, sw2=None):
+        E, d, f, ns = shape.n_experts, shape.d, shape.ffn, shape.n_shared
+        _want_bf16(router_w, (E, d), "router_w")
+        _want_bf16(w1, (E, f, d), "w1")
+        _want_bf16(w3, (E, f, d), "w3")
+        _want_bf16(w2, (E, d, f), "w2")
+        if ns:
+            _want_bf16(sw1, (ns, f, d), "sw1")
+            _want_bf16(sw3, (ns, f, d), "sw3")
+            _want_bf16(sw2, (ns, d, f), "sw2")
+            if sw1 is None or sw3 is None or sw2 is None:
+                raise ValueError("shared expert weights required")
+        self.tensors = (router_w, w1, w3, w2, sw1, sw3, sw2)
+        self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors])
+
+
+class MoeContext:
+    """Owns a moe_ctx (device workspace for one layer geometry on the current device)."""
+
+    def __init__(self, d, ffn, n_experts, top_k, n_shared=0, max_tokens=9):
+        self.shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens)
+        self._h = c_void_p()
+        _check(lib().moe_ctx_create(byref(self.shape), byref(self._h)), "moe_ctx_create")
+
+    def close(self):
+        if self._h:
+            lib().moe_ctx_destroy(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().moe_ctx_workspace_bytes(self._h))
+
+    def weights(self, W: dict) -> LayerWeights:
+        return LayerWeights(self.shape, W["router_w"], W["w1"], W["w3"], W["w2"], W.get("sw1"), W.get("sw3"),
+                            W.get("sw2"))
+
+    KERNELS = ("route", "group", "gateup", "down", "combine")
+
+    def moe_ctx_profile(self, enable: bool) -> None:
+        _check(lib().moe_ctx_profile(self._h, 1 if enable else 0), "moe_ctx_profile")
+
+    def moe_ctx_profile_read(self):
+        """-> ({kernel: summed ms}, number of layer-steps) since profiling was enabled / last read."""
+        ms = (c_double * 5)()
+        n = c_int64()
+        _check(lib().moe_ctx_profile_read(self._h, ms, byref(n)), "moe_ctx_profile_read")
+        return dict(zip(self.KERNELS, [float(v) for v in ms])), int(n.value)
+
+    # ---- device calls (same names as the C ABI) -------------------------------------------
+    def moe_route(self, hidden, router_w, ids=None, gates=None, unique_experts=None, n_unique=None, stream=None):
+        import torch
+        s = self.shape
+        T = hidden.shape[0]
+        _want(hidden, torch.float32, (T, s.d), "hidden")
+        _want_bf16(router_w, (s.n_experts, s.d), "router_w")
+        _want(ids, torch.int32, (T, s.top_k), "ids")
+        _want(gates, torch.float32, (T, s.top_k), "gates")
+        _want(unique_experts, torch.int32, (s.n_experts,), "unique_experts")
+        _want(n_unique, torch.int32, (1,), "n_unique")
+        _check(lib().moe_route(self._h, _ptr(hidden), _ptr(router_w), T, _ptr(ids), _ptr(gates), _ptr(unique_experts),
+                               _ptr(n_unique), _stream_ptr(stream)), "moe_route")
+
+    def moe_group(self, ids, unique_experts=None, n_unique=None, expert_count=None, expert_offset=None, assign=None,
+                  stream=None):
+        import torch
+        s = self.shape
+        T = ids.shape[0]
+        _want(ids, torch.int32, (T, s.top_k), "ids")
+        _want(unique_experts, torch.int32, (s.n_experts,), "unique_experts")
+        _want(n_unique, torch.int32, (1,), "n_unique")
+        _want(expert_count, torch.int32, (s.n_experts,), "expert_count")
+        _want(expert_offset, torch.int32, (s.n_experts + 1,), "expert_offset")
+        _want(assign, torch.int32, (T * s.top_k,), "assign")
+        _check(lib().moe_group(self._h, _ptr(ids), T, _ptr(unique_experts), _ptr(n_unique), _ptr(expert_count),
+                               _ptr(expert_offset), _ptr(assign), _stream_ptr(stream)), "moe_group")
+
+    def moe_verify_layer(self, weights: LayerWeights, hidden, out, ids=None, gates=None, unique_experts=None,
+                         n_unique=None, stream=None):
+        import torch
+        s = self.shape
+        T = hidden.shape[0]
+        _want(hidden, torch.float32, (T, s.d), "hidden")
+        _want(out, torch.float32, (T, s.d), "out")
+        _want(ids, torch.int32, (T, s.top_k), "ids")
+        _want(gates, torch.float32, (T, s.top_k), "gates")
+        _want(unique_experts, torch.int32, (s.n_experts,), "unique_experts")
+        _want(n_unique, torch.int32, (1,), "n_unique")
+        _check(lib().moe_verify_layer(self._h, byref(weights.c), _ptr(hidden), T, _ptr(out), _ptr(ids), _ptr(gates),
+                                      _ptr(unique_experts), _ptr(n_unique), _stream_ptr(stream)), "moe_verify_layer")
+
+    def moe_verify_stack(self, layers, hidden, out, n_unique_per_layer=None, stream=None):
+        import torch
+        s = self.shape
+        L, T = hidden.shape[0], hidden.shape[1]
+        if L != len(layers):
+            raise ValueError("hidden.shape[0] must equal the number of layers")
+        _want(hidden, torch.float32, (L, T, s.d), "hidden")
+        _want(out, torch.float32, (L, T, s.d), "out")
+        _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
+        arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
+        _check(lib().moe_verify_stack(self._h, arr, L, _ptr(hidden), T, _ptr(out), _ptr(n_unique_per_layer),
+                                      _stream_ptr(stream)), "moe_verify_stack")
+
+
+def moe_stream_read_probe(src, sink, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().moe_stream_read_probe(_ptr(src), nbytes - nbytes % 16, _ptr(sink), _stream_ptr(stream)),
+           "moe_stream_read_probe")
+
+
+# ---- host side ---------------------------------------------------------------------------------
+def cascade_utility(tokens_per_iter: float, t_verify: float, t_base: float) -> float:
+    return float(lib().cascade_utility(tokens_per_iter, t_verify, t_base))
+
+
+def cascade_default_params() -> CascadeParams:
+    p = CascadeParams()
+    lib().cascade_default_params(byref(p))
+    return p
+
+
+class CascadeController:
+    """Per-request controller: K = next_k(); run the iteration; observe(K, tokens, time)."""
+
+    def __init__(self, params: CascadeParams | None = None, **overrides):
+        p = params or cascade_default_params()
+        for k, v in overrides.items():
+            if not hasattr(p, k):
+                raise AttributeError(k)
+            setattr(p, k, v)
+        self.params = p
+        self._h = lib().cascade_ctrl_create(byref(p))
+        if not self._h:
+            raise ValueError("cascade_ctrl_create: bad parameters")
+
+    def close(self):
+        if self._h:
+            lib().cascade_ctrl_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def next_k(self) -> int:
+        return int(lib().cascade_next_k(self._h))
+
+    def observe(self, k_used: int, tokens_emitted: int, t_iter: float) -> None:
+        _check(lib().cascade_observe(self._h, k_used, tokens_emitted, t_iter), "cascade_observe")
+
+    def state(self) -> CascadeState:
+        st = CascadeState()
+        lib().cascade_get_state(self._h, byref(st))
+        return st

@@ -1,0 +1,43 @@
+"""Builds the shared libraries in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(ROOT, "include")
+LIB = os.path.join(HERE, "libcascade_moe.so")
+SYNTH_LIB = os.path.join(HERE, "libmoe_synth.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# packed-fp32 VALU forms are switched off on purpose (scalar fp32 code only)
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
+             "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("build failed: " + " ".join(cmd) + "\n" + r.stdout + r.stderr)
+    return r
+
+
+def build_all(verbose: bool = False) -> None:
+    obj_k = os.path.join(HERE, "moe_kernels.o")
+    obj_c = os.path.join(HERE, "cascade_ctrl.o")
+    _run([HIPCC] + HIP_FLAGS + ["-I", INCLUDE, "-c", os.path.join(CSRC, "moe_kernels.hip"), "-o", obj_k])
+    # host policy code: plain C++ with contraction off so decisions replay identically everywhere
+    _run(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-I", INCLUDE, "-c",
+          os.path.join(CSRC, "cascade_ctrl.cpp"), "-o", obj_c])
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", obj_k, obj_c, "-o", LIB])
+    _run([HIPCC] + HIP_FLAGS + ["-shared", os.path.join(CSRC, "synth_fill.hip"), "-o", SYNTH_LIB])
+    for o in (obj_k, obj_c):
+        os.remove(o)
+    if verbose:
+        print("built", LIB, SYNTH_LIB)
+
+
+if __name__ == "__main__":
+    build_all(verbose=True)

@@ -8,9 +8,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <thread>
+#include <vector>
+
 namespace {
 
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
   return z ^ (z >> 31);
@@ -52,4 +55,31 @@ extern "C" int synth_fill_bf16(void* dst, uint64_t key, uint64_t start, uint64_t
   hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                      static_cast<uint16_t*>(dst), key, start / 4, n_full, tail, static_cast<const uint16_t*>(table));
   return (int)hipGetLastError();
+}
+
+// Host twin (same integers, plain loops split over a few threads) for building oracle inputs quickly.
+// dst, table: HOST pointers; start % 4 == 0.  Returns 0, or -1 on bad arguments.
+extern "C" int synth_fill_bf16_host(uint16_t* dst, uint64_t key, uint64_t start, uint64_t count,
+                                    const uint16_t* table, int n_threads) {
+  if (!dst || !table || (start & 3)) return -1;
+  const uint64_t first_block = start / 4, n_blocks = (count + 3) / 4;
+  if (n_threads < 1) n_threads = 1;
+  if (n_threads > 64) n_threads = 64;
+  auto work = [=](uint64_t b0, uint64_t b1) {
+    for (uint64_t b = b0; b < b1; ++b) {
+      const uint64_t h = mix64(key + (first_block + b + 1) * 0x9E3779B97F4A7C15ull);
+      for (uint64_t j = 0; j < 4; ++j) {
+        const uint64_t i = 4 * b + j;
+        if (i < count) dst[i] = table[(h >> (16 * j)) & 0xFFFF];
+      }
+    }
+  };
+  std::vector<std::thread> pool;
+  const uint64_t per = (n_blocks + n_threads - 1) / n_threads;
+  for (int t = 0; t < n_threads; ++t) {
+    const uint64_t b0 = (uint64_t)t * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
+    if (b0 < b1) pool.emplace_back(work, b0, b1);
+  }
+  for (auto& th : pool) th.join();
+  return 0;
 }

@@ -144,12 +144,24 @@ def normal_table_bf16(sigma: float) -> np.ndarray:
     return f32_to_bf16_bits((sigma * z).astype(np.float32))
 
 
-def normal_bf16(key: int, sigma: float, count: int, start: int = 0) -> np.ndarray:
+def normal_bf16(key: int, sigma: float, count: int, start: int = 0, force_numpy: bool = False) -> np.ndarray:
     """`count` bf16 values (uint16 bits) of stream `key`, elements start .. start+count-1.
 
-    Element i uses 16-bit field (i % 4) of the hash of counter i // 4.
+    Element i uses 16-bit field (i % 4) of the hash of counter i // 4.  Large requests go through
+    the threaded C twin of this loop when the generator library is built (same integers; a test
+    checks the two against each other); the numpy code below is the definition.
     """
     table = normal_table_bf16(sigma)
+    if not force_numpy and count >= (1 << 16) and os.path.exists(synth_lib_path()):
+        lib = _load_synth_lib()
+        lo = start % 4
+        buf = np.empty(count + lo, dtype=np.uint16)
+        rc = lib.synth_fill_bf16_host(buf.ctypes.data_as(ctypes.c_void_p), ctypes.c_uint64(key),
+                                      ctypes.c_uint64(start - lo), ctypes.c_uint64(count + lo),
+                                      table.ctypes.data_as(ctypes.c_void_p), min(16, os.cpu_count() or 1))
+        if rc != 0:
+            raise RuntimeError("synth_fill_bf16_host failed")
+        return buf[lo:]
     b0 = start // 4
     b1 = (start + count + 3) // 4
     out = np.empty((b1 - b0) * 4, dtype=np.uint16)
@@ -262,6 +274,9 @@ def _load_synth_lib():
         lib.synth_fill_bf16.restype = ctypes.c_int
         lib.synth_fill_bf16.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                         ctypes.c_void_p, ctypes.c_void_p]
+        lib.synth_fill_bf16_host.restype = ctypes.c_int
+        lib.synth_fill_bf16_host.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
+                                             ctypes.c_void_p, ctypes.c_int]
         _SYNTH_LIB = lib
     return _SYNTH_LIB
 

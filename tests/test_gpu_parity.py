@@ -1,0 +1,275 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars (written here, derived in the design doc):
+  * expert ids, unique-expert lists/counts, token grouping: bit-exact;
+  * gates: |err| <= 1e-5;
+  * out: the benchmark's bar  max|err| <= 2e-2 and relative RMS <= 1e-2  against the plain fp32
+    oracle, AND the tighter bar this implementation is built to (fp32 accumulation, activations
+    carried as bf16 hi+lo pairs): relative RMS <= 5e-5 and max|err| <= 1e-4 * max|ref| against the
+    fp64 oracle.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import moe_oracle as orc
+from paper_2506_20675_amd import binding, synth
+
+
+def _dev(a):
+    import torch
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _weights_dev(W):
+    return {k: _dev(v) for k, v in W.items()}
+
+
+def _run_layer(ctx, Wd, x, want_routing=True):
+    import torch
+    s = ctx.shape
+    T = x.shape[0]
+    hid = _dev(x)
+    out = torch.full((T, s.d), float("nan"), dtype=torch.float32, device="cuda")
+    ids = torch.full((T, s.top_k), -7, dtype=torch.int32, device="cuda")
+    gates = torch.zeros((T, s.top_k), dtype=torch.float32, device="cuda")
+    uniq = torch.full((s.n_experts,), -7, dtype=torch.int32, device="cuda")
+    nu = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    ctx.moe_verify_layer(ctx.weights(Wd), hid, out, ids, gates, uniq, nu)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), ids.cpu().numpy(), gates.cpu().numpy(), uniq.cpu().numpy(), int(nu.item())
+
+
+def _check_out(out, ref32, ref64):
+    assert np.isfinite(out).all()
+    err32 = out.astype(np.float64) - ref32
+    assert np.abs(err32).max() <= 2e-2
+    assert np.sqrt((err32 ** 2).sum() / (ref32.astype(np.float64) ** 2).sum()) <= 1e-2
+    err64 = out.astype(np.float64) - ref64
+    rel = np.sqrt((err64 ** 2).sum() / (ref64.astype(np.float64) ** 2).sum())
+    assert rel <= 5e-5, rel
+    assert np.abs(err64).max() <= 1e-4 * np.abs(ref64).max()
+    return rel
+
+
+def _check_layer(cfg_like, W, x, ctx=None, Wd=None):
+    d, ffn, E, k, ns = cfg_like
+    own = ctx is None
+    if own:
+        ctx = binding.MoeContext(d, ffn, E, k, ns, max_tokens=max(9, x.shape[0]))
+        Wd = _weights_dev(W)
+    out, ids, gates, uniq, nu = _run_layer(ctx, Wd, x)
+    ref32, rids, rgates = orc.layer(x, W, k, ns, "f32")
+    ref64, rids64, _ = orc.layer(x, W, k, ns, "f64")
+    # margin between the k-th and (k+1)-th logit: routing is decided in fp64 on both sides, so
+    # only margins at the 1e-12 level could legitimately differ
+    _, _, logits = orc.route(x, W["router_w"], k, "f64")
+    srt = np.sort(logits, axis=1)[:, ::-1]
+    if E > k:
+        assert (srt[:, k - 1] - srt[:, k]).min() > 1e-9, "seed produces a routing near-tie; pick another"
+    np.testing.assert_array_equal(ids, rids)
+    np.testing.assert_array_equal(rids, rids64)
+    assert np.abs(gates - rgates).max() <= 1e-5
+    u = orc.union(rids, E)
+    assert nu == u["n_unique"]
+    np.testing.assert_array_equal(uniq, u["unique"])
+    rel = _check_out(out, ref32, ref64)
+    if own:
+        ctx.close()
+    return out, rel
+
+
+# ------------------------------------------------------------------------------------------
+def test_device_weight_fill_is_bit_identical_to_host():
+    import torch
+    key = synth.stream_key(2, 5, synth.T_W1)
+    for n, start in ((4096, 0), (1000, 4), (7, 0), (3, 8), (1 << 20, 1 << 22), (65537 * 4 + 2, 12)):
+        t = torch.zeros(n, dtype=torch.int16, device="cuda")
+        synth.fill_normal_bf16_device(t, key, 0.02, start)
+        torch.cuda.synchronize()
+        host = synth.normal_bf16(key, 0.02, n, start)
+        assert (t.cpu().numpy().view(np.uint16) == host).all(), (n, start)
+    Wd = synth.layer_weights_device(synth.TINY, 3)
+    Wh = synth.layer_weights_host(synth.TINY, 3)
+    torch.cuda.synchronize()
+    for name in Wh:
+        assert (Wd[name].cpu().numpy().view(np.uint16) == Wh[name]).all(), name
+
+
+@pytest.mark.parametrize("cfg", [synth.TINY, synth.OLMOE, synth.DEEPSEEK, synth.MIXTRAL], ids=lambda c: c.name)
+def test_route_parity(cfg):
+    import torch
+    W = synth.layer_weights_host(cfg, 0) if cfg is not synth.MIXTRAL else None
+    if W is None:      # router only: no need to build 2.8 GB of expert weights
+        rw = synth.normal_bf16(synth.weight_key(cfg, 0, synth.T_ROUTER), synth.SIGMA_ROUTER,
+                               cfg.n_experts * cfg.d).reshape(cfg.n_experts, cfg.d)
+    else:
+        rw = W["router_w"]
+    rwd = _dev(rw)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 9)
+    for it, (T, rho) in enumerate(((1, 0.5), (2, 0.0), (5, 0.9), (9, 0.0), (9, 0.5), (9, 0.9))):
+        x = synth.hidden_host(cfg, 0, 100 + it, T, rho)
+        ids = torch.zeros((T, cfg.top_k), dtype=torch.int32, device="cuda")
+        gates = torch.zeros((T, cfg.top_k), dtype=torch.float32, device="cuda")
+        uniq = torch.zeros((cfg.n_experts,), dtype=torch.int32, device="cuda")
+        nu = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        ctx.moe_route(_dev(x), rwd, ids, gates, uniq, nu)
+        torch.cuda.synchronize()
+        rids, rgates, logits = orc.route(x, rw, cfg.top_k, "f32")
+        srt = np.sort(logits, axis=1)[:, ::-1]
+        assert (srt[:, cfg.top_k - 1] - srt[:, cfg.top_k]).min() > 1e-9
+        np.testing.assert_array_equal(ids.cpu().numpy(), rids)
+        assert np.abs(gates.cpu().numpy() - rgates).max() <= 1e-5
+        u = orc.union(rids, cfg.n_experts)
+        assert int(nu.item()) == u["n_unique"]
+        np.testing.assert_array_equal(uniq.cpu().numpy(), u["unique"])
+        assert cfg.top_k <= u["n_unique"] <= min(cfg.n_experts, T * cfg.top_k)
+    ctx.close()
+
+
+def test_route_tie_rule_and_topk_equals_E():
+    import torch
+    d, E = 64, 8
+    ctx = binding.MoeContext(d, 64, E, E, 0, 4)
+    x = np.random.default_rng(0).normal(size=(3, d)).astype(np.float32)
+    ids = torch.zeros((3, E), dtype=torch.int32, device="cuda")
+    gates = torch.zeros((3, E), dtype=torch.float32, device="cuda")
+    ctx.moe_route(_dev(x), _dev(np.zeros((E, d), np.uint16)), ids, gates)      # all logits equal -> index order
+    torch.cuda.synchronize()
+    assert (ids.cpu().numpy() == np.arange(E)[None]).all()
+    np.testing.assert_allclose(gates.cpu().numpy(), 1.0 / E, rtol=1e-6)
+    rw = synth.f32_to_bf16_bits(np.random.default_rng(1).normal(0, 0.5, (E, d)).astype(np.float32))
+    rw[5] = rw[2]
+    ctx.moe_route(_dev(x), _dev(rw), ids, gates)
+    torch.cuda.synchronize()
+    rids, rgates, _ = orc.route(x, rw, E)
+    np.testing.assert_array_equal(ids.cpu().numpy(), rids)
+    ctx.close()
+
+
+def test_group_parity_random_routings():
+    import torch
+    rng = np.random.default_rng(2)
+    for E, k, T in ((8, 2, 9), (64, 8, 9), (64, 6, 1), (256, 16, 16), (5, 5, 3), (1, 1, 4)):
+        ctx = binding.MoeContext(64, 64, E, k, 0, T)
+        ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+        outs = dict(unique_experts=torch.full((E,), -9, dtype=torch.int32, device="cuda"),
+                    n_unique=torch.full((1,), -9, dtype=torch.int32, device="cuda"),
+                    expert_count=torch.full((E,), -9, dtype=torch.int32, device="cuda"),
+                    expert_offset=torch.full((E + 1,), -9, dtype=torch.int32, device="cuda"),
+                    assign=torch.full((T * k,), -9, dtype=torch.int32, device="cuda"))
+        ctx.moe_group(_dev(ids), **outs)
+        torch.cuda.synchronize()
+        u = orc.union(ids, E)
+        assert int(outs["n_unique"].item()) == u["n_unique"]
+        np.testing.assert_array_equal(outs["unique_experts"].cpu().numpy(), u["unique"])
+        np.testing.assert_array_equal(outs["expert_count"].cpu().numpy(), u["count"])
+        np.testing.assert_array_equal(outs["expert_offset"].cpu().numpy(), u["offset"])
+        np.testing.assert_array_equal(outs["assign"].cpu().numpy(), u["assign"])
+        ctx.close()
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 5, 9])
+def test_layer_parity_tiny(T):
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 0)
+    x = synth.hidden_host(cfg, 0, T, T, 0.5)
+    _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0), W, x)
+
+
+@pytest.mark.parametrize("shape", [
+    # d, ffn, E, top_k, n_shared, T : ragged tile counts, odd k-step counts, shared experts, top_k == E, T = 16
+    (96, 160, 5, 3, 1, 7), (32, 32, 1, 1, 0, 1), (64, 96, 4, 4, 2, 16), (160, 224, 12, 2, 0, 9), (1056, 544, 6, 2, 1, 4),
+])
+def test_layer_parity_ragged_shapes(shape):
+    d, ffn, E, k, ns, T = shape
+    rng = np.random.default_rng(sum(shape))
+    bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+    W = dict(router_w=bf(rng.normal(0, 0.3, (E, d))), w1=bf(rng.normal(0, 0.1, (E, ffn, d))),
+             w3=bf(rng.normal(0, 0.1, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))))
+    if ns:
+        W.update(sw1=bf(rng.normal(0, 0.1, (ns, ffn, d))), sw3=bf(rng.normal(0, 0.1, (ns, ffn, d))),
+                 sw2=bf(rng.normal(0, 0.1, (ns, d, ffn))))
+    x = rng.normal(size=(T, d)).astype(np.float32)
+    _check_layer((d, ffn, E, k, ns), W, x)
+
+
+@pytest.mark.parametrize("cfg", [synth.OLMOE, synth.DEEPSEEK], ids=lambda c: c.name)
+def test_layer_parity_fine_grained_full_size(cfg):
+    W = synth.layer_weights_host(cfg, 1)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 9)
+    Wd = _weights_dev(W)
+    for it, (T, rho) in enumerate(((1, 0.5), (4, 0.0), (9, 0.9))):
+        x = synth.hidden_host(cfg, 1, 200 + it, T, rho)
+        _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared), W, x, ctx, Wd)
+    ctx.close()
+
+
+def test_layer_parity_mixtral_full_size():
+    """Full Mixtral-8x7B-shaped layer in the launch configuration the benchmark times; device-generated
+    weights (bit-identical to the host generator) against the oracle on the whole output."""
+    import torch
+    cfg = synth.MIXTRAL
+    W = synth.layer_weights_host(cfg, 0)
+    Wd = synth.layer_weights_device(cfg, 0)
+    torch.cuda.synchronize()
+    assert (Wd["w2"][3, 100:200].cpu().numpy().view(np.uint16) == W["w2"][3, 100:200]).all()
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    for it, (T, rho) in enumerate(((1, 0.5), (9, 0.0))):
+        x = synth.hidden_host(cfg, 0, 300 + it, T, rho)
+        _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0), W, x, ctx, Wd)
+    ctx.close()
+
+
+def test_batch_invariance_and_determinism_on_gpu():
+    """Row t of a T-token step equals the T = 1 step on that token (verification == decoding), and
+    reruns are bit-identical (fixed reduction order, no atomics)."""
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 2)
+    Wd = _weights_dev(W)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    x = synth.hidden_host(cfg, 2, 5, 9, 0.5)
+    out9, ids9, *_ = _run_layer(ctx, Wd, x)
+    again, *_ = _run_layer(ctx, Wd, x)
+    np.testing.assert_array_equal(out9, again)
+    for t in (0, 4, 8):
+        o1, i1, *_ = _run_layer(ctx, Wd, x[t:t + 1])
+        np.testing.assert_array_equal(i1[0], ids9[t])
+        np.testing.assert_allclose(o1[0], out9[t], rtol=0, atol=2e-6 * np.abs(out9).max())
+    ctx.close()
+
+
+def test_stack_matches_per_layer_oracle():
+    import torch
+    cfg = synth.TINY
+    L, T = 3, 4
+    Ws = [synth.layer_weights_host(cfg, 10 + l) for l in range(L)]
+    Wds = [_weights_dev(W) for W in Ws]
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    x = np.stack([synth.hidden_host(cfg, 10 + l, 0, T, 0.5) for l in range(L)])
+    out = torch.zeros((L, T, cfg.d), dtype=torch.float32, device="cuda")
+    nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+    ctx.moe_verify_stack([ctx.weights(w) for w in Wds], _dev(x), out, nu)
+    torch.cuda.synchronize()
+    for l in range(L):
+        ref32, rids, _ = orc.layer(x[l], Ws[l], cfg.top_k, 0, "f32")
+        ref64, _, _ = orc.layer(x[l], Ws[l], cfg.top_k, 0, "f64")
+        _check_out(out[l].cpu().numpy(), ref32, ref64)
+        assert int(nu[l].item()) == orc.union(rids, cfg.n_experts)["n_unique"]
+    ctx.close()
+
+
+def test_argument_errors_are_reported_not_launched():
+    import torch
+    ctx = binding.MoeContext(64, 64, 4, 2, 0, 4)
+    x = torch.zeros((5, 64), dtype=torch.float32, device="cuda")
+    rw = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
+    with pytest.raises(binding.MoeError) as e:
+        ctx.moe_route(x, rw)                       # T = 5 > max_tokens
+    assert e.value.status == -1
+    with pytest.raises(ValueError):
+        ctx.moe_route(x[:2, :32].contiguous(), rw)
+    ctx.close()

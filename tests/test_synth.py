@@ -15,6 +15,14 @@ def test_streams_are_deterministic_and_sliceable():
     assert (a != other).mean() > 0.9
 
 
+def test_threaded_c_twin_equals_numpy_definition():
+    key = synth.stream_key(3, 1, synth.T_W3)
+    for count, start in ((1 << 17, 0), ((1 << 17) + 3, 8), (100_001, 6), (70_000, 1)):
+        a = synth.normal_bf16(key, 0.02, count, start)
+        b = synth.normal_bf16(key, 0.02, count, start, force_numpy=True)
+        assert a.shape == b.shape and (a == b).all()
+
+
 def test_weight_distribution():
     w = synth.bf16_bits_to_f32(synth.normal_bf16(synth.stream_key(1, 0, synth.T_W2), 0.02, 400_000)).astype(np.float64)
     assert abs(w.mean()) < 2e-4
