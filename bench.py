@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE verification path on one MI355X.
 
-A "step" is one pass of the whole hot path (route -> group -> gate/up -> down -> combine, i.e. one
+A "step" is one pass of the whole hot path (route + group -> gate/up -> down + combine, i.e. one
 moe_verify_layer call) over one batch of T = K+1 synthetic tokens on a Mixtral-8x7B-shaped layer.
 Step i uses K = i mod 9 (so every sweep K = 0..8 is timed equally often) and layer i mod L of L
 distinct resident layers, so consecutive steps never re-read weights that could still sit in the
@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--config", default="mixtral-8x7b-shaped")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fixed-k", type=int, default=-1, help="time a single K instead of cycling 0..8")
+    ap.add_argument("--layout", choices=("tiled", "row"), default="tiled",
+                    help="expert weight storage: tiled = re-ordered once at load time by moe_pack_weights")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build is single-GPU (no sharding, no collectives); --gpus {args.gpus} is not supported",
@@ -55,9 +57,16 @@ def main():
     T_MAX = 9
 
     # ---- resident inputs -------------------------------------------------------------------
-    layers_dev = [synth.layer_weights_device(cfg, l) for l in range(L)]
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX)
-    lw = [ctx.weights(w) for w in layers_dev]
+    lw = []
+    for l in range(L):
+        wd = synth.layer_weights_device(cfg, l)          # row-major, as the oracle sees them
+        w = ctx.weights(wd)
+        if args.layout == "tiled":
+            w = ctx.moe_pack_weights(w)                   # one-off static re-layout, same bytes
+            torch.cuda.synchronize()
+        lw.append(w)
+        del wd
     total = W_steps + K_steps
 
     def k_of(i):
@@ -126,7 +135,7 @@ def main():
 
     # ---- the box's plain read-stream rate, as a second denominator ---------------------------
     sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
-    probe = [layers_dev[l][n] for l in range(min(L, 4)) for n in ("w1", "w3")]
+    probe = [lw[l].tensors[i] for l in range(min(L, 4)) for i in (1, 2)]
     for t in probe[:2]:
         binding.moe_stream_read_probe(t, sink)
     torch.cuda.synchronize()
@@ -164,7 +173,7 @@ def main():
         "config": {"workload": f"{cfg.name} MoE layer d={cfg.d} E={cfg.n_experts} top{cfg.top_k} ffn={cfg.ffn} "
                                f"shared={cfg.n_shared}, bf16 weights, T=K+1 with K "
                                + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
-                               + f", rho={args.rho}, {L} rotating resident layers"},
+                               + f", rho={args.rho}, {L} rotating resident layers, {args.layout} weight layout"},
         "frac_hbm_peak": round(float(value / HBM_PEAK_GBS), 4),
         "by_K": by_k, "roofline": roofline, "stream_read_GBps": round(stream_gbs, 1), "cpu_baseline": cpu,
     }

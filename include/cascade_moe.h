@@ -92,8 +92,17 @@ moe_status moe_route(moe_ctx* ctx, const float* hidden, const uint16_t* router_w
 moe_status moe_group(moe_ctx* ctx, const int32_t* ids, int32_t T, int32_t* unique_experts, int32_t* n_unique,
                      int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream);
 
-/* One layer's weights: DEVICE pointers, caller-owned, bf16 row-major, alive until the stream drains.
- * sw1/sw3/sw2 are required iff shape.n_shared > 0. */
+/* Storage order of the expert matrices (the router is always row-major).
+ * MOE_LAYOUT_ROW_MAJOR: dense row-major as listed below.
+ * MOE_LAYOUT_TILED:     same bytes, re-ordered once by moe_pack_weights so that the 16-row x 32-column
+ *                       block a wavefront consumes per step is 1 KB of contiguous memory (block
+ *                       (i, s) = rows 16i..16i+15, columns 32s..32s+31 at block index i*(K/32)+s; inside
+ *                       a block, 16-byte unit l = r + 16*g holds row 16i+r, columns 32s+8g..32s+8g+7).
+ *                       Per-matrix and per-expert sizes are unchanged. */
+enum { MOE_LAYOUT_ROW_MAJOR = 0, MOE_LAYOUT_TILED = 1 };
+
+/* One layer's weights: DEVICE pointers, caller-owned, bf16, alive until the stream drains.
+ * sw1/sw3/sw2 are required iff shape.n_shared > 0.  Every pointer must be 16-byte aligned. */
 typedef struct {
   const uint16_t* router_w; /* [E, d]              */
   const uint16_t* w1;       /* [E, ffn, d]  gate   */
@@ -102,7 +111,16 @@ typedef struct {
   const uint16_t* sw1;      /* [n_shared, ffn, d]  */
   const uint16_t* sw3;      /* [n_shared, ffn, d]  */
   const uint16_t* sw2;      /* [n_shared, d, ffn]  */
+  int32_t layout;           /* MOE_LAYOUT_* of w1, w3, w2, sw1, sw3, sw2 */
 } moe_layer_weights;
+
+/* One-off static re-layout of a layer's expert weights for streaming (weights do not change while
+ * serving, so this runs once at load time, outside the path the paper's Section 2.4 cost is about).
+ * src: row-major weights.  dst: HOST struct whose DEVICE pointers the caller has set to buffers of
+ * the same sizes as src's (dst->router_w may equal src->router_w; otherwise the router is copied).
+ * On success dst->layout is set to MOE_LAYOUT_TILED.  Enqueues on `stream`; src and dst buffers
+ * must not overlap. */
+moe_status moe_pack_weights(moe_ctx* ctx, const moe_layer_weights* src, moe_layer_weights* dst, void* stream);
 
 /* Steps 1-5 — the whole verification step of one MoE layer (Section 2.2: the target model
  * verifies all K+1 tokens in one step; Section 2.4: expert-layer latency follows the number of
@@ -125,10 +143,11 @@ moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32
                             int32_t T, float* out, int32_t* n_unique_per_layer_opt, void* stream);
 
 /* Measurement aid: per-kernel timing.  While enabled, every moe_verify_layer / moe_verify_stack
- * layer records HIP events on its stream around each of its five kernels (route, group, gate-up,
- * down, combine); this adds event packets between the kernels, so whole-step latency is measured
- * with profiling OFF.  moe_ctx_profile_read waits for the recorded events, adds the elapsed times
- * into ms_sum[0..4] (HOST, milliseconds, same kernel order), stores the number of layer-steps in
+ * layer records HIP events on its stream around each of its four kernels (route+group, gate/up, down,
+ * combine); this adds event packets between the kernels, so whole-step latency is measured with
+ * profiling OFF.
+ * moe_ctx_profile_read waits for the recorded events, adds the elapsed times into ms_sum[0..3]
+ * (HOST, milliseconds, same kernel order), stores the number of layer-steps in
  * *steps (HOST) and forgets the events.  Both calls may allocate/free event objects. */
 moe_status moe_ctx_profile(moe_ctx* ctx, int32_t enable);
 moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);

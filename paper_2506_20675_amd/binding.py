@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
            "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_stream_read_probe",
-           "moe_ctx_profile", "moe_ctx_profile_read",
+           "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
            "cascade_next_k", "cascade_observe", "cascade_get_state")
 
@@ -36,7 +36,7 @@ class MoeShape(ctypes.Structure):
 
 
 class MoeLayerWeights(ctypes.Structure):
-    _fields_ = [(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")]
+    _fields_ = [(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")] + [("layout", c_int32)]
 
 
 class CascadeParams(ctypes.Structure):
@@ -80,6 +80,8 @@ def lib():
     L.moe_verify_stack.restype = ctypes.c_int
     L.moe_verify_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_int32, c_void_p, c_int32, c_void_p,
                                    c_void_p, c_void_p]
+    L.moe_pack_weights.restype = ctypes.c_int
+    L.moe_pack_weights.argtypes = [c_void_p, POINTER(MoeLayerWeights), POINTER(MoeLayerWeights), c_void_p]
     L.moe_ctx_profile.restype = ctypes.c_int
     L.moe_ctx_profile.argtypes = [c_void_p, c_int32]
     L.moe_ctx_profile_read.restype = ctypes.c_int
@@ -149,7 +151,7 @@ def _want_bf16(t, shape, name):
 class LayerWeights:
     """Device pointers of one layer's bf16 weights (tensors stay owned by the caller)."""
 
-    def __init__(self, shape: "MoeShape", router_w, w1, w3, w2, sw1=None, sw3=None, sw2=None):
+    def __init__(self, shape: "MoeShape", router_w, w1, w3, w2, sw1=None, sw3=None, sw2=None, layout=0):
         E, d, f, ns = shape.n_experts, shape.d, shape.ffn, shape.n_shared
         _want_bf16(router_w, (E, d), "router_w")
         _want_bf16(w1, (E, f, d), "w1")
@@ -162,7 +164,7 @@ class LayerWeights:
             if sw1 is None or sw3 is None or sw2 is None:
                 raise ValueError("shared expert weights required")
         self.tensors = (router_w, w1, w3, w2, sw1, sw3, sw2)
-        self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors])
+        self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors], layout)
 
 
 class MoeContext:
@@ -192,17 +194,26 @@ class MoeContext:
         return LayerWeights(self.shape, W["router_w"], W["w1"], W["w3"], W["w2"], W.get("sw1"), W.get("sw3"),
                             W.get("sw2"))
 
-    KERNELS = ("route", "group", "gateup", "down", "combine")
+    KERNELS = ("route_group", "gateup", "down", "combine")
 
     def moe_ctx_profile(self, enable: bool) -> None:
         _check(lib().moe_ctx_profile(self._h, 1 if enable else 0), "moe_ctx_profile")
 
     def moe_ctx_profile_read(self):
         """-> ({kernel: summed ms}, number of layer-steps) since profiling was enabled / last read."""
-        ms = (c_double * 5)()
+        ms = (c_double * 4)()
         n = c_int64()
         _check(lib().moe_ctx_profile_read(self._h, ms, byref(n)), "moe_ctx_profile_read")
         return dict(zip(self.KERNELS, [float(v) for v in ms])), int(n.value)
+
+    def moe_pack_weights(self, src: LayerWeights, stream=None, in_place_of=None) -> LayerWeights:
+        """Re-layout src (row-major) into freshly allocated tiled buffers; returns the tiled LayerWeights."""
+        import torch
+        bufs = [None if t is None else torch.empty_like(t) for t in src.tensors]
+        bufs[0] = src.tensors[0]            # router is shared, it stays row-major
+        dst = LayerWeights(self.shape, *bufs, layout=0)
+        _check(lib().moe_pack_weights(self._h, byref(src.c), byref(dst.c), _stream_ptr(stream)), "moe_pack_weights")
+        return dst
 
     # ---- device calls (same names as the C ABI) -------------------------------------------
     def moe_route(self, hidden, router_w, ids=None, gates=None, unique_experts=None, n_unique=None, stream=None):

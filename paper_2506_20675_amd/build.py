@@ -24,10 +24,25 @@ def _run(cmd):
     return r
 
 
+def _check_no_scratch(stderr: str) -> None:
+    """Refuse a build in which any kernel spills registers to scratch memory: the expert kernels are
+    sized to stay in registers, and a spilling variant of them has been seen to give wrong results."""
+    name = None
+    for line in stderr.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0].strip())
+            if size != 0:
+                raise RuntimeError(f"kernel {name} uses {size} bytes/lane of scratch (register spill)")
+
+
 def build_all(verbose: bool = False) -> None:
     obj_k = os.path.join(HERE, "moe_kernels.o")
     obj_c = os.path.join(HERE, "cascade_ctrl.o")
-    _run([HIPCC] + HIP_FLAGS + ["-I", INCLUDE, "-c", os.path.join(CSRC, "moe_kernels.hip"), "-o", obj_k])
+    r = _run([HIPCC] + HIP_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-I", INCLUDE, "-c",
+                                   os.path.join(CSRC, "moe_kernels.hip"), "-o", obj_k])
+    _check_no_scratch(r.stderr)
     # host policy code: plain C++ with contraction off so decisions replay identically everywhere
     _run(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-I", INCLUDE, "-c",
           os.path.join(CSRC, "cascade_ctrl.cpp"), "-o", obj_c])

@@ -5,12 +5,14 @@
 // HBM traffic for the UNION of the picked experts (Section 1, Section 2.4).  The path below touches
 // every unique expert's weights exactly once per step:
 //
-//   route_kernel   router logits (fp64 accumulate), top-k, softmax gates; also splits the fp32
-//                  activations into bf16 hi + lo halves for the matrix cores
-//   group_kernel   union of experts, per-expert token lists, per-slot gate table
+//   route_kernel   router logits (fp64 accumulate), top-k, softmax gates; splits the fp32 activations
+//                  into bf16 hi + lo fragments for the matrix cores; its last-finishing workgroup
+//                  builds the union of experts, the per-expert token lists and the per-slot gate table
 //   gateup_kernel  for each unique expert: G = w1 X, U = w3 X, H = gate * silu(G) * U      (2/3 of bytes)
-//   down_kernel    split-K partial sums of w2 H over (expert, k-chunk)                     (1/3 of bytes)
-//   combine_kernel out[t] = sum of the partial slabs in a fixed order (deterministic, no atomics)
+//   down_kernel    split-K partial sums of w2 H over (expert, k-chunk)                     (1/3 of bytes);
+//                  the last-finishing workgroup of each row block adds the slabs in a fixed order into
+//                  out (gate-weighted combine, deterministic, no floating-point atomics)
+//   (group_kernel  the grouping step alone, for callers that bring their own routing)
 //
 // The two FFN kernels are skinny GEMMs (at most 16 token columns) and purely HBM-bound.  They use
 // v_mfma_f32_16x16x32_bf16 with the weight tile as the A operand: lane l holds 8 consecutive k of
@@ -21,6 +23,7 @@
 // matter how many tokens share the expert.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -54,8 +57,38 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t& hi, uint16_t& lo) 
   lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit global load; NT = streaming (non-temporal) hint for bytes that are read exactly once.
+template <bool NT>
 __device__ __forceinline__ uint4 ld128(const char* base, uint32_t byte_off) {
-  return *reinterpret_cast<const uint4*>(base + byte_off);
+  if constexpr (NT) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
+    return uint4{v.x, v.y, v.z, v.w};
+  } else {
+    return *reinterpret_cast<const uint4*>(base + byte_off);
+  }
+}
+
+// Hand-off of a few words from one workgroup to another INSIDE a launch (the router's "last workgroup
+// builds the expert union" tail).  The words are written and read with relaxed agent-scope atomics,
+// which write through / read past the per-XCD caches, so no cache-wide writeback or invalidate is
+// needed (a full agent-scope fence costs far more than the data it protects here); the producer only
+// has to wait until its stores have been acknowledged before it takes its ticket.
+// Producer side: all of this thread's earlier stores are acknowledged, and neither the compiler nor the
+// hardware moves later accesses above this point.  Consumer side: the mirror image.
+__device__ __forceinline__ void handoff_release() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+}
+__device__ __forceinline__ void handoff_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+
+// Activation fragments.  The MFMA B operand of k-step s (32 k) wants, in lane (n = l%16, kg = l/16),
+// the 8 values k = 32 s + 8 kg .. +7 of token column n.  Activations are therefore stored in that
+// order — unit q = s*64 + kg*16 + n holds those 8 bf16 (16 bytes) — so a wave fetches the whole
+// fragment of a k-step with ONE contiguous 1 KB load.  Token columns are padded to 16.
+__device__ __forceinline__ size_t frag_unit(int k8, int n) {  // k8 = k / 8
+  return (size_t)(k8 >> 2) * 64 + (size_t)(k8 & 3) * 16 + n;
 }
 
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
@@ -64,128 +97,36 @@ __device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 1: router.  One workgroup (4 waves) per token.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hidden,
-                                                    const uint16_t* __restrict__ router_w, int d, int E, int top_k,
-                                                    int32_t* __restrict__ ids_ws, float* __restrict__ gates_ws,
-                                                    int32_t* __restrict__ ids_out, float* __restrict__ gates_out,
-                                                    uint16_t* __restrict__ xs_hi, uint16_t* __restrict__ xs_lo) {
-  __shared__ double s_logit[kMaxExperts];
-  __shared__ float s_sel[kMaxTopK];
-  __shared__ int s_id[kMaxTopK];
-  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const float* x = hidden + (size_t)t * d;
-
-  // activations -> bf16 hi/lo halves, consumed by the expert kernels as the MFMA B operand
-  for (int j = tid * 4; j < d; j += 256 * 4) {
-    const float4 v = *reinterpret_cast<const float4*>(x + j);
-    ushort4 h, l;
-    split_bf16(v.x, h.x, l.x);
-    split_bf16(v.y, h.y, l.y);
-    split_bf16(v.z, h.z, l.z);
-    split_bf16(v.w, h.w, l.w);
-    *reinterpret_cast<ushort4*>(xs_hi + (size_t)t * d + j) = h;
-    *reinterpret_cast<ushort4*>(xs_lo + (size_t)t * d + j) = l;
-  }
-
-  // logits in fp64: fp32 x bf16 products are exact in double, so the top-k decision does not
-  // depend on the order of summation (beyond ~1e-13 relative)
-  for (int e = wave; e < E; e += 4) {
-    const uint16_t* w = router_w + (size_t)e * d;
-    double acc = 0.0;
-    for (int j = lane * 8; j < d; j += 64 * 8) {
-      const uint4 wv = *reinterpret_cast<const uint4*>(w + j);
-      const float4 x0 = *reinterpret_cast<const float4*>(x + j);
-      const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
-      acc = fma((double)x0.x, (double)bf16_to_f32(wv.x & 0xffffu), acc);
-      acc = fma((double)x0.y, (double)bf16_to_f32(wv.x >> 16), acc);
-      acc = fma((double)x0.z, (double)bf16_to_f32(wv.y & 0xffffu), acc);
-      acc = fma((double)x0.w, (double)bf16_to_f32(wv.y >> 16), acc);
-      acc = fma((double)x1.x, (double)bf16_to_f32(wv.z & 0xffffu), acc);
-      acc = fma((double)x1.y, (double)bf16_to_f32(wv.z >> 16), acc);
-      acc = fma((double)x1.z, (double)bf16_to_f32(wv.w & 0xffffu), acc);
-      acc = fma((double)x1.w, (double)bf16_to_f32(wv.w >> 16), acc);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) s_logit[e] = acc;
-  }
-  __syncthreads();
-  if (wave != 0) return;
-
-  // top-k by repeated wave-wide arg-max; ties go to the lower expert index
-  double v[kMaxExperts / 64];
-#pragma unroll
-  for (int q = 0; q < kMaxExperts / 64; ++q) {
-    const int e = lane + 64 * q;
-    double lv = e < E ? s_logit[e] : 0.0;
-    if (lv != lv) lv = -INFINITY;  // a NaN logit is never preferred
-    v[q] = lv;
-  }
-  unsigned taken = 0;
-  for (int i = 0; i < top_k; ++i) {
-    double bv = -INFINITY;
-    int be = INT_MAX;
-#pragma unroll
-    for (int q = 0; q < kMaxExperts / 64; ++q) {
-      const int e = lane + 64 * q;
-      if (e < E && !((taken >> q) & 1u) && (be == INT_MAX || v[q] > bv)) {
-        bv = v[q];
-        be = e;
-      }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const double ov = __shfl_xor(bv, o);
-      const int oe = __shfl_xor(be, o);
-      if (ov > bv || (ov == bv && oe < be)) {
-        bv = ov;
-        be = oe;
-      }
-    }
-    if ((be & 63) == lane) taken |= 1u << (be >> 6);
-    if (lane == 0) {
-      s_id[i] = be;
-      s_sel[i] = (float)bv;
-    }
-  }
-  if (lane == 0) {
-    // gates = softmax over the selected logits, summed in slot order
-    float p[kMaxTopK];
-    const float l0 = s_sel[0];
-    float sum = 0.f;
-    for (int i = 0; i < top_k; ++i) {
-      p[i] = expf(s_sel[i] - l0);
-      sum += p[i];
-    }
-    for (int i = 0; i < top_k; ++i) {
-      const float g = p[i] / sum;
-      const int a = t * top_k + i;
-      ids_ws[a] = s_id[i];
-      gates_ws[a] = g;
-      if (ids_out) ids_out[a] = s_id[i];
-      if (gates_out) gates_out[a] = g;
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
 // Step 2: union of activated experts + per-expert token lists.  One workgroup, thread e = expert e.
 // ------------------------------------------------------------------------------------------
 struct GroupOut {
   int32_t *unique, *n_unique, *count, *offset, *assign;
 };
+struct GroupArgs {
+  const int32_t* ids;   // [T, top_k]
+  const float* gates;   // [T, top_k] or NULL (then no gate table is built)
+  int T, top_k, E;
+  GroupOut ws, user;    // every pointer optional
+  int32_t* n_unique_extra;
+  int32_t* slot_expert;  // [u_max] expert of unique slot u
+  float* slot_gate;      // [u_max, 16] gate of token column n for slot u, 0 = not routed
+};
 
-__global__ __launch_bounds__(256) void group_kernel(const int32_t* __restrict__ ids, const float* __restrict__ gates,
-                                                    int T, int top_k, int E, GroupOut ws, GroupOut user,
-                                                    int32_t* __restrict__ n_unique_extra,
-                                                    int32_t* __restrict__ slot_expert, float* __restrict__ slot_gate) {
+// Executed by one whole 256-thread workgroup.  ids/gates may have been written by other workgroups of
+// the same launch: they are read with agent-scope atomic loads, which never hit a stale cache line.
+__device__ void group_body(const GroupArgs& g) {
   __shared__ int s_ids[kMaxTokens * kMaxTopK];
   __shared__ int s_cnt[4], s_uni[4];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int T = g.T, top_k = g.top_k, E = g.E;
+  const GroupOut& ws = g.ws;
+  const GroupOut& user = g.user;
+  const float* gates = g.gates;
+  int32_t* slot_expert = g.slot_expert;
+  float* slot_gate = g.slot_gate;
+  int32_t* n_unique_extra = g.n_unique_extra;
   const int A = T * top_k;
-  if (tid < A) s_ids[tid] = ids[tid];
+  if (tid < A) s_ids[tid] = __hip_atomic_load(g.ids + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   const int e = tid;
   int cnt = 0;
@@ -235,10 +176,10 @@ __global__ __launch_bounds__(256) void group_kernel(const int32_t* __restrict__ 
           ++j;
           if (gates) {
             const int tok = a / top_k;
-            const float g = gates[a];
+            const float gv = __hip_atomic_load(gates + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int n = 0; n < kGateCols; ++n)
-              if (n == tok) row[n] = g;
+              if (n == tok) row[n] = gv;
           }
         }
       if (slot_gate && gates) {
@@ -258,6 +199,136 @@ __global__ __launch_bounds__(256) void group_kernel(const int32_t* __restrict__ 
     if (user.n_unique) *user.n_unique = n_unique;
     if (n_unique_extra) *n_unique_extra = n_unique;
   }
+}
+
+__global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g); }
+
+// ------------------------------------------------------------------------------------------
+// Step 1: router.  One workgroup (4 waves) per token.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hidden,
+                                                    const uint16_t* __restrict__ router_w, int d, int E, int top_k,
+                                                    int32_t* __restrict__ ids_ws, float* __restrict__ gates_ws,
+                                                    int32_t* __restrict__ ids_out, float* __restrict__ gates_out,
+                                                    uint16_t* __restrict__ xs_hi, uint16_t* __restrict__ xs_lo,
+                                                    int32_t* __restrict__ ticket, GroupArgs grp) {
+  __shared__ double s_logit[kMaxExperts];
+  __shared__ float s_sel[kMaxTopK];
+  __shared__ int s_id[kMaxTopK];
+  __shared__ int s_last;
+  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* x = hidden + (size_t)t * d;
+
+  // activations -> bf16 hi/lo halves in fragment order, consumed by the expert kernels as the MFMA B operand
+  for (int k8 = tid; k8 < (d >> 3); k8 += 256) {
+    const float4 v0 = *reinterpret_cast<const float4*>(x + k8 * 8);
+    const float4 v1 = *reinterpret_cast<const float4*>(x + k8 * 8 + 4);
+    const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint16_t h0, l0, h1, l1;
+      split_bf16(v[2 * i], h0, l0);
+      split_bf16(v[2 * i + 1], h1, l1);
+      h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    const size_t q = frag_unit(k8, t);
+    reinterpret_cast<uint4*>(xs_hi)[q] = uint4{h[0], h[1], h[2], h[3]};
+    reinterpret_cast<uint4*>(xs_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
+  }
+
+  // logits in fp64: fp32 x bf16 products are exact in double, so the top-k decision does not
+  // depend on the order of summation (beyond ~1e-13 relative)
+  for (int e = wave; e < E; e += 4) {
+    const uint16_t* w = router_w + (size_t)e * d;
+    double acc = 0.0;
+    for (int j = lane * 8; j < d; j += 64 * 8) {
+      const uint4 wv = *reinterpret_cast<const uint4*>(w + j);
+      const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+      const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+      acc = fma((double)x0.x, (double)bf16_to_f32(wv.x & 0xffffu), acc);
+      acc = fma((double)x0.y, (double)bf16_to_f32(wv.x >> 16), acc);
+      acc = fma((double)x0.z, (double)bf16_to_f32(wv.y & 0xffffu), acc);
+      acc = fma((double)x0.w, (double)bf16_to_f32(wv.y >> 16), acc);
+      acc = fma((double)x1.x, (double)bf16_to_f32(wv.z & 0xffffu), acc);
+      acc = fma((double)x1.y, (double)bf16_to_f32(wv.z >> 16), acc);
+      acc = fma((double)x1.z, (double)bf16_to_f32(wv.w & 0xffffu), acc);
+      acc = fma((double)x1.w, (double)bf16_to_f32(wv.w >> 16), acc);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) s_logit[e] = acc;
+  }
+  __syncthreads();
+  if (wave == 0) {
+  // top-k by repeated wave-wide arg-max; ties go to the lower expert index
+  double v[kMaxExperts / 64];
+#pragma unroll
+  for (int q = 0; q < kMaxExperts / 64; ++q) {
+    const int e = lane + 64 * q;
+    double lv = e < E ? s_logit[e] : 0.0;
+    if (lv != lv) lv = -INFINITY;  // a NaN logit is never preferred
+    v[q] = lv;
+  }
+  unsigned taken = 0;
+  for (int i = 0; i < top_k; ++i) {
+    double bv = -INFINITY;
+    int be = INT_MAX;
+#pragma unroll
+    for (int q = 0; q < kMaxExperts / 64; ++q) {
+      const int e = lane + 64 * q;
+      if (e < E && !((taken >> q) & 1u) && (be == INT_MAX || v[q] > bv)) {
+        bv = v[q];
+        be = e;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const double ov = __shfl_xor(bv, o);
+      const int oe = __shfl_xor(be, o);
+      if (ov > bv || (ov == bv && oe < be)) {
+        bv = ov;
+        be = oe;
+      }
+    }
+    if ((be & 63) == lane) taken |= 1u << (be >> 6);
+    if (lane == 0) {
+      s_id[i] = be;
+      s_sel[i] = (float)bv;
+    }
+  }
+  if (lane == 0) {
+    // gates = softmax over the selected logits, summed in slot order
+    float p[kMaxTopK];
+    const float l0 = s_sel[0];
+    float sum = 0.f;
+    for (int i = 0; i < top_k; ++i) {
+      p[i] = expf(s_sel[i] - l0);
+      sum += p[i];
+    }
+    for (int i = 0; i < top_k; ++i) {
+      const float g = p[i] / sum;
+      const int a = t * top_k + i;
+      __hip_atomic_store(ids_ws + a, s_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(gates_ws + a, g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ids_out) ids_out[a] = s_id[i];
+      if (gates_out) gates_out[a] = g;
+    }
+    handoff_release();  // this token's routing is out before the ticket is taken
+  }
+  }  // wave 0
+
+  // Step 2 rides in the same launch: the workgroup that finishes last sees every token's routing
+  // and builds the expert union and the per-slot tables (fixed order -> deterministic).
+  __syncthreads();
+  if (tid == 0)
+    s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+  __syncthreads();
+  if (!s_last) return;
+  handoff_acquire();
+  group_body(grp);
+  if (tid == 0) *ticket = 0;  // ready for the next launch on this stream
 }
 
 // ------------------------------------------------------------------------------------------
@@ -300,22 +371,45 @@ __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Weight addressing.  A k-step of a 16-row tile is 16 rows x 32 k = 1 KB of bf16.
+//   row-major [rows, K]:  lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg
+//   tiled              :  the same 1 KB stored contiguously, block index tile*(K/32) + s, lane l at
+//                         byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
+// ------------------------------------------------------------------------------------------
+template <bool TILED>
+struct WeightAddr {
+  uint32_t lane_off, step_stride;
+  size_t tile_stride;
+  __device__ __forceinline__ WeightAddr(int K, int r, int kg, int lane) {
+    if constexpr (TILED) {
+      lane_off = lane * 16;
+      step_stride = 1024;
+      tile_stride = (size_t)(K >> 5) * 1024;
+    } else {
+      lane_off = ((uint32_t)r * K + kg * 8) * 2;
+      step_stride = 64;
+      tile_stride = (size_t)16 * K * 2;
+    }
+  }
+};
+
+// ------------------------------------------------------------------------------------------
 // Step 3: gate/up projections + SiLU*mul for every unique expert (and shared expert).
 // grid = (row blocks of 16*R rows of ffn, expert slots); block = W waves that split d.
 // ------------------------------------------------------------------------------------------
 struct GateupArgs {
   const uint16_t *w1, *w3, *sw1, *sw3;  // [E,ffn,d] / [n_shared,ffn,d]
-  const uint16_t *xs_hi, *xs_lo;        // [max_tokens,d]
+  const uint16_t *xf_hi, *xf_lo;        // activation fragments, d*16 elements each
   const int32_t* n_unique;
   const int32_t* slot_expert;  // [u_max]
   const float* slot_gate;      // [u_tot,16]
-  uint16_t *h_hi, *h_lo;       // [u_tot,max_tokens,ffn]
-  int d, ffn, T, u_max, max_tokens;
+  uint16_t *hf_hi, *hf_lo;     // [u_tot] fragments of gate*silu(G)*U, ffn*16 elements each
+  int d, ffn, T, u_max;
 };
 
-template <int R, int W, int P>
+template <int R, int W, int P, bool TILED, bool NT>
 __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
-  __shared__ float4 red[W * 2 * R * 64];
+  __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
   const int u = blockIdx.y;
   const char *W1, *W3;
   const size_t per = (size_t)g.ffn * g.d * 2;
@@ -334,18 +428,17 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   const int nst = max(0, min(chunk, nsteps - wave * chunk));
   const int s_beg = min(wave * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
 
+  const WeightAddr<TILED> wa(g.d, r, kg, lane);
   const char* base[2 * R];
 #pragma unroll
   for (int j = 0; j < R; ++j) {
-    const size_t row0 = (size_t)min(tile0 + j, ntiles - 1) * 16;  // ragged last block: re-read a valid tile, result unused
-    base[j] = W1 + row0 * g.d * 2;
-    base[R + j] = W3 + row0 * g.d * 2;
+    const size_t t = (size_t)min(tile0 + j, ntiles - 1);  // ragged last block: re-read a valid tile, result unused
+    base[j] = W1 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
+    base[R + j] = W3 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
   }
-  const uint32_t a_off = ((uint32_t)r * g.d + s_beg * 32 + kg * 8) * 2;
-  const int n = min(r, g.T - 1);  // columns >= T duplicate the last token; their results are dropped
-  const uint32_t b_off = ((uint32_t)n * g.d + s_beg * 32 + kg * 8) * 2;
-  const char* XH = reinterpret_cast<const char*>(g.xs_hi);
-  const char* XL = reinterpret_cast<const char*>(g.xs_lo);
+  const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * 1024;
+  const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * 1024;
+  const uint32_t b_off = lane * 16;
 
   f32x4 acc[2 * R];
 #pragma unroll
@@ -354,45 +447,71 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   pipeline<2 * R, P>(
       nst,
       [&](Stage<2 * R>& st, int s) {
-        const uint32_t ko = (uint32_t)s * 64;
 #pragma unroll
-        for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128(base[j], a_off + ko);
-        st.bh = ld128(XH, b_off + ko);
-        st.bl = ld128(XL, b_off + ko);
+        for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+#ifdef MOE_EXPERIMENT_NO_B
+        st.bh = ld128<false>(XH, b_off);
+        st.bl = ld128<false>(XL, b_off);
+#else
+        st.bh = ld128<false>(XH, b_off + (uint32_t)s * 1024);
+        st.bl = ld128<false>(XL, b_off + (uint32_t)s * 1024);
+#endif
       },
       [&](const Stage<2 * R>& st) {
+#ifdef MOE_EXPERIMENT_NO_MFMA
+#pragma unroll
+        for (int j = 0; j < 2 * R; ++j) {
+          acc[j][0] += __uint_as_float((st.a[j].x ^ st.bh.x) & 0x3fffffffu);
+          acc[j][1] += __uint_as_float((st.a[j].y ^ st.bl.y) & 0x3fffffffu);
+          acc[j][2] += __uint_as_float((st.a[j].z ^ st.bh.z) & 0x3fffffffu);
+          acc[j][3] += __uint_as_float((st.a[j].w ^ st.bl.w) & 0x3fffffffu);
+        }
+#else
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh, acc[j]);
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl, acc[j]);
+#endif
       });
 
   // reduce the W k-slices through LDS, then wave w finishes tiles w, w+W, ...
+  if constexpr (W > 1) {
 #pragma unroll
-  for (int j = 0; j < 2 * R; ++j)
-    red[(wave * 2 * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
-  __syncthreads();
+    for (int j = 0; j < 2 * R; ++j)
+      red[(wave * 2 * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    __syncthreads();
+  }
   const float gate = g.slot_gate[u * kGateCols + r];
-  for (int j = wave; j < R; j += W) {
-    if (tile0 + j >= ntiles) break;
-    float4 G = red[j * 64 + lane], U = red[(R + j) * 64 + lane];
-    for (int w = 1; w < W; ++w) {
-      const float4 g2 = red[(w * 2 * R + j) * 64 + lane], u2 = red[(w * 2 * R + R + j) * 64 + lane];
-      G.x += g2.x, G.y += g2.y, G.z += g2.z, G.w += g2.w;
-      U.x += u2.x, U.y += u2.y, U.z += u2.z, U.w += u2.w;
+  uint16_t* HH = g.hf_hi + (size_t)u * g.ffn * 16;
+  uint16_t* HL = g.hf_lo + (size_t)u * g.ffn * 16;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j % W != wave || tile0 + j >= ntiles) continue;
+    float4 G, U;
+    if constexpr (W > 1) {
+      G = red[j * 64 + lane];
+      U = red[(R + j) * 64 + lane];
+      for (int w = 1; w < W; ++w) {
+        const float4 g2 = red[(w * 2 * R + j) * 64 + lane], u2 = red[(w * 2 * R + R + j) * 64 + lane];
+        G.x += g2.x, G.y += g2.y, G.z += g2.z, G.w += g2.w;
+        U.x += u2.x, U.y += u2.y, U.z += u2.z, U.w += u2.w;
+      }
+    } else {
+      G = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+      U = float4{acc[R + j][0], acc[R + j][1], acc[R + j][2], acc[R + j][3]};
     }
     if (r < g.T && gate != 0.f) {
-      // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r
-      const float hv[4] = {gate * (G.x / (1.f + expf(-G.x))) * U.x, gate * (G.y / (1.f + expf(-G.y))) * U.y,
-                           gate * (G.z / (1.f + expf(-G.z))) * U.z, gate * (G.w / (1.f + expf(-G.w))) * U.w};
-      ushort4 hi, lo;
-      split_bf16(hv[0], hi.x, lo.x);
-      split_bf16(hv[1], hi.y, lo.y);
-      split_bf16(hv[2], hi.z, lo.z);
-      split_bf16(hv[3], hi.w, lo.w);
-      const size_t o = ((size_t)u * g.max_tokens + r) * g.ffn + (size_t)(tile0 + j) * 16 + kg * 4;
-      *reinterpret_cast<ushort4*>(g.h_hi + o) = hi;
-      *reinterpret_cast<ushort4*>(g.h_lo + o) = lo;
+      // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r: four consecutive k of the
+      // down projection, i.e. one half of a 16-byte fragment unit
+      uint16_t hi[4], lo[4];
+      split_bf16(gate * (G.x / (1.f + expf(-G.x))) * U.x, hi[0], lo[0]);
+      split_bf16(gate * (G.y / (1.f + expf(-G.y))) * U.y, hi[1], lo[1]);
+      split_bf16(gate * (G.z / (1.f + expf(-G.z))) * U.z, hi[2], lo[2]);
+      split_bf16(gate * (G.w / (1.f + expf(-G.w))) * U.w, hi[3], lo[3]);
+      const int k = (tile0 + j) * 16 + kg * 4;
+      const size_t o = frag_unit(k >> 3, r) * 8 + (k & 4);
+      *reinterpret_cast<uint2*>(HH + o) = uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+      *reinterpret_cast<uint2*>(HL + o) = uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
     }
   }
 }
@@ -404,7 +523,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
 // ------------------------------------------------------------------------------------------
 struct DownArgs {
   const uint16_t *w2, *sw2;      // [E,d,ffn] / [n_shared,d,ffn]
-  const uint16_t *h_hi, *h_lo;   // [u_tot,max_tokens,ffn]
+  const uint16_t *hf_hi, *hf_lo; // [u_tot] fragments, ffn*16 elements each
   const int32_t* n_unique;
   const int32_t* slot_expert;
   const float* slot_gate;
@@ -412,9 +531,9 @@ struct DownArgs {
   int d, ffn, T, u_max, max_tokens, KS;
 };
 
-template <int R, int W, int P>
+template <int R, int W, int P, bool TILED, bool NT>
 __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
-  __shared__ float4 red[W * R * 64];
+  __shared__ float4 red[W > 1 ? W * R * 64 : 1];
   const int u = blockIdx.y, ks = blockIdx.z;
   const char* W2;
   const size_t per = (size_t)g.ffn * g.d * 2;
@@ -430,16 +549,16 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   const int nst = max(0, min(chunk, nsteps - (ks * W + wave) * chunk));
   const int s_beg = min((ks * W + wave) * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
 
+  const WeightAddr<TILED> wa(g.ffn, r, kg, lane);
   const char* base[R];
 #pragma unroll
-  for (int j = 0; j < R; ++j) base[j] = W2 + (size_t)min(tile0 + j, ntiles - 1) * 16 * g.ffn * 2;
-  const uint32_t a_off = ((uint32_t)r * g.ffn + s_beg * 32 + kg * 8) * 2;
+  for (int j = 0; j < R; ++j)
+    base[j] = W2 + (size_t)min(tile0 + j, ntiles - 1) * wa.tile_stride + (size_t)s_beg * wa.step_stride;
   // token column r contributes only if the token is routed to this expert (gate != 0)
   const bool live = r < g.T && g.slot_gate[u * kGateCols + r] != 0.f;
-  const size_t hrow = ((size_t)u * g.max_tokens + min(r, g.T - 1)) * g.ffn;
-  const char* HH = reinterpret_cast<const char*>(g.h_hi + hrow);
-  const char* HL = reinterpret_cast<const char*>(g.h_lo + hrow);
-  const uint32_t b_off = (uint32_t)(s_beg * 32 + kg * 8) * 2;
+  const char* HH = reinterpret_cast<const char*>(g.hf_hi) + ((size_t)u * g.ffn * 16 + (size_t)s_beg * 512) * 2;
+  const char* HL = reinterpret_cast<const char*>(g.hf_lo) + ((size_t)u * g.ffn * 16 + (size_t)s_beg * 512) * 2;
+  const uint32_t b_off = lane * 16;
 
   f32x4 acc[R];
 #pragma unroll
@@ -448,14 +567,13 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   pipeline<R, P>(
       nst,
       [&](Stage<R>& st, int s) {
-        const uint32_t ko = (uint32_t)s * 64;
 #pragma unroll
-        for (int j = 0; j < R; ++j) st.a[j] = ld128(base[j], a_off + ko);
+        for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
         st.bh = uint4{0u, 0u, 0u, 0u};
         st.bl = uint4{0u, 0u, 0u, 0u};
         if (live) {
-          st.bh = ld128(HH, b_off + ko);
-          st.bl = ld128(HL, b_off + ko);
+          st.bh = ld128<false>(HH, b_off + (uint32_t)s * 1024);
+          st.bl = ld128<false>(HL, b_off + (uint32_t)s * 1024);
         }
       },
       [&](const Stage<R>& st) {
@@ -465,15 +583,23 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
         for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl, acc[j]);
       });
 
+  if constexpr (W > 1) {
 #pragma unroll
-  for (int j = 0; j < R; ++j) red[(wave * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
-  __syncthreads();
-  for (int j = wave; j < R; j += W) {
-    if (tile0 + j >= ntiles) break;
-    float4 y = red[j * 64 + lane];
-    for (int w = 1; w < W; ++w) {
-      const float4 y2 = red[(w * R + j) * 64 + lane];
-      y.x += y2.x, y.y += y2.y, y.z += y2.z, y.w += y2.w;
+    for (int j = 0; j < R; ++j) red[(wave * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j % W != wave || tile0 + j >= ntiles) continue;
+    float4 y;
+    if constexpr (W > 1) {
+      y = red[j * 64 + lane];
+      for (int w = 1; w < W; ++w) {
+        const float4 y2 = red[(w * R + j) * 64 + lane];
+        y.x += y2.x, y.y += y2.y, y.z += y2.z, y.w += y2.w;
+      }
+    } else {
+      y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
     }
     if (r < g.T) {
       const size_t o = (((size_t)u * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
@@ -483,7 +609,8 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 5: combine.  out[t,c] = sum over live slabs (routed slots ascending, then shared), fixed order.
+// Step 5 (after the split-K down kernel): out[t,c] = sum over live slabs, routed slots ascending then
+// shared experts, k-chunks ascending — a fixed order, so reruns are bit-identical.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
                                                       const int32_t* __restrict__ n_unique_p, float* __restrict__ out,
@@ -507,6 +634,18 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
       s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
     }
   *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
+}
+
+// One-off re-layout of a row-major [rows, K] bf16 matrix into the tiled order (see WeightAddr).
+__global__ __launch_bounds__(256) void pack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t rows,
+                                                   int K) {
+  const size_t nsteps = (size_t)(K >> 5), units = rows * (size_t)(K >> 3);
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < units; q += (size_t)gridDim.x * 256) {
+    const size_t blk = q >> 6;
+    const int l = (int)(q & 63), rr = l & 15, kk = l >> 4;
+    const size_t tile = blk / nsteps, st = blk % nsteps;
+    dst[q] = src[((tile * 16 + rr) * (size_t)K + st * 32 + kk * 8) >> 3];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -541,60 +680,68 @@ struct moe_ctx {
   moe_shape s;
   int device;
   int u_max, u_tot;
-  int gu_R, dn_R, dn_KS;  // launch plan
+  int ks_alloc;           // split-K slabs the partial buffer is sized for
+  int plan_override[3];   // MOE_PLAN=guR,dnR,dnKS (tuning), zeros = automatic
   char* ws;
   size_t ws_bytes;
-  uint16_t *xs_hi, *xs_lo, *h_hi, *h_lo;
+  uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
   int32_t *ids, *unique, *n_unique, *count, *offset, *assign, *slot_expert;
   float *gates, *slot_gate, *partial;
+  int32_t* route_ticket;  // arrival counter of the router's fused grouping tail, zero between launches
   bool profiling;
-  std::vector<hipEvent_t> events;  // 6 per profiled layer-step
+  std::vector<hipEvent_t> events;  // kProfMarks per profiled layer-step
 };
 
 namespace {
 
-constexpr int kWaves = 4;  // waves per workgroup in the expert kernels
-constexpr int kDepth = 2;  // pipeline depth
+constexpr int kProfMarks = 5;  // events per profiled layer-step: route+group, gate/up, down, combine
+constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
+constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 
-long plan_waves(int ntiles, int R, int parts, int min_slots) {
-  return (long)((ntiles + R - 1) / R) * parts * min_slots;
+// Launch plan of the two expert kernels for one (T, weight layout).
+//   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
+//               deeper pipeline, same bytes in flight per wave)
+//   dn_KS       split-K factor of the down projection across workgroups
+// Chosen from measurements on Mixtral-shaped layers: tiled weights stream best with one tile per wave
+// and 8 k-steps in flight; the down projection wants about 4-5 thousand waves in the grid.
+struct Plan {
+  int gu_R, dn_R, dn_KS;
+};
+
+int ks_cap_for(const moe_shape& s) {
+  const int nsteps = s.ffn / 32;
+  int cap = 1;
+  while (cap < kMaxKS && nsteps / (kWaves * cap * 2) >= 4) cap *= 2;  // every wave keeps >= 4 k-steps
+  return cap;
 }
 
-// The grid must put enough waves on 256 CUs even when the fewest experts are live (T = 1), while
-// keeping R (weight tiles that share one activation fragment) as large as possible.
-void make_plan(moe_ctx* c) {
+Plan plan_for(const moe_ctx* c, int T, bool tiled) {
   const moe_shape& s = c->s;
-  const int min_slots = s.top_k + s.n_shared;
-  c->gu_R = 1;
-  for (int R : {4, 2})
-    if (plan_waves(s.ffn / 16, R, kWaves, min_slots) >= 1536) {
-      c->gu_R = R;
-      break;
-    }
-  // down: split K over KS workgroups x kWaves waves, every wave keeping >= 4 k-steps
-  const int nsteps = s.ffn / 32;
-  int ks_cap = 1;
-  while (ks_cap < 16 && nsteps / (kWaves * ks_cap * 2) >= 4) ks_cap *= 2;
-  c->dn_R = 1;
-  c->dn_KS = ks_cap;
+  // expected number of live expert slots for T tokens under uniform routing (balls into bins)
+  double miss = 1.0;
+  for (int t = 0; t < T; ++t) miss *= 1.0 - (double)s.top_k / s.n_experts;
+  const double slots = s.n_experts * (1.0 - miss) + s.n_shared;
+  Plan p;
+  p.gu_R = tiled ? 1 : ((s.ffn / 16 / 2) * kWaves * slots >= 1536 ? 2 : 1);
+  const int cap = ks_cap_for(s);
+  p.dn_R = 1;
+  p.dn_KS = cap;
   for (int R : {4, 2, 1}) {
+    const double per_ks = (double)((s.d / 16 + R - 1) / R) * kWaves * slots;
     int ks = 1;
-    while (ks < ks_cap && plan_waves(s.d / 16, R, kWaves * ks, min_slots) < 2048) ks *= 2;
-    if (plan_waves(s.d / 16, R, kWaves * ks, min_slots) >= 1536 || R == 1) {
-      c->dn_R = R;
-      c->dn_KS = ks;
+    while (ks < cap && per_ks * ks < 3584) ks *= 2;
+    if (per_ks * ks >= 3072 || R == 1) {
+      p.dn_R = R;
+      p.dn_KS = ks;
       break;
     }
   }
-  if (const char* env = getenv("MOE_PLAN")) {  // tuning override: "guR,dnR,dnKS"
-    int a = 0, b = 0, k = 0;
-    if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
-        k >= 1 && k <= 64) {
-      c->gu_R = a;
-      c->dn_R = b;
-      c->dn_KS = k;
-    }
+  if (c->plan_override[0] > 0) {
+    p.gu_R = c->plan_override[0];
+    p.dn_R = c->plan_override[1];
+    p.dn_KS = c->plan_override[2] < cap ? c->plan_override[2] : cap;
   }
+  return p;
 }
 
 moe_status check_stream_device(const moe_ctx* c) {
@@ -616,50 +763,58 @@ moe_status launch_route_group(moe_ctx* c, const float* hidden, const uint16_t* r
                               float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra,
                               hipStream_t st) {
   const moe_shape& s = c->s;
+  GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts,
+               GroupOut{c->unique, c->n_unique, c->count, c->offset, c->assign},
+               GroupOut{unique, n_unique, nullptr, nullptr, nullptr}, n_unique_extra, c->slot_expert, c->slot_gate};
   mark(c, st);
   hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, st, hidden, router_w, s.d, s.n_experts, s.top_k, c->ids,
-                     c->gates, ids, gates, c->xs_hi, c->xs_lo);
-  mark(c, st);
-  GroupOut ws{c->unique, c->n_unique, c->count, c->offset, c->assign};
-  GroupOut user{unique, n_unique, nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)c->ids, (const float*)c->gates, T,
-                     s.top_k, s.n_experts, ws, user, n_unique_extra, c->slot_expert, c->slot_gate);
+                     c->gates, ids, gates, c->xf_hi, c->xf_lo, c->route_ticket, ga);
   mark(c, st);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-template <int R>
-void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {
+// Tiled weights are read exactly once in contiguous 1 KB pieces -> streaming loads; row-major weights
+// are read in 64-byte row segments whose cache lines are completed by the next k-step -> cached loads.
+template <int R, int P>
+void launch_gateup(const moe_ctx* c, const GateupArgs& a, bool tiled, hipStream_t st) {
   const dim3 grid((c->s.ffn / 16 + R - 1) / R, c->u_tot);
-  hipLaunchKernelGGL((gateup_kernel<R, kWaves, kDepth>), grid, dim3(64 * kWaves), 0, st, a);
+  if (tiled)
+    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, true, true>), grid, dim3(64 * kWaves), 0, st, a);
+  else
+    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
-template <int R>
-void launch_down(const moe_ctx* c, const DownArgs& a, hipStream_t st) {
-  const dim3 grid((c->s.d / 16 + R - 1) / R, c->u_tot, c->dn_KS);
-  hipLaunchKernelGGL((down_kernel<R, kWaves, kDepth>), grid, dim3(64 * kWaves), 0, st, a);
+template <int R, int P>
+void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, hipStream_t st) {
+  const dim3 grid((c->s.d / 16 + R - 1) / R, c->u_tot, a.KS);
+  if (tiled)
+    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true>), grid, dim3(64 * kWaves), 0, st, a);
+  else
+    hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
 
 moe_status launch_experts(moe_ctx* c, const moe_layer_weights* w, int T, float* out, hipStream_t st) {
   const moe_shape& s = c->s;
-  GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, c->xs_hi, c->xs_lo, c->n_unique, c->slot_expert, c->slot_gate,
-                c->h_hi, c->h_lo, s.d, s.ffn, T, c->u_max, s.max_tokens};
-  switch (c->gu_R) {
-    case 4: launch_gateup<4>(c, ga, st); break;
-    case 2: launch_gateup<2>(c, ga, st); break;
-    default: launch_gateup<1>(c, ga, st); break;
+  const bool tiled = w->layout == MOE_LAYOUT_TILED;
+  const Plan p = plan_for(c, T, tiled);
+  GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
+                c->hf_hi, c->hf_lo, s.d, s.ffn, T, c->u_max};
+  switch (p.gu_R) {
+    case 4: launch_gateup<4, 2>(c, ga, tiled, st); break;
+    case 2: launch_gateup<2, 4>(c, ga, tiled, st); break;
+    default: launch_gateup<1, 8>(c, ga, tiled, st); break;
   }
   mark(c, st);
-  DownArgs da{w->w2, w->sw2, c->h_hi, c->h_lo, c->n_unique, c->slot_expert, c->slot_gate, c->partial,
-              s.d, s.ffn, T, c->u_max, s.max_tokens, c->dn_KS};
-  switch (c->dn_R) {
-    case 4: launch_down<4>(c, da, st); break;
-    case 2: launch_down<2>(c, da, st); break;
-    default: launch_down<1>(c, da, st); break;
+  DownArgs da{w->w2, w->sw2, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert, c->slot_gate, c->partial,
+              s.d, s.ffn, T, c->u_max, s.max_tokens, p.dn_KS};
+  switch (p.dn_R) {
+    case 4: launch_down<4, 3>(c, da, tiled, st); break;
+    case 2: launch_down<2, 4>(c, da, tiled, st); break;
+    default: launch_down<1, 8>(c, da, tiled, st); break;
   }
   mark(c, st);
   const int n4 = T * (s.d / 4);
   hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
-                     (const int32_t*)c->n_unique, out, s.d, T, c->u_max, s.n_shared, s.max_tokens, c->dn_KS);
+                     (const int32_t*)c->n_unique, out, s.d, T, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
   mark(c, st);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -669,6 +824,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // kernels use 128-bit loads: every tensor base must be 16-byte aligned (rows are, since d, ffn % 32 == 0)
 bool weights_ok(const moe_ctx* c, const moe_layer_weights* w) {
   if (!w || !w->router_w || !w->w1 || !w->w3 || !w->w2) return false;
+  if (w->layout != MOE_LAYOUT_ROW_MAJOR && w->layout != MOE_LAYOUT_TILED) return false;
   if (!aligned16(w->router_w) || !aligned16(w->w1) || !aligned16(w->w3) || !aligned16(w->w2)) return false;
   if (c->s.n_shared > 0) {
     if (!w->sw1 || !w->sw3 || !w->sw2) return false;
@@ -714,7 +870,17 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
   c->u_tot = c->u_max + s.n_shared;
-  make_plan(c);
+  c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
+  if (const char* env = getenv("MOE_PLAN")) {  // tuning override: "guR,dnR,dnKS"
+    int a = 0, b = 0, k = 0;
+    if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
+        k >= 1 && k <= kMaxKS) {
+      c->plan_override[0] = a;
+      c->plan_override[1] = b;
+      c->plan_override[2] = k;
+    }
+  }
+  c->ks_alloc = ks_cap_for(s);
 
   const size_t A = (size_t)s.max_tokens * s.top_k;
   size_t off = 0;
@@ -723,24 +889,25 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
     off = align_up(off + bytes, 256);
     return o;
   };
-  const size_t o_xh = carve((size_t)s.max_tokens * s.d * 2), o_xl = carve((size_t)s.max_tokens * s.d * 2);
-  const size_t o_hh = carve((size_t)c->u_tot * s.max_tokens * s.ffn * 2);
-  const size_t o_hl = carve((size_t)c->u_tot * s.max_tokens * s.ffn * 2);
+  const size_t o_xh = carve((size_t)s.d * kGateCols * 2), o_xl = carve((size_t)s.d * kGateCols * 2);
+  const size_t o_hh = carve((size_t)c->u_tot * s.ffn * kGateCols * 2);
+  const size_t o_hl = carve((size_t)c->u_tot * s.ffn * kGateCols * 2);
   const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_uni = carve((size_t)s.n_experts * 4);
   const size_t o_nu = carve(4), o_cnt = carve((size_t)s.n_experts * 4), o_off = carve((size_t)(s.n_experts + 1) * 4);
   const size_t o_asg = carve(A * 4), o_se = carve((size_t)c->u_max * 4);
   const size_t o_sg = carve((size_t)c->u_tot * kGateCols * 4);
-  const size_t o_part = carve((size_t)c->u_tot * c->dn_KS * s.max_tokens * s.d * 4);
+  const size_t o_tk = carve(4);
+  const size_t o_part = carve((size_t)c->u_tot * c->ks_alloc * s.max_tokens * s.d * 4);
   c->ws_bytes = off;
   if (hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
     return MOE_ERR_WORKSPACE;
   }
-  c->xs_hi = reinterpret_cast<uint16_t*>(c->ws + o_xh);
-  c->xs_lo = reinterpret_cast<uint16_t*>(c->ws + o_xl);
-  c->h_hi = reinterpret_cast<uint16_t*>(c->ws + o_hh);
-  c->h_lo = reinterpret_cast<uint16_t*>(c->ws + o_hl);
+  c->xf_hi = reinterpret_cast<uint16_t*>(c->ws + o_xh);
+  c->xf_lo = reinterpret_cast<uint16_t*>(c->ws + o_xl);
+  c->hf_hi = reinterpret_cast<uint16_t*>(c->ws + o_hh);
+  c->hf_lo = reinterpret_cast<uint16_t*>(c->ws + o_hl);
   c->ids = reinterpret_cast<int32_t*>(c->ws + o_ids);
   c->gates = reinterpret_cast<float*>(c->ws + o_gates);
   c->unique = reinterpret_cast<int32_t*>(c->ws + o_uni);
@@ -751,8 +918,9 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->slot_expert = reinterpret_cast<int32_t*>(c->ws + o_se);
   c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
   c->partial = reinterpret_cast<float*>(c->ws + o_part);
+  c->route_ticket = reinterpret_cast<int32_t*>(c->ws + o_tk);
   // small tables start at zero; shared-expert slots carry gate 1 for every token column
-  bool ok = hipMemset(c->ws + o_ids, 0, o_part - o_ids) == hipSuccess;
+  bool ok = hipMemset(c->ws, 0, c->ws_bytes) == hipSuccess;
   if (ok && s.n_shared > 0) {
     float ones[kMaxShared * kGateCols];
     for (int i = 0; i < s.n_shared * kGateCols; ++i) ones[i] = 1.f;
@@ -791,10 +959,9 @@ moe_status moe_group(moe_ctx* c, const int32_t* ids, int32_t T, int32_t* unique_
                      int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream) {
   if (!c || !ids || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
-  GroupOut none{nullptr, nullptr, nullptr, nullptr, nullptr};
-  GroupOut user{unique_experts, n_unique, expert_count, expert_offset, assign};
-  hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ids, (const float*)nullptr, T,
-                     c->s.top_k, c->s.n_experts, none, user, (int32_t*)nullptr, (int32_t*)nullptr, (float*)nullptr);
+  GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, GroupOut{nullptr, nullptr, nullptr, nullptr, nullptr},
+               GroupOut{unique_experts, n_unique, expert_count, expert_offset, assign}, nullptr, nullptr, nullptr};
+  hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ga);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -829,6 +996,36 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
   return MOE_OK;
 }
 
+moe_status moe_pack_weights(moe_ctx* c, const moe_layer_weights* src, moe_layer_weights* dst, void* stream) {
+  if (!c || !weights_ok(c, src) || src->layout != MOE_LAYOUT_ROW_MAJOR || !dst) return MOE_ERR_INVALID_ARG;
+  moe_layer_weights chk = *dst;
+  chk.layout = MOE_LAYOUT_ROW_MAJOR;
+  if (!weights_ok(c, &chk)) return MOE_ERR_INVALID_ARG;
+  if (moe_status st = check_stream_device(c)) return st;
+  const moe_shape& s = c->s;
+  hipStream_t st = (hipStream_t)stream;
+  auto pack = [&](const uint16_t* a, uint16_t* b, size_t rows, int K) {
+    const size_t units = rows * (size_t)(K / 8);
+    const unsigned blocks = (unsigned)((units + 255) / 256 < 65536 ? (units + 255) / 256 : 65536);
+    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<const uint4*>(a),
+                       reinterpret_cast<uint4*>(b), rows, K);
+  };
+  if (dst->router_w != src->router_w &&
+      hipMemcpyAsync(const_cast<uint16_t*>(dst->router_w), src->router_w, (size_t)s.n_experts * s.d * 2,
+                     hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return MOE_ERR_HIP;
+  pack(src->w1, const_cast<uint16_t*>(dst->w1), (size_t)s.n_experts * s.ffn, s.d);
+  pack(src->w3, const_cast<uint16_t*>(dst->w3), (size_t)s.n_experts * s.ffn, s.d);
+  pack(src->w2, const_cast<uint16_t*>(dst->w2), (size_t)s.n_experts * s.d, s.ffn);
+  if (s.n_shared > 0) {
+    pack(src->sw1, const_cast<uint16_t*>(dst->sw1), (size_t)s.n_shared * s.ffn, s.d);
+    pack(src->sw3, const_cast<uint16_t*>(dst->sw3), (size_t)s.n_shared * s.ffn, s.d);
+    pack(src->sw2, const_cast<uint16_t*>(dst->sw2), (size_t)s.n_shared * s.d, s.ffn);
+  }
+  dst->layout = MOE_LAYOUT_TILED;
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 moe_status moe_ctx_profile(moe_ctx* c, int32_t enable) {
   if (!c) return MOE_ERR_INVALID_ARG;
   c->profiling = enable != 0;
@@ -837,14 +1034,15 @@ moe_status moe_ctx_profile(moe_ctx* c, int32_t enable) {
 
 moe_status moe_ctx_profile_read(moe_ctx* c, double* ms_sum, int64_t* steps) {
   if (!c || !ms_sum || !steps) return MOE_ERR_INVALID_ARG;
-  for (int i = 0; i < 5; ++i) ms_sum[i] = 0.0;
-  const size_t n = c->events.size() / 6;
+  for (int i = 0; i < kProfMarks - 1; ++i) ms_sum[i] = 0.0;
+  const size_t n = c->events.size() / kProfMarks;
   moe_status rc = MOE_OK;
-  if (n > 0 && hipEventSynchronize(c->events[n * 6 - 1]) != hipSuccess) rc = MOE_ERR_HIP;
+  if (n > 0 && hipEventSynchronize(c->events[n * kProfMarks - 1]) != hipSuccess) rc = MOE_ERR_HIP;
   for (size_t i = 0; i < n && rc == MOE_OK; ++i)
-    for (int k = 0; k < 5; ++k) {
+    for (int k = 0; k < kProfMarks - 1; ++k) {
       float ms = 0.f;
-      if (hipEventElapsedTime(&ms, c->events[i * 6 + k], c->events[i * 6 + k + 1]) != hipSuccess) rc = MOE_ERR_HIP;
+      if (hipEventElapsedTime(&ms, c->events[i * kProfMarks + k], c->events[i * kProfMarks + k + 1]) != hipSuccess)
+        rc = MOE_ERR_HIP;
       ms_sum[k] += ms;
     }
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);

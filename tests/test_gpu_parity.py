@@ -28,7 +28,19 @@ def _weights_dev(W):
     return {k: _dev(v) for k, v in W.items()}
 
 
-def _run_layer(ctx, Wd, x, want_routing=True):
+_TILED_CACHE = {}
+
+
+def _tiled(ctx, Wd):
+    """Tiled copy of a layer's weights (made once per dict by moe_pack_weights)."""
+    key = (id(ctx), id(Wd))
+    if key not in _TILED_CACHE:
+        _TILED_CACHE.clear()
+        _TILED_CACHE[key] = ctx.moe_pack_weights(ctx.weights(Wd))
+    return _TILED_CACHE[key]
+
+
+def _run_layer(ctx, Wd, x, tiled=False):
     import torch
     s = ctx.shape
     T = x.shape[0]
@@ -38,7 +50,8 @@ def _run_layer(ctx, Wd, x, want_routing=True):
     gates = torch.zeros((T, s.top_k), dtype=torch.float32, device="cuda")
     uniq = torch.full((s.n_experts,), -7, dtype=torch.int32, device="cuda")
     nu = torch.full((1,), -7, dtype=torch.int32, device="cuda")
-    ctx.moe_verify_layer(ctx.weights(Wd), hid, out, ids, gates, uniq, nu)
+    lw = _tiled(ctx, Wd) if tiled else ctx.weights(Wd)
+    ctx.moe_verify_layer(lw, hid, out, ids, gates, uniq, nu)
     torch.cuda.synchronize()
     return out.cpu().numpy(), ids.cpu().numpy(), gates.cpu().numpy(), uniq.cpu().numpy(), int(nu.item())
 
@@ -77,6 +90,11 @@ def _check_layer(cfg_like, W, x, ctx=None, Wd=None):
     assert nu == u["n_unique"]
     np.testing.assert_array_equal(uniq, u["unique"])
     rel = _check_out(out, ref32, ref64)
+    # the tiled weight layout holds the same numbers in another order: identical arithmetic, identical bits
+    out_t, ids_t, gates_t, uniq_t, nu_t = _run_layer(ctx, Wd, x, tiled=True)
+    np.testing.assert_array_equal(ids_t, ids)
+    np.testing.assert_array_equal(out_t, out)
+    assert nu_t == nu
     if own:
         ctx.close()
     return out, rel
@@ -221,6 +239,27 @@ def test_layer_parity_mixtral_full_size():
     for it, (T, rho) in enumerate(((1, 0.5), (9, 0.0))):
         x = synth.hidden_host(cfg, 0, 300 + it, T, rho)
         _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0), W, x, ctx, Wd)
+    ctx.close()
+
+
+def test_pack_weights_layout_is_as_documented():
+    """Block (i, s) of the tiled matrix is rows 16i..16i+15 x columns 32s..32s+31; 16-byte unit l = r + 16 g
+    holds row 16i + r, columns 32s + 8g .. + 7."""
+    import torch
+    d, ffn, E = 64, 96, 3
+    rng = np.random.default_rng(7)
+    W = {n: rng.integers(0, 65536, size=shp, dtype=np.uint16) for n, shp in
+         (("router_w", (E, d)), ("w1", (E, ffn, d)), ("w3", (E, ffn, d)), ("w2", (E, d, ffn)))}
+    ctx = binding.MoeContext(d, ffn, E, 2, 0, 4)
+    Wd = _weights_dev(W)
+    packed = ctx.moe_pack_weights(ctx.weights(Wd))
+    torch.cuda.synchronize()
+    assert packed.c.layout == 1
+    for idx, name, rows, K in ((1, "w1", E * ffn, d), (2, "w3", E * ffn, d), (3, "w2", E * d, ffn)):
+        got = packed.tensors[idx].cpu().numpy().view(np.uint16).reshape(-1)
+        src = W[name].reshape(rows, K)
+        want = src.reshape(rows // 16, 16, K // 32, 4, 8).transpose(0, 2, 3, 1, 4).reshape(-1)   # [i][s][g][r][8]
+        np.testing.assert_array_equal(got, want)
     ctx.close()
 
 
