@@ -130,6 +130,14 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_us": round(gu_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(gu_bytes_per_launch),
                 "kernel_us_per_step": {k: round(v / max(n_prof, 1) * 1e3, 2) for k, v in kms.items()}}
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same default
+    # workload (summary committed under profiles/); reported only when the run matches that workload
+    traffic_file = os.path.join(ROOT, "profiles", "gateup_kernel_mixtral_hbm_traffic.txt")
+    if (cfg is synth.MIXTRAL and args.layout == "tiled" and args.rho == 0.5 and args.fixed_k < 0 and L == 8
+            and K_steps == 180 and os.path.exists(traffic_file)):
+        for line in open(traffic_file):
+            if line.startswith("traffic_bytes_per_launch gateup_kernel"):
+                roofline["traffic"] = int(line.split()[-1])
     dn_bytes = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * cfg.d * cfg.ffn * 2
     roofline["down_kernel_GBps"] = round(dn_bytes / (kms["down"] / max(n_prof, 1) * 1e-3) / 1e9, 1)
 
@@ -152,7 +160,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as orc
         Wh = synth.layer_weights_host(cfg, 0)
-        sample_T = (1, 5) if cfg is synth.MIXTRAL else (1, 9)
+        sample_T = tuple(range(1, T_MAX + 1))
         cbytes, csec = 0, 0.0
         for T in sample_T:
             x = synth.hidden_host(cfg, 0, 10_000 + T, T, args.rho)
