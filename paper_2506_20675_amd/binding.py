@@ -60,6 +60,9 @@ def lib():
         return _LIB
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built. Run: python -c 'import __graft_entry__ as g; g.build()'")
+    # torch owns the device memory handed to the library, so both must sit on ONE HIP runtime: import
+    # torch first, so that the library's libamdhip64 dependency resolves to the copy torch has loaded
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     L.moe_strerror.restype = ctypes.c_char_p
     L.moe_strerror.argtypes = [ctypes.c_int]

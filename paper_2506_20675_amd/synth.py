@@ -270,6 +270,7 @@ def _load_synth_lib():
         path = synth_lib_path()
         if not os.path.exists(path):
             raise RuntimeError(f"{path} not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        import torch  # noqa: F401  (one HIP runtime per process: let torch load its copy first)
         lib = ctypes.CDLL(path)
         lib.synth_fill_bf16.restype = ctypes.c_int
         lib.synth_fill_bf16.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,

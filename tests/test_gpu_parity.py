@@ -312,3 +312,23 @@ def test_argument_errors_are_reported_not_launched():
     with pytest.raises(ValueError):
         ctx.moe_route(x[:2, :32].contiguous(), rw)
     ctx.close()
+
+
+def test_stack_driver_decisions_replay_on_the_policy_oracle():
+    """The decode loop on a small stack: measured t_verify feeds the C controller; replaying the recorded
+    (K, tokens, time) trace through the Python policy oracle must give the same K at every iteration."""
+    from oracle import cascade_oracle as co
+    from paper_2506_20675_amd import stack_driver
+    cfg = synth.TINY
+    summary, recs = stack_driver.run(cfg, layers=4, iters=160, rho=0.5, layout="tiled")
+    ref = co.Controller()
+    for r in recs:
+        assert ref.next_k() == r["K"], r
+        assert 1 <= r["tokens"] <= r["K"] + 1
+        ref.observe(r["K"], r["tokens"], r["t_verify_ms"] * 1e-3)
+    assert summary["iters"] == 160 and summary["tokens"] >= 160
+    assert [r["K"] for r in recs[:4]] == [0, 0, 0, 0] and recs[4]["K"] == 3
+    assert all(2 <= r["mean_unique"] <= 8 for r in recs)
+    # a static-K run uses the same trace
+    s3, recs3 = stack_driver.run(cfg, layers=4, iters=40, rho=0.5, layout="row", static_k=3)
+    assert s3["K_histogram"] == {"3": 40}
