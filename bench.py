@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE verification path on one MI355X.
 
-A "step" is one pass of the whole hot path (route + group -> gate/up -> down + combine, i.e. one
+A "step" is one pass of the whole hot path (route -> group + gate/up -> down -> combine, i.e. one
 moe_verify_layer call) over one batch of T = K+1 synthetic tokens on a Mixtral-8x7B-shaped layer.
 Step i uses K = i mod 9 (so every sweep K = 0..8 is timed equally often) and layer i mod L of L
 distinct resident layers, so consecutive steps never re-read weights that could still sit in the

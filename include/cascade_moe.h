@@ -143,8 +143,8 @@ moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32
                             int32_t T, float* out, int32_t* n_unique_per_layer_opt, void* stream);
 
 /* Measurement aid: per-kernel timing.  While enabled, every moe_verify_layer / moe_verify_stack
- * layer records HIP events on its stream around each of its four kernels (route+group, gate/up, down,
- * combine); this adds event packets between the kernels, so whole-step latency is measured with
+ * layer records HIP events on its stream around each of its four kernels (route, gate/up with the
+ * expert-union step, down, combine); this adds event packets between the kernels, so whole-step latency is measured with
  * profiling OFF.
  * moe_ctx_profile_read waits for the recorded events, adds the elapsed times into ms_sum[0..3]
  * (HOST, milliseconds, same kernel order), stores the number of layer-steps in

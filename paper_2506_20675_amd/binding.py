@@ -197,7 +197,7 @@ class MoeContext:
         return LayerWeights(self.shape, W["router_w"], W["w1"], W["w3"], W["w2"], W.get("sw1"), W.get("sw3"),
                             W.get("sw2"))
 
-    KERNELS = ("route_group", "gateup", "down", "combine")
+    KERNELS = ("route", "gateup", "down", "combine")
 
     def moe_ctx_profile(self, enable: bool) -> None:
         _check(lib().moe_ctx_profile(self._h, 1 if enable else 0), "moe_ctx_profile")

@@ -5,14 +5,13 @@
 // HBM traffic for the UNION of the picked experts (Section 1, Section 2.4).  The path below touches
 // every unique expert's weights exactly once per step:
 //
-//   route_kernel   router logits (fp64 accumulate), top-k, softmax gates; splits the fp32 activations
-//                  into bf16 hi + lo fragments for the matrix cores; its last-finishing workgroup
-//                  builds the union of experts, the per-expert token lists and the per-slot gate table
-//   gateup_kernel  for each unique expert: G = w1 X, U = w3 X, H = gate * silu(G) * U      (2/3 of bytes)
-//   down_kernel    split-K partial sums of w2 H over (expert, k-chunk)                     (1/3 of bytes);
-//                  the last-finishing workgroup of each row block adds the slabs in a fixed order into
-//                  out (gate-weighted combine, deterministic, no floating-point atomics)
-//   (group_kernel  the grouping step alone, for callers that bring their own routing)
+//   route_kernel   one workgroup per token: router logits (fp64 accumulate), top-k, softmax gates, and
+//                  the bf16 hi + lo activation fragments for the matrix cores
+//   group_kernel   union of experts, per-expert token lists, slot tables for the expert kernels (for a
+//                  single token, T = 1, route_kernel does this itself and the launch is skipped)
+//   gateup_kernel  for each slot of the union: G = w1 X, U = w3 X, H = gate * silu(G) * U   (2/3 of bytes)
+//   down_kernel    split-K partial sums of w2 H over (slot, k-chunk)                        (1/3 of bytes)
+//   combine_kernel out[t] = sum of the live slabs in slot order (deterministic, no atomics)
 //
 // The two FFN kernels are skinny GEMMs (at most 16 token columns) and purely HBM-bound.  They use
 // v_mfma_f32_16x16x32_bf16 with the weight tile as the A operand: lane l holds 8 consecutive k of
@@ -70,19 +69,6 @@ __device__ __forceinline__ uint4 ld128(const char* base, uint32_t byte_off) {
   }
 }
 
-// Hand-off of a few words from one workgroup to another INSIDE a launch (the router's "last workgroup
-// builds the expert union" tail).  The words are written and read with relaxed agent-scope atomics,
-// which write through / read past the per-XCD caches, so no cache-wide writeback or invalidate is
-// needed (a full agent-scope fence costs far more than the data it protects here); the producer only
-// has to wait until its stores have been acknowledged before it takes its ticket.
-// Producer side: all of this thread's earlier stores are acknowledged, and neither the compiler nor the
-// hardware moves later accesses above this point.  Consumer side: the mirror image.
-__device__ __forceinline__ void handoff_release() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0);
-}
-__device__ __forceinline__ void handoff_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
-
 // Activation fragments.  The MFMA B operand of k-step s (32 k) wants, in lane (n = l%16, kg = l/16),
 // the 8 values k = 32 s + 8 kg .. +7 of token column n.  Activations are therefore stored in that
 // order — unit q = s*64 + kg*16 + n holds those 8 bf16 (16 bytes) — so a wave fetches the whole
@@ -97,40 +83,32 @@ __device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 2: union of activated experts + per-expert token lists.  One workgroup, thread e = expert e.
+// Step 2 as a launch of its own (moe_route / moe_group): union of activated experts + per-expert token
+// lists.  One workgroup, thread e = expert e.
 // ------------------------------------------------------------------------------------------
-struct GroupOut {
-  int32_t *unique, *n_unique, *count, *offset, *assign;
-};
 struct GroupArgs {
   const int32_t* ids;   // [T, top_k]
   const float* gates;   // [T, top_k] or NULL (then no gate table is built)
   int T, top_k, E;
-  GroupOut ws, user;    // every pointer optional
-  int32_t* n_unique_extra;
-  int32_t* slot_expert;  // [u_max] expert of unique slot u
-  float* slot_gate;      // [u_max, 16] gate of token column n for slot u, 0 = not routed
+  int32_t *unique, *n_unique, *count, *offset, *assign;     // caller-visible outputs, each optional
+  int32_t *n_unique_ws, *n_unique_extra, *slot_expert;      // tables for the expert kernels, each optional
+  float* slot_gate;                                         // [u_max, 16]
 };
 
-// Executed by one whole 256-thread workgroup.  ids/gates may have been written by other workgroups of
-// the same launch: they are read with agent-scope atomic loads, which never hit a stale cache line.
-__device__ void group_body(const GroupArgs& g) {
-  __shared__ int s_ids[kMaxTokens * kMaxTopK];
+// Executed by the first 256 threads of a workgroup (all of them reach the two barriers inside, so the
+// caller must let EVERY thread of the block call it).  s_ids: the routing in LDS, or NULL to read g.ids.
+__device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float* s_gates_in) {
+  __shared__ int s_ids_own[kMaxTokens * kMaxTopK];
   __shared__ int s_cnt[4], s_uni[4];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int T = g.T, top_k = g.top_k, E = g.E;
-  const GroupOut& ws = g.ws;
-  const GroupOut& user = g.user;
-  const float* gates = g.gates;
-  int32_t* slot_expert = g.slot_expert;
-  float* slot_gate = g.slot_gate;
-  int32_t* n_unique_extra = g.n_unique_extra;
-  const int A = T * top_k;
-  if (tid < A) s_ids[tid] = __hip_atomic_load(g.ids + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int E = g.E, A = g.T * g.top_k;
+  const int* s_ids = s_ids_in ? s_ids_in : s_ids_own;
+  if (!s_ids_in && tid < A) s_ids_own[tid] = g.ids[tid];
   __syncthreads();
+  const bool act = tid < 256;
   const int e = tid;
   int cnt = 0;
-  if (e < E)
+  if (act && e < E)
     for (int a = 0; a < A; ++a) cnt += (s_ids[a] == e);
   const int flag = cnt > 0;
   // inclusive scan of cnt inside the wave, ballot for the unique rank
@@ -142,9 +120,10 @@ __device__ void group_body(const GroupArgs& g) {
   }
   const unsigned long long bal = __ballot(flag);
   const int rank_in_wave = __popcll(bal & ((1ull << lane) - 1ull));
-  if (lane == 63) s_cnt[wave] = incl;
-  if (lane == 0) s_uni[wave] = __popcll(bal);
+  if (act && lane == 63) s_cnt[wave] = incl;
+  if (act && lane == 0) s_uni[wave] = __popcll(bal);
   __syncthreads();
+  if (!act) return;
   int cbase = 0, ubase = 0, n_unique = 0, total = 0;
   for (int w = 0; w < 4; ++w) {
     if (w < wave) {
@@ -157,70 +136,60 @@ __device__ void group_body(const GroupArgs& g) {
   const int off = cbase + incl - cnt;
   const int rank = ubase + rank_in_wave;
   if (e < E) {
-    if (ws.count) ws.count[e] = cnt;
-    if (ws.offset) ws.offset[e] = off;
-    if (user.count) user.count[e] = cnt;
-    if (user.offset) user.offset[e] = off;
+    if (g.count) g.count[e] = cnt;
+    if (g.offset) g.offset[e] = off;
     if (flag) {
-      if (ws.unique) ws.unique[rank] = e;
-      if (user.unique) user.unique[rank] = e;
-      if (slot_expert) slot_expert[rank] = e;
+      if (g.unique) g.unique[rank] = e;
+      if (g.slot_expert) g.slot_expert[rank] = e;
       float row[kGateCols];
 #pragma unroll
       for (int n = 0; n < kGateCols; ++n) row[n] = 0.f;
       int j = 0;
       for (int a = 0; a < A; ++a)
         if (s_ids[a] == e) {
-          if (ws.assign) ws.assign[off + j] = a;
-          if (user.assign) user.assign[off + j] = a;
+          if (g.assign) g.assign[off + j] = a;
           ++j;
-          if (gates) {
-            const int tok = a / top_k;
-            const float gv = __hip_atomic_load(gates + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (g.gates || s_gates_in) {
+            const int tok = a / g.top_k;
+            const float gv = s_gates_in ? s_gates_in[a] : g.gates[a];
 #pragma unroll
             for (int n = 0; n < kGateCols; ++n)
               if (n == tok) row[n] = gv;
           }
         }
-      if (slot_gate && gates) {
+      if (g.slot_gate && (g.gates || s_gates_in)) {
 #pragma unroll
-        for (int n = 0; n < kGateCols; ++n) slot_gate[rank * kGateCols + n] = row[n];
+        for (int n = 0; n < kGateCols; ++n) g.slot_gate[rank * kGateCols + n] = row[n];
       }
     }
-    if (e >= n_unique) {
-      if (ws.unique) ws.unique[e] = -1;
-      if (user.unique) user.unique[e] = -1;
-    }
+    if (e >= n_unique && g.unique) g.unique[e] = -1;
   }
   if (tid == 0) {
-    if (ws.offset) ws.offset[E] = total;
-    if (user.offset) user.offset[E] = total;
-    if (ws.n_unique) *ws.n_unique = n_unique;
-    if (user.n_unique) *user.n_unique = n_unique;
-    if (n_unique_extra) *n_unique_extra = n_unique;
+    if (g.offset) g.offset[E] = total;
+    if (g.n_unique) *g.n_unique = n_unique;
+    if (g.n_unique_ws) *g.n_unique_ws = n_unique;
+    if (g.n_unique_extra) *g.n_unique_extra = n_unique;
   }
 }
 
-__global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g); }
+__global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g, nullptr, nullptr); }
 
 // ------------------------------------------------------------------------------------------
-// Step 1: router.  One workgroup (4 waves) per token.
+// Step 1: router.  Building blocks shared by the two launch shapes below.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hidden,
-                                                    const uint16_t* __restrict__ router_w, int d, int E, int top_k,
-                                                    int32_t* __restrict__ ids_ws, float* __restrict__ gates_ws,
-                                                    int32_t* __restrict__ ids_out, float* __restrict__ gates_out,
-                                                    uint16_t* __restrict__ xs_hi, uint16_t* __restrict__ xs_lo,
-                                                    int32_t* __restrict__ ticket, GroupArgs grp) {
-  __shared__ double s_logit[kMaxExperts];
-  __shared__ float s_sel[kMaxTopK];
-  __shared__ int s_id[kMaxTopK];
-  __shared__ int s_last;
-  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const float* x = hidden + (size_t)t * d;
+struct RouteArgs {
+  const float* hidden;       // [T, d]
+  const uint16_t* router_w;  // [E, d]
+  int d, E, top_k, T;
+  int32_t *ids_ws, *ids_out;  // [T, top_k]; *_out optional
+  float *gates_ws, *gates_out;
+  uint16_t *xf_hi, *xf_lo;    // activation fragments
+};
 
-  // activations -> bf16 hi/lo halves in fragment order, consumed by the expert kernels as the MFMA B operand
-  for (int k8 = tid; k8 < (d >> 3); k8 += 256) {
+// activations of token t -> bf16 hi/lo halves in fragment order (the MFMA B operand of the expert kernels)
+__device__ __forceinline__ void split_token(const float* __restrict__ x, int d, int t, int first, int stride,
+                                            uint16_t* __restrict__ xf_hi, uint16_t* __restrict__ xf_lo) {
+  for (int k8 = first; k8 < (d >> 3); k8 += stride) {
     const float4 v0 = *reinterpret_cast<const float4*>(x + k8 * 8);
     const float4 v1 = *reinterpret_cast<const float4*>(x + k8 * 8 + 4);
     const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
@@ -234,35 +203,65 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hi
       l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
     }
     const size_t q = frag_unit(k8, t);
-    reinterpret_cast<uint4*>(xs_hi)[q] = uint4{h[0], h[1], h[2], h[3]};
-    reinterpret_cast<uint4*>(xs_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
+    reinterpret_cast<uint4*>(xf_hi)[q] = uint4{h[0], h[1], h[2], h[3]};
+    reinterpret_cast<uint4*>(xf_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
   }
+}
 
-  // logits in fp64: fp32 x bf16 products are exact in double, so the top-k decision does not
-  // depend on the order of summation (beyond ~1e-13 relative)
-  for (int e = wave; e < E; e += 4) {
-    const uint16_t* w = router_w + (size_t)e * d;
-    double acc = 0.0;
-    for (int j = lane * 8; j < d; j += 64 * 8) {
-      const uint4 wv = *reinterpret_cast<const uint4*>(w + j);
+// One wave's share of the logits of one token: the wave owns the 512-element chunks c = first_chunk,
+// first_chunk + chunk_stride, ... of d and, per trip, issues the 2 activation loads and the loads of up
+// to EMAX expert rows TOGETHER (independent loads, one round trip) instead of walking expert after
+// expert through dependent round trips.  Accumulation in fp64: fp32 x bf16 products are exact in
+// double, so the top-k decision does not depend on the order of summation (beyond ~1e-13 relative).
+// The wave's partial sum for expert e0 + e goes to s_part[e0 + e] (written by lane 0).
+template <int EMAX>
+__device__ __forceinline__ void partial_logits_wave(const float* __restrict__ x, const uint16_t* __restrict__ router_w,
+                                                    int d, int E, int lane, int first_chunk, int chunk_stride,
+                                                    double* s_part) {
+  for (int e0 = 0; e0 < E; e0 += EMAX) {
+    const int ne = min(EMAX, E - e0);
+    double acc[EMAX];
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) acc[e] = 0.0;
+    for (int j = lane * 8 + first_chunk * 512; j < d; j += chunk_stride * 512) {
       const float4 x0 = *reinterpret_cast<const float4*>(x + j);
       const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
-      acc = fma((double)x0.x, (double)bf16_to_f32(wv.x & 0xffffu), acc);
-      acc = fma((double)x0.y, (double)bf16_to_f32(wv.x >> 16), acc);
-      acc = fma((double)x0.z, (double)bf16_to_f32(wv.y & 0xffffu), acc);
-      acc = fma((double)x0.w, (double)bf16_to_f32(wv.y >> 16), acc);
-      acc = fma((double)x1.x, (double)bf16_to_f32(wv.z & 0xffffu), acc);
-      acc = fma((double)x1.y, (double)bf16_to_f32(wv.z >> 16), acc);
-      acc = fma((double)x1.z, (double)bf16_to_f32(wv.w & 0xffffu), acc);
-      acc = fma((double)x1.w, (double)bf16_to_f32(wv.w >> 16), acc);
+      uint4 wv[EMAX];
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e)
+        if (e < ne) wv[e] = *reinterpret_cast<const uint4*>(router_w + (size_t)(e0 + e) * d + j);
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e)
+        if (e < ne) {
+          double a = acc[e];
+          a = fma((double)x0.x, (double)bf16_to_f32(wv[e].x & 0xffffu), a);
+          a = fma((double)x0.y, (double)bf16_to_f32(wv[e].x >> 16), a);
+          a = fma((double)x0.z, (double)bf16_to_f32(wv[e].y & 0xffffu), a);
+          a = fma((double)x0.w, (double)bf16_to_f32(wv[e].y >> 16), a);
+          a = fma((double)x1.x, (double)bf16_to_f32(wv[e].z & 0xffffu), a);
+          a = fma((double)x1.y, (double)bf16_to_f32(wv[e].z >> 16), a);
+          a = fma((double)x1.z, (double)bf16_to_f32(wv[e].w & 0xffffu), a);
+          a = fma((double)x1.w, (double)bf16_to_f32(wv[e].w >> 16), a);
+          acc[e] = a;
+        }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) s_logit[e] = acc;
+    for (int e = 0; e < EMAX; ++e)
+      if (e < ne) {
+        double a = acc[e];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+        if (lane == 0) s_part[e0 + e] = a;
+      }
   }
-  __syncthreads();
-  if (wave == 0) {
-  // top-k by repeated wave-wide arg-max; ties go to the lower expert index
+}
+
+// One wave: top-k of E logits (in LDS) by repeated wave-wide arg-max, ties to the lower expert index;
+// gates = softmax over the selected logits in fp32, summed in slot order.  Lane 0 writes the token's
+// ids and gates to global memory and, if given, to the LDS copies s_ids / s_gates.
+__device__ __forceinline__ void topk_gates_wave(const double* s_logit, const RouteArgs& g, int t, int lane,
+                                                int* s_ids, float* s_gates) {
+  const int E = g.E, top_k = g.top_k;
   double v[kMaxExperts / 64];
 #pragma unroll
   for (int q = 0; q < kMaxExperts / 64; ++q) {
@@ -272,6 +271,8 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hi
     v[q] = lv;
   }
   unsigned taken = 0;
+  int sel_id = 0;      // lane i < top_k keeps the i-th pick
+  float sel_l = 0.f;
   for (int i = 0; i < top_k; ++i) {
     double bv = -INFINITY;
     int be = INT_MAX;
@@ -293,42 +294,49 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ hi
       }
     }
     if ((be & 63) == lane) taken |= 1u << (be >> 6);
-    if (lane == 0) {
-      s_id[i] = be;
-      s_sel[i] = (float)bv;
+    if (lane == i) {
+      sel_id = be;
+      sel_l = (float)bv;
     }
   }
-  if (lane == 0) {
-    // gates = softmax over the selected logits, summed in slot order
-    float p[kMaxTopK];
-    const float l0 = s_sel[0];
-    float sum = 0.f;
-    for (int i = 0; i < top_k; ++i) {
-      p[i] = expf(s_sel[i] - l0);
-      sum += p[i];
+  // softmax over the picks: p_i = exp(l_i - l_0), sum in slot order (lane 0 adds them up one by one)
+  const float l0 = __shfl(sel_l, 0);
+  const float p = lane < top_k ? expf(sel_l - l0) : 0.f;
+  float sum = 0.f;
+  for (int i = 0; i < top_k; ++i) sum += __shfl(p, i);
+  if (lane < top_k) {
+    const float gate = p / sum;
+    const int a = t * top_k + lane;
+    g.ids_ws[a] = sel_id;
+    g.gates_ws[a] = gate;
+    if (g.ids_out) g.ids_out[a] = sel_id;
+    if (g.gates_out) g.gates_out[a] = gate;
+    if (s_ids) {
+      s_ids[a] = sel_id;
+      s_gates[a] = gate;
     }
-    for (int i = 0; i < top_k; ++i) {
-      const float g = p[i] / sum;
-      const int a = t * top_k + i;
-      __hip_atomic_store(ids_ws + a, s_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(gates_ws + a, g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (ids_out) ids_out[a] = s_id[i];
-      if (gates_out) gates_out[a] = g;
-    }
-    handoff_release();  // this token's routing is out before the ticket is taken
   }
-  }  // wave 0
+}
 
-  // Step 2 rides in the same launch: the workgroup that finishes last sees every token's routing
-  // and builds the expert union and the per-slot tables (fixed order -> deterministic).
+// One workgroup (4 waves) per token: the waves split d, their partial logits meet in LDS, wave 0 does
+// the top-k and the gates.  With a single token in flight (T = 1, no speculation) that one workgroup
+// already sees the whole routing, so the expert-union step runs right here; with more tokens it
+// needs the launch of its own that follows (group_kernel).
+__global__ __launch_bounds__(256) void route_kernel(RouteArgs g, GroupArgs grp) {
+  __shared__ double s_part[4][kMaxExperts];
+  __shared__ double s_logit[kMaxExperts];
+  __shared__ int s_ids[kMaxTopK];
+  __shared__ float s_gates[kMaxTopK];
+  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* x = g.hidden + (size_t)t * g.d;
+  partial_logits_wave<16>(x, g.router_w, g.d, g.E, lane, wave, 4, s_part[wave]);
+  split_token(x, g.d, t, tid, 256, g.xf_hi, g.xf_lo);
   __syncthreads();
-  if (tid == 0)
-    s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1;
+  for (int e = tid; e < g.E; e += 256) s_logit[e] = ((s_part[0][e] + s_part[1][e]) + s_part[2][e]) + s_part[3][e];
   __syncthreads();
-  if (!s_last) return;
-  handoff_acquire();
-  group_body(grp);
-  if (tid == 0) *ticket = 0;  // ready for the next launch on this stream
+  const bool alone = gridDim.x == 1;
+  if (wave == 0) topk_gates_wave(s_logit, g, t, lane, alone ? s_ids : nullptr, alone ? s_gates : nullptr);
+  if (alone) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
 }
 
 // ------------------------------------------------------------------------------------------
@@ -395,34 +403,38 @@ struct WeightAddr {
 
 // ------------------------------------------------------------------------------------------
 // Step 3: gate/up projections + SiLU*mul for every unique expert (and shared expert).
-// grid = (row blocks of 16*R rows of ffn, expert slots); block = W waves that split d.
+// grid = (row blocks of 16*R rows of ffn, min(E, T*top_k) + n_shared slots); block = W waves that split d.
 // ------------------------------------------------------------------------------------------
 struct GateupArgs {
   const uint16_t *w1, *w3, *sw1, *sw3;  // [E,ffn,d] / [n_shared,ffn,d]
   const uint16_t *xf_hi, *xf_lo;        // activation fragments, d*16 elements each
-  const int32_t* n_unique;
-  const int32_t* slot_expert;  // [u_max]
-  const float* slot_gate;      // [u_tot,16]
-  uint16_t *hf_hi, *hf_lo;     // [u_tot] fragments of gate*silu(G)*U, ffn*16 elements each
-  int d, ffn, T, u_max;
+  const int32_t* n_unique;              // [1]        size of the union                   } written by the
+  const int32_t* slot_expert;           // [u_max]    expert of slot u (ascending)        } grouping step
+  const float* slot_gate;               // [u_max+n_shared, 16] gate of token column n, 0 = not routed
+  uint16_t *hf_hi, *hf_lo;              // [u_max + n_shared] fragments of gate*silu(G)*U, ffn*16 elements each
+  int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
 };
 
 template <int R, int W, int P, bool TILED, bool NT>
 __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
-  const int u = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const char *W1, *W3;
   const size_t per = (size_t)g.ffn * g.d * 2;
-  if (u < g.u_max) {
-    if (u >= *g.n_unique) return;
-    const int e = g.slot_expert[u];
+  float gate;
+  int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
+  if (slot < g.routed_slots) {
+    if (slot >= *g.n_unique) return;  // beyond the union of this step
+    const int e = g.slot_expert[slot];
+    gate = g.slot_gate[slot * kGateCols + r];
     W1 = reinterpret_cast<const char*>(g.w1) + e * per;
     W3 = reinterpret_cast<const char*>(g.w3) + e * per;
   } else {
-    W1 = reinterpret_cast<const char*>(g.sw1) + (u - g.u_max) * per;
-    W3 = reinterpret_cast<const char*>(g.sw3) + (u - g.u_max) * per;
+    gate = 1.f;  // shared expert: every token, gate 1
+    W1 = reinterpret_cast<const char*>(g.sw1) + (slot - g.routed_slots) * per;
+    W3 = reinterpret_cast<const char*>(g.sw3) + (slot - g.routed_slots) * per;
+    slot = g.u_max + (slot - g.routed_slots);  // buffers keep shared experts after the largest union
   }
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int ntiles = g.ffn >> 4, tile0 = blockIdx.x * R;
   const int nsteps = g.d >> 5, chunk = (nsteps + W - 1) / W;
   const int nst = max(0, min(chunk, nsteps - wave * chunk));
@@ -449,29 +461,14 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       [&](Stage<2 * R>& st, int s) {
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
-#ifdef MOE_EXPERIMENT_NO_B
-        st.bh = ld128<false>(XH, b_off);
-        st.bl = ld128<false>(XL, b_off);
-#else
         st.bh = ld128<false>(XH, b_off + (uint32_t)s * 1024);
         st.bl = ld128<false>(XL, b_off + (uint32_t)s * 1024);
-#endif
       },
       [&](const Stage<2 * R>& st) {
-#ifdef MOE_EXPERIMENT_NO_MFMA
-#pragma unroll
-        for (int j = 0; j < 2 * R; ++j) {
-          acc[j][0] += __uint_as_float((st.a[j].x ^ st.bh.x) & 0x3fffffffu);
-          acc[j][1] += __uint_as_float((st.a[j].y ^ st.bl.y) & 0x3fffffffu);
-          acc[j][2] += __uint_as_float((st.a[j].z ^ st.bh.z) & 0x3fffffffu);
-          acc[j][3] += __uint_as_float((st.a[j].w ^ st.bl.w) & 0x3fffffffu);
-        }
-#else
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh, acc[j]);
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl, acc[j]);
-#endif
       });
 
   // reduce the W k-slices through LDS, then wave w finishes tiles w, w+W, ...
@@ -481,9 +478,8 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       red[(wave * 2 * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
     __syncthreads();
   }
-  const float gate = g.slot_gate[u * kGateCols + r];
-  uint16_t* HH = g.hf_hi + (size_t)u * g.ffn * 16;
-  uint16_t* HL = g.hf_lo + (size_t)u * g.ffn * 16;
+  uint16_t* HH = g.hf_hi + (size_t)slot * g.ffn * 16;
+  uint16_t* HL = g.hf_lo + (size_t)slot * g.ffn * 16;
 #pragma unroll
   for (int j = 0; j < R; ++j) {
     if (j % W != wave || tile0 + j >= ntiles) continue;
@@ -510,40 +506,48 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       split_bf16(gate * (G.w / (1.f + expf(-G.w))) * U.w, hi[3], lo[3]);
       const int k = (tile0 + j) * 16 + kg * 4;
       const size_t o = frag_unit(k >> 3, r) * 8 + (k & 4);
-      *reinterpret_cast<uint2*>(HH + o) = uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-      *reinterpret_cast<uint2*>(HL + o) = uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+      *reinterpret_cast<uint2*>(HH + o) =
+          uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+      *reinterpret_cast<uint2*>(HL + o) =
+          uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 4: down projection, split-K over (expert slot, k-chunk).  The gate is already folded into H,
-// so every slab is a plain partial sum of out.
-// grid = (row blocks of 16*R rows of d, expert slots, KS k-chunks); block = W waves splitting the chunk.
+// Step 4: down projection, split-K over (expert, k-chunk).  The gate is already folded into H, so
+// every slab is a plain partial sum of out.
+// grid = (row blocks of 16*R rows of d, min(E, T*top_k) + n_shared slots, KS k-chunks); block = W waves
+// splitting the chunk.
 // ------------------------------------------------------------------------------------------
 struct DownArgs {
-  const uint16_t *w2, *sw2;      // [E,d,ffn] / [n_shared,d,ffn]
-  const uint16_t *hf_hi, *hf_lo; // [u_tot] fragments, ffn*16 elements each
+  const uint16_t *w2, *sw2;       // [E,d,ffn] / [n_shared,d,ffn]
+  const uint16_t *hf_hi, *hf_lo;  // [u_max + n_shared] fragments, ffn*16 elements each
   const int32_t* n_unique;
   const int32_t* slot_expert;
   const float* slot_gate;
-  float* partial;                // [u_tot*KS, max_tokens, d]
-  int d, ffn, T, u_max, max_tokens, KS;
+  float* partial;                 // [(u_max + n_shared)*KS, max_tokens, d]
+  int d, ffn, T, routed_slots, u_max, max_tokens, KS;
 };
 
 template <int R, int W, int P, bool TILED, bool NT>
 __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   __shared__ float4 red[W > 1 ? W * R * 64 : 1];
-  const int u = blockIdx.y, ks = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int ks = blockIdx.z;
+  int slot = blockIdx.y;
   const char* W2;
   const size_t per = (size_t)g.ffn * g.d * 2;
-  if (u < g.u_max) {
-    if (u >= *g.n_unique) return;
-    W2 = reinterpret_cast<const char*>(g.w2) + g.slot_expert[u] * per;
+  bool live;  // token column r contributes only if the token is routed to this expert
+  if (slot < g.routed_slots) {
+    if (slot >= *g.n_unique) return;
+    live = g.slot_gate[slot * kGateCols + r] != 0.f;  // 0 also for the padded columns r >= T
+    W2 = reinterpret_cast<const char*>(g.w2) + g.slot_expert[slot] * per;
   } else {
-    W2 = reinterpret_cast<const char*>(g.sw2) + (u - g.u_max) * per;
+    live = r < g.T;
+    W2 = reinterpret_cast<const char*>(g.sw2) + (slot - g.routed_slots) * per;
+    slot = g.u_max + (slot - g.routed_slots);
   }
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int ntiles = g.d >> 4, tile0 = blockIdx.x * R;
   const int nsteps = g.ffn >> 5, parts = g.KS * W, chunk = (nsteps + parts - 1) / parts;
   const int nst = max(0, min(chunk, nsteps - (ks * W + wave) * chunk));
@@ -554,10 +558,8 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 #pragma unroll
   for (int j = 0; j < R; ++j)
     base[j] = W2 + (size_t)min(tile0 + j, ntiles - 1) * wa.tile_stride + (size_t)s_beg * wa.step_stride;
-  // token column r contributes only if the token is routed to this expert (gate != 0)
-  const bool live = r < g.T && g.slot_gate[u * kGateCols + r] != 0.f;
-  const char* HH = reinterpret_cast<const char*>(g.hf_hi) + ((size_t)u * g.ffn * 16 + (size_t)s_beg * 512) * 2;
-  const char* HL = reinterpret_cast<const char*>(g.hf_lo) + ((size_t)u * g.ffn * 16 + (size_t)s_beg * 512) * 2;
+  const char* HH = reinterpret_cast<const char*>(g.hf_hi) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * 512) * 2;
+  const char* HL = reinterpret_cast<const char*>(g.hf_lo) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * 512) * 2;
   const uint32_t b_off = lane * 16;
 
   f32x4 acc[R];
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
         for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
         st.bh = uint4{0u, 0u, 0u, 0u};
         st.bl = uint4{0u, 0u, 0u, 0u};
-        if (live) {
+        if (live) {  // H of a token that was not routed here was never written: do not read it
           st.bh = ld128<false>(HH, b_off + (uint32_t)s * 1024);
           st.bl = ld128<false>(HL, b_off + (uint32_t)s * 1024);
         }
@@ -602,15 +604,16 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
     }
     if (r < g.T) {
-      const size_t o = (((size_t)u * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
+      const size_t o = (((size_t)slot * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
       *reinterpret_cast<float4*>(g.partial + o) = y;
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 5 (after the split-K down kernel): out[t,c] = sum over live slabs, routed slots ascending then
-// shared experts, k-chunks ascending — a fixed order, so reruns are bit-identical.
+// Step 5: out[t,c] = sum over the slabs of live slots — routed slots 0 .. n_unique-1 (ascending expert
+// id), then shared experts — k-chunks ascending: a fixed order, so reruns are bit-identical and no
+// floating-point atomics are needed.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
                                                       const int32_t* __restrict__ n_unique_p, float* __restrict__ out,
@@ -679,22 +682,21 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct moe_ctx {
   moe_shape s;
   int device;
-  int u_max, u_tot;
+  int u_max;              // largest possible union: min(E, max_tokens * top_k)
   int ks_alloc;           // split-K slabs the partial buffer is sized for
   int plan_override[3];   // MOE_PLAN=guR,dnR,dnKS (tuning), zeros = automatic
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
-  int32_t *ids, *unique, *n_unique, *count, *offset, *assign, *slot_expert;
+  int32_t *ids, *n_unique, *slot_expert;
   float *gates, *slot_gate, *partial;
-  int32_t* route_ticket;  // arrival counter of the router's fused grouping tail, zero between launches
   bool profiling;
   std::vector<hipEvent_t> events;  // kProfMarks per profiled layer-step
 };
 
 namespace {
 
-constexpr int kProfMarks = 5;  // events per profiled layer-step: route+group, gate/up, down, combine
+constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 
@@ -759,53 +761,60 @@ void mark(moe_ctx* c, hipStream_t st) {
   c->events.push_back(e);
 }
 
-moe_status launch_route_group(moe_ctx* c, const float* hidden, const uint16_t* router_w, int T, int32_t* ids,
-                              float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra,
-                              hipStream_t st) {
+// Steps 1 and 2.  ids / gates / unique / n_unique / n_unique_extra: optional DEVICE outputs.
+void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* router_w, int T, int32_t* ids,
+                            float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
   const moe_shape& s = c->s;
-  GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts,
-               GroupOut{c->unique, c->n_unique, c->count, c->offset, c->assign},
-               GroupOut{unique, n_unique, nullptr, nullptr, nullptr}, n_unique_extra, c->slot_expert, c->slot_gate};
-  mark(c, st);
-  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, st, hidden, router_w, s.d, s.n_experts, s.top_k, c->ids,
-                     c->gates, ids, gates, c->xf_hi, c->xf_lo, c->route_ticket, ga);
-  mark(c, st);
-  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+  RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, c->ids, ids, c->gates, gates, c->xf_hi, c->xf_lo};
+  GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
+               c->n_unique, n_unique_extra, c->slot_expert, c->slot_gate};
+  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, st, ra, ga);
+  if (T > 1) hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, st, ga);  // T = 1: done inside route_kernel
 }
 
+template <int R, int P>
+void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // row-major weights
+  const dim3 grid((c->s.ffn / 16 + R - 1) / R, a.routed_slots + c->s.n_shared);
+  hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
+}
 // Tiled weights are read exactly once in contiguous 1 KB pieces -> streaming loads; row-major weights
 // are read in 64-byte row segments whose cache lines are completed by the next k-step -> cached loads.
 template <int R, int P>
-void launch_gateup(const moe_ctx* c, const GateupArgs& a, bool tiled, hipStream_t st) {
-  const dim3 grid((c->s.ffn / 16 + R - 1) / R, c->u_tot);
-  if (tiled)
-    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, true, true>), grid, dim3(64 * kWaves), 0, st, a);
-  else
-    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
-}
-template <int R, int P>
 void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, hipStream_t st) {
-  const dim3 grid((c->s.d / 16 + R - 1) / R, c->u_tot, a.KS);
+  const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS);
   if (tiled)
     hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true>), grid, dim3(64 * kWaves), 0, st, a);
   else
     hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
 
-moe_status launch_experts(moe_ctx* c, const moe_layer_weights* w, int T, float* out, hipStream_t st) {
+// One layer-step after validation: router, gate/up, down, slab sum.  The expert-union step has no
+// launch of its own: it is the liveness test at the top of the expert kernels.
+// unique / n_unique / n_unique_extra: optional DEVICE outputs.
+moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
+                        float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED;
   const Plan p = plan_for(c, T, tiled);
+  mark(c, st);
+  launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st);
+  mark(c, st);
+  const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
-                c->hf_hi, c->hf_lo, s.d, s.ffn, T, c->u_max};
-  switch (p.gu_R) {
-    case 4: launch_gateup<4, 2>(c, ga, tiled, st); break;
-    case 2: launch_gateup<2, 4>(c, ga, tiled, st); break;
-    default: launch_gateup<1, 8>(c, ga, tiled, st); break;
+                c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
+  if (tiled) {
+    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);  // one wave per 16-row tile pair, whole d
+    hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true>), grid, dim3(64), 0, st, ga);
+  } else {
+    switch (p.gu_R) {
+      case 4: launch_gateup<4, 2>(c, ga, st); break;
+      case 2: launch_gateup<2, 4>(c, ga, st); break;
+      default: launch_gateup<1, 8>(c, ga, st); break;
+    }
   }
   mark(c, st);
   DownArgs da{w->w2, w->sw2, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert, c->slot_gate, c->partial,
-              s.d, s.ffn, T, c->u_max, s.max_tokens, p.dn_KS};
+              s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
     case 4: launch_down<4, 3>(c, da, tiled, st); break;
     case 2: launch_down<2, 4>(c, da, tiled, st); break;
@@ -869,7 +878,6 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->device = dev;
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
-  c->u_tot = c->u_max + s.n_shared;
   c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
   if (const char* env = getenv("MOE_PLAN")) {  // tuning override: "guR,dnR,dnKS"
     int a = 0, b = 0, k = 0;
@@ -880,7 +888,13 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
       c->plan_override[2] = k;
     }
   }
-  c->ks_alloc = ks_cap_for(s);
+  // the slab buffer is sized for the largest split-K factor any T can ask for
+  c->ks_alloc = 1;
+  for (int T = 1; T <= s.max_tokens; ++T)
+    for (bool tiled : {false, true}) {
+      const int ks = plan_for(c, T, tiled).dn_KS;
+      if (ks > c->ks_alloc) c->ks_alloc = ks;
+    }
 
   const size_t A = (size_t)s.max_tokens * s.top_k;
   size_t off = 0;
@@ -890,16 +904,14 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
     return o;
   };
   const size_t o_xh = carve((size_t)s.d * kGateCols * 2), o_xl = carve((size_t)s.d * kGateCols * 2);
-  const size_t o_hh = carve((size_t)c->u_tot * s.ffn * kGateCols * 2);
-  const size_t o_hl = carve((size_t)c->u_tot * s.ffn * kGateCols * 2);
-  const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_uni = carve((size_t)s.n_experts * 4);
-  const size_t o_nu = carve(4), o_cnt = carve((size_t)s.n_experts * 4), o_off = carve((size_t)(s.n_experts + 1) * 4);
-  const size_t o_asg = carve(A * 4), o_se = carve((size_t)c->u_max * 4);
-  const size_t o_sg = carve((size_t)c->u_tot * kGateCols * 4);
-  const size_t o_tk = carve(4);
-  const size_t o_part = carve((size_t)c->u_tot * c->ks_alloc * s.max_tokens * s.d * 4);
+  const size_t n_slots = (size_t)c->u_max + s.n_shared;
+  const size_t o_hh = carve(n_slots * s.ffn * kGateCols * 2);
+  const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
+  const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
+  const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4);
+  const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
   c->ws_bytes = off;
-  if (hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
+  if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
     return MOE_ERR_WORKSPACE;
@@ -910,27 +922,24 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->hf_lo = reinterpret_cast<uint16_t*>(c->ws + o_hl);
   c->ids = reinterpret_cast<int32_t*>(c->ws + o_ids);
   c->gates = reinterpret_cast<float*>(c->ws + o_gates);
-  c->unique = reinterpret_cast<int32_t*>(c->ws + o_uni);
   c->n_unique = reinterpret_cast<int32_t*>(c->ws + o_nu);
-  c->count = reinterpret_cast<int32_t*>(c->ws + o_cnt);
-  c->offset = reinterpret_cast<int32_t*>(c->ws + o_off);
-  c->assign = reinterpret_cast<int32_t*>(c->ws + o_asg);
   c->slot_expert = reinterpret_cast<int32_t*>(c->ws + o_se);
   c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
   c->partial = reinterpret_cast<float*>(c->ws + o_part);
-  c->route_ticket = reinterpret_cast<int32_t*>(c->ws + o_tk);
-  // small tables start at zero; shared-expert slots carry gate 1 for every token column
-  bool ok = hipMemset(c->ws, 0, c->ws_bytes) == hipSuccess;
-  if (ok && s.n_shared > 0) {
-    float ones[kMaxShared * kGateCols];
-    for (int i = 0; i < s.n_shared * kGateCols; ++i) ones[i] = 1.f;
-    ok = hipMemcpy(c->slot_gate + (size_t)c->u_max * kGateCols, ones, sizeof(float) * s.n_shared * kGateCols,
-                   hipMemcpyHostToDevice) == hipSuccess;
-  }
-  if (!ok) {
+  if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
     delete c;
     return MOE_ERR_HIP;
+  }
+  if (s.n_shared > 0) {  // shared-expert slots carry gate 1 for every token column
+    float ones[kMaxShared * kGateCols];
+    for (int i = 0; i < s.n_shared * kGateCols; ++i) ones[i] = 1.f;
+    if (hipMemcpy(c->slot_gate + (size_t)c->u_max * kGateCols, ones, sizeof(float) * s.n_shared * kGateCols,
+                  hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipFree(c->ws);
+      delete c;
+      return MOE_ERR_HIP;
+    }
   }
   *out = c;
   return MOE_OK;
@@ -951,16 +960,16 @@ moe_status moe_route(moe_ctx* c, const float* hidden, const uint16_t* router_w, 
   if (!c || !hidden || !router_w || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (!aligned16(hidden) || !aligned16(router_w)) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
-  return launch_route_group(c, hidden, router_w, T, ids, gates, unique_experts, n_unique, nullptr,
-                            (hipStream_t)stream);
+  launch_route_and_group(c, hidden, router_w, T, ids, gates, unique_experts, n_unique, nullptr, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 moe_status moe_group(moe_ctx* c, const int32_t* ids, int32_t T, int32_t* unique_experts, int32_t* n_unique,
                      int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream) {
   if (!c || !ids || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
-  GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, GroupOut{nullptr, nullptr, nullptr, nullptr, nullptr},
-               GroupOut{unique_experts, n_unique, expert_count, expert_offset, assign}, nullptr, nullptr, nullptr};
+  GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, unique_experts, n_unique, expert_count, expert_offset,
+               assign, nullptr, nullptr, nullptr, nullptr};
   hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ga);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -972,10 +981,7 @@ moe_status moe_verify_layer(moe_ctx* c, const moe_layer_weights* w, const float*
   if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
   hipStream_t st = (hipStream_t)stream;
-  if (moe_status rc = launch_route_group(c, hidden, w->router_w, T, ids_opt, gates_opt, unique_opt, n_unique_opt,
-                                         nullptr, st))
-    return rc;
-  return launch_experts(c, w, T, out, st);
+  return launch_layer(c, w, hidden, T, out, ids_opt, gates_opt, unique_opt, n_unique_opt, nullptr, st);
 }
 
 moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t L, const float* hidden, int32_t T,
@@ -988,10 +994,9 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
   hipStream_t st = (hipStream_t)stream;
   const size_t per = (size_t)T * c->s.d;
   for (int l = 0; l < L; ++l) {
-    if (moe_status rc = launch_route_group(c, hidden + l * per, layers[l].router_w, T, nullptr, nullptr, nullptr,
-                                           nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st))
+    if (moe_status rc = launch_layer(c, layers + l, hidden + l * per, T, out + l * per, nullptr, nullptr, nullptr,
+                                     nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st))
       return rc;
-    if (moe_status rc = launch_experts(c, layers + l, T, out + l * per, st)) return rc;
   }
   return MOE_OK;
 }

@@ -90,11 +90,13 @@ def _check_layer(cfg_like, W, x, ctx=None, Wd=None):
     assert nu == u["n_unique"]
     np.testing.assert_array_equal(uniq, u["unique"])
     rel = _check_out(out, ref32, ref64)
-    # the tiled weight layout holds the same numbers in another order: identical arithmetic, identical bits
+    # the tiled weight layout holds the same numbers in another order; its kernels split the sums
+    # differently, so it is checked against the oracle in its own right
     out_t, ids_t, gates_t, uniq_t, nu_t = _run_layer(ctx, Wd, x, tiled=True)
-    np.testing.assert_array_equal(ids_t, ids)
-    np.testing.assert_array_equal(out_t, out)
-    assert nu_t == nu
+    np.testing.assert_array_equal(ids_t, rids)
+    np.testing.assert_array_equal(uniq_t, u["unique"])
+    assert nu_t == nu and np.abs(gates_t - rgates).max() <= 1e-5
+    rel = max(rel, _check_out(out_t, ref32, ref64))
     if own:
         ctx.close()
     return out, rel
@@ -271,13 +273,15 @@ def test_batch_invariance_and_determinism_on_gpu():
     Wd = _weights_dev(W)
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
     x = synth.hidden_host(cfg, 2, 5, 9, 0.5)
-    out9, ids9, *_ = _run_layer(ctx, Wd, x)
-    again, *_ = _run_layer(ctx, Wd, x)
-    np.testing.assert_array_equal(out9, again)
-    for t in (0, 4, 8):
-        o1, i1, *_ = _run_layer(ctx, Wd, x[t:t + 1])
-        np.testing.assert_array_equal(i1[0], ids9[t])
-        np.testing.assert_allclose(o1[0], out9[t], rtol=0, atol=2e-6 * np.abs(out9).max())
+    for tiled in (False, True):
+        out9, ids9, *_ = _run_layer(ctx, Wd, x, tiled)
+        again, *_ = _run_layer(ctx, Wd, x, tiled)
+        np.testing.assert_array_equal(out9, again)
+        for t in (0, 4, 8):
+            o1, i1, *_ = _run_layer(ctx, Wd, x[t:t + 1], tiled)
+            np.testing.assert_array_equal(i1[0], ids9[t])
+            # T = 1 may use another split-K factor than T = 9, hence a tolerance and not bit equality
+            np.testing.assert_allclose(o1[0], out9[t], rtol=0, atol=2e-6 * np.abs(out9).max())
     ctx.close()
 
 
