@@ -87,8 +87,10 @@ moe_status moe_route(moe_ctx* ctx, const float* hidden, const uint16_t* router_w
  *   expert_offset[e]  exclusive prefix sum of expert_count, expert_offset[E] = T*top_k
  *   assign[..]        flat pair indices a = t*top_k + i grouped by expert (ascending e), ascending
  *                     a inside each group
- * ids [T,top_k]: DEVICE input, every id in [0,E).  unique_experts [E], n_unique [1], expert_count
- * [E], expert_offset [E+1], assign [T*top_k]: DEVICE int32 outputs, each may be NULL. */
+ * ids [T,top_k]: DEVICE input, every id in [0,E) and the top_k ids of one token distinct (as
+ * moe_route produces them; a repeated id inside a token is counted once).  unique_experts [E],
+ * n_unique [1], expert_count [E], expert_offset [E+1], assign [T*top_k]: DEVICE int32 outputs, each
+ * may be NULL. */
 moe_status moe_group(moe_ctx* ctx, const int32_t* ids, int32_t T, int32_t* unique_experts, int32_t* n_unique,
                      int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream);
 

@@ -5,13 +5,13 @@
 // HBM traffic for the UNION of the picked experts (Section 1, Section 2.4).  The path below touches
 // every unique expert's weights exactly once per step:
 //
-//   route_kernel   one workgroup per token: router logits (fp64 accumulate), top-k, softmax gates, and
-//                  the bf16 hi + lo activation fragments for the matrix cores
-//   group_kernel   union of experts, per-expert token lists, slot tables for the expert kernels (for a
-//                  single token, T = 1, route_kernel does this itself and the launch is skipped)
+//   route_kernel   one workgroup (16 waves) per token: router logits (fp64 accumulate), top-k by rank
+//                  counting, softmax gates, and the bf16 hi + lo activation fragments for the matrix cores
+//   group_kernel   union of experts, per-expert token lists, slot tables for the expert kernels and the
+//                  combine (for a single token, T = 1, route_kernel does this itself and the launch is skipped)
 //   gateup_kernel  for each slot of the union: G = w1 X, U = w3 X, H = gate * silu(G) * U   (2/3 of bytes)
 //   down_kernel    split-K partial sums of w2 H over (slot, k-chunk)                        (1/3 of bytes)
-//   combine_kernel out[t] = sum of the live slabs in slot order (deterministic, no atomics)
+//   combine_kernel out[t] = sum of the slabs of token t's own picks, in pick order (deterministic, no atomics)
 //
 // The two FFN kernels are skinny GEMMs (at most 16 token columns) and purely HBM-bound.  They use
 // v_mfma_f32_16x16x32_bf16 with the weight tile as the A operand: lane l holds 8 consecutive k of
@@ -83,35 +83,55 @@ __device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 2 as a launch of its own (moe_route / moe_group): union of activated experts + per-expert token
-// lists.  One workgroup, thread e = expert e.
+// Step 2: union of activated experts + per-expert token lists + the tables the expert kernels and
+// the combine read.  One workgroup; thread a = one (token, pick) pair, thread e = one expert.
 // ------------------------------------------------------------------------------------------
 struct GroupArgs {
-  const int32_t* ids;   // [T, top_k]
+  const int32_t* ids;   // [T, top_k], the picks of one token distinct
   const float* gates;   // [T, top_k] or NULL (then no gate table is built)
   int T, top_k, E;
   int32_t *unique, *n_unique, *count, *offset, *assign;     // caller-visible outputs, each optional
   int32_t *n_unique_ws, *n_unique_extra, *slot_expert;      // tables for the expert kernels, each optional
+  int32_t* tok_slot;                                        // [T, top_k] slot of the union each pick landed in
   float* slot_gate;                                         // [u_max, 16]
 };
 
-// Executed by the first 256 threads of a workgroup (all of them reach the two barriers inside, so the
-// caller must let EVERY thread of the block call it).  s_ids: the routing in LDS, or NULL to read g.ids.
+// Every thread of the workgroup must call this (it holds barriers); blockDim.x >= 256.
+// s_ids_in / s_gates_in: the routing in LDS, or NULL to read g.ids / g.gates.
+// A token picks an expert at most once, so expert e's token list is a 16-bit mask: pairs set their
+// bit with an LDS atomic OR (commutative, so the result does not depend on arrival order), counts are
+// popcounts, and lists come out in ascending token order by walking the set bits.
 __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float* s_gates_in) {
   __shared__ int s_ids_own[kMaxTokens * kMaxTopK];
+  __shared__ unsigned s_mask[kMaxExperts];
+  __shared__ unsigned char s_pos[kMaxExperts * kMaxTokens];  // which pick i of token t chose expert e
+  __shared__ int s_rank[kMaxExperts];
+  __shared__ float s_row[kMaxExperts * kGateCols];           // gate table by slot, built in LDS
   __shared__ int s_cnt[4], s_uni[4];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int E = g.E, A = g.T * g.top_k;
+  const bool want_gates = g.slot_gate && (g.gates || s_gates_in);
   const int* s_ids = s_ids_in ? s_ids_in : s_ids_own;
   if (!s_ids_in && tid < A) s_ids_own[tid] = g.ids[tid];
+  if (tid < E) s_mask[tid] = 0u;
+  const int max_slots = A < E ? A : E;
+  if (want_gates)
+    for (int i = tid; i < max_slots * kGateCols; i += blockDim.x) s_row[i] = 0.f;
+  __syncthreads();
+  const int my_e = tid < A ? s_ids[tid] : -1;
+  const int my_t = tid / g.top_k;
+  const bool pair_ok = tid < A && (unsigned)my_e < (unsigned)E;
+  if (pair_ok) {
+    atomicOr(&s_mask[my_e], 1u << my_t);
+    s_pos[my_e * kMaxTokens + my_t] = (unsigned char)(tid - my_t * g.top_k);
+  }
   __syncthreads();
   const bool act = tid < 256;
   const int e = tid;
-  int cnt = 0;
-  if (act && e < E)
-    for (int a = 0; a < A; ++a) cnt += (s_ids[a] == e);
+  unsigned m = (act && e < E) ? s_mask[e] : 0u;
+  const int cnt = __popc(m);
   const int flag = cnt > 0;
-  // inclusive scan of cnt inside the wave, ballot for the unique rank
+  // inclusive scan of cnt inside the wave, ballot for the rank among live experts
   int incl = cnt;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -123,7 +143,6 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
   if (act && lane == 63) s_cnt[wave] = incl;
   if (act && lane == 0) s_uni[wave] = __popcll(bal);
   __syncthreads();
-  if (!act) return;
   int cbase = 0, ubase = 0, n_unique = 0, total = 0;
   for (int w = 0; w < 4; ++w) {
     if (w < wave) {
@@ -133,33 +152,22 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
     n_unique += s_uni[w];
     total += s_cnt[w];
   }
-  const int off = cbase + incl - cnt;
-  const int rank = ubase + rank_in_wave;
-  if (e < E) {
+  if (act && e < E) {
+    const int off = cbase + incl - cnt;
+    const int rank = ubase + rank_in_wave;
     if (g.count) g.count[e] = cnt;
     if (g.offset) g.offset[e] = off;
     if (flag) {
+      s_rank[e] = rank;
       if (g.unique) g.unique[rank] = e;
       if (g.slot_expert) g.slot_expert[rank] = e;
-      float row[kGateCols];
-#pragma unroll
-      for (int n = 0; n < kGateCols; ++n) row[n] = 0.f;
-      int j = 0;
-      for (int a = 0; a < A; ++a)
-        if (s_ids[a] == e) {
-          if (g.assign) g.assign[off + j] = a;
-          ++j;
-          if (g.gates || s_gates_in) {
-            const int tok = a / g.top_k;
-            const float gv = s_gates_in ? s_gates_in[a] : g.gates[a];
-#pragma unroll
-            for (int n = 0; n < kGateCols; ++n)
-              if (n == tok) row[n] = gv;
-          }
+      if (g.assign) {
+        int j = 0;
+        while (m) {
+          const int t = __ffs(m) - 1;
+          m &= m - 1u;
+          g.assign[off + j++] = t * g.top_k + s_pos[e * kMaxTokens + t];
         }
-      if (g.slot_gate && (g.gates || s_gates_in)) {
-#pragma unroll
-        for (int n = 0; n < kGateCols; ++n) g.slot_gate[rank * kGateCols + n] = row[n];
       }
     }
     if (e >= n_unique && g.unique) g.unique[e] = -1;
@@ -170,12 +178,21 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
     if (g.n_unique_ws) *g.n_unique_ws = n_unique;
     if (g.n_unique_extra) *g.n_unique_extra = n_unique;
   }
+  __syncthreads();
+  if (pair_ok) {
+    const int slot = s_rank[my_e];
+    if (g.tok_slot) g.tok_slot[tid] = slot;
+    if (want_gates) s_row[slot * kGateCols + my_t] = s_gates_in ? s_gates_in[tid] : g.gates[tid];
+  }
+  if (!want_gates) return;
+  __syncthreads();
+  for (int i = tid; i < n_unique * kGateCols; i += blockDim.x) g.slot_gate[i] = s_row[i];
 }
 
 __global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g, nullptr, nullptr); }
 
 // ------------------------------------------------------------------------------------------
-// Step 1: router.  Building blocks shared by the two launch shapes below.
+// Step 1: router.
 // ------------------------------------------------------------------------------------------
 struct RouteArgs {
   const float* hidden;       // [T, d]
@@ -208,135 +225,151 @@ __device__ __forceinline__ void split_token(const float* __restrict__ x, int d, 
   }
 }
 
-// One wave's share of the logits of one token: the wave owns the 512-element chunks c = first_chunk,
-// first_chunk + chunk_stride, ... of d and, per trip, issues the 2 activation loads and the loads of up
-// to EMAX expert rows TOGETHER (independent loads, one round trip) instead of walking expert after
-// expert through dependent round trips.  Accumulation in fp64: fp32 x bf16 products are exact in
-// double, so the top-k decision does not depend on the order of summation (beyond ~1e-13 relative).
-// The wave's partial sum for expert e0 + e goes to s_part[e0 + e] (written by lane 0).
-template <int EMAX>
-__device__ __forceinline__ void partial_logits_wave(const float* __restrict__ x, const uint16_t* __restrict__ router_w,
-                                                    int d, int E, int lane, int first_chunk, int chunk_stride,
-                                                    double* s_part) {
-  for (int e0 = 0; e0 < E; e0 += EMAX) {
-    const int ne = min(EMAX, E - e0);
-    double acc[EMAX];
+constexpr int kRouteWaves = 16;  // waves per token in route_kernel
+constexpr int kRouteBatch = 8;   // expert rows one work item covers
+
+// One work item of the router of one token: the 512-element chunk `chunk` of d against the expert
+// rows e0 .. e0+7.  The activation loads and the (up to) 8 row loads are issued together — one round
+// trip — and accumulated in fp64: fp32 x bf16 products are exact in double, so the top-k decision does
+// not depend on the order of summation (beyond ~1e-13 relative).  The 64 lanes' partial sums are
+// folded by a reduce-scatter butterfly (each exchange halves the experts a lane still carries: 4 + 2 +
+// 1 exchanges, then 3 plain ones) instead of one 6-step butterfly per expert; lane 8*i then adds the
+// sum of expert e0 + i to s_acc[e0 + i], the wave's own row of partial logits.
+__device__ __forceinline__ void route_item(const float* __restrict__ x, const uint16_t* __restrict__ router_w, int d,
+                                           int E, int lane, int chunk, int e0, double* s_acc) {
+  const int j = chunk * 512 + lane * 8;
+  const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+  const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+  uint4 wv[kRouteBatch];
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) acc[e] = 0.0;
-    for (int j = lane * 8 + first_chunk * 512; j < d; j += chunk_stride * 512) {
-      const float4 x0 = *reinterpret_cast<const float4*>(x + j);
-      const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
-      uint4 wv[EMAX];
-#pragma unroll
-      for (int e = 0; e < EMAX; ++e)
-        if (e < ne) wv[e] = *reinterpret_cast<const uint4*>(router_w + (size_t)(e0 + e) * d + j);
-#pragma unroll
-      for (int e = 0; e < EMAX; ++e)
-        if (e < ne) {
-          double a = acc[e];
-          a = fma((double)x0.x, (double)bf16_to_f32(wv[e].x & 0xffffu), a);
-          a = fma((double)x0.y, (double)bf16_to_f32(wv[e].x >> 16), a);
-          a = fma((double)x0.z, (double)bf16_to_f32(wv[e].y & 0xffffu), a);
-          a = fma((double)x0.w, (double)bf16_to_f32(wv[e].y >> 16), a);
-          a = fma((double)x1.x, (double)bf16_to_f32(wv[e].z & 0xffffu), a);
-          a = fma((double)x1.y, (double)bf16_to_f32(wv[e].z >> 16), a);
-          a = fma((double)x1.z, (double)bf16_to_f32(wv[e].w & 0xffffu), a);
-          a = fma((double)x1.w, (double)bf16_to_f32(wv[e].w >> 16), a);
-          acc[e] = a;
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < EMAX; ++e)
-      if (e < ne) {
-        double a = acc[e];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
-        if (lane == 0) s_part[e0 + e] = a;
-      }
+  for (int e = 0; e < kRouteBatch; ++e) {
+    const int row = min(e0 + e, E - 1);  // past the last expert: re-read a valid row, result unused
+    wv[e] = *reinterpret_cast<const uint4*>(router_w + (size_t)row * d + j);
   }
+  const double xd[8] = {(double)x0.x, (double)x0.y, (double)x0.z, (double)x0.w,
+                        (double)x1.x, (double)x1.y, (double)x1.z, (double)x1.w};
+  double v[kRouteBatch];
+#pragma unroll
+  for (int e = 0; e < kRouteBatch; ++e) {
+    double a = 0.0;
+    a = fma(xd[0], (double)bf16_to_f32(wv[e].x & 0xffffu), a);
+    a = fma(xd[1], (double)bf16_to_f32(wv[e].x >> 16), a);
+    a = fma(xd[2], (double)bf16_to_f32(wv[e].y & 0xffffu), a);
+    a = fma(xd[3], (double)bf16_to_f32(wv[e].y >> 16), a);
+    a = fma(xd[4], (double)bf16_to_f32(wv[e].z & 0xffffu), a);
+    a = fma(xd[5], (double)bf16_to_f32(wv[e].z >> 16), a);
+    a = fma(xd[6], (double)bf16_to_f32(wv[e].w & 0xffffu), a);
+    a = fma(xd[7], (double)bf16_to_f32(wv[e].w >> 16), a);
+    v[e] = a;
+  }
+  // reduce-scatter: after the exchange over lane bit 5 a lane carries experts {0..3} or {4..7}, ...
+  const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
+  double u4[4], u2[2], u1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const double send = b5 ? v[i] : v[i + 4];
+    const double keep = b5 ? v[i + 4] : v[i];
+    u4[i] = keep + __shfl_xor(send, 32);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const double send = b4 ? u4[i] : u4[i + 2];
+    const double keep = b4 ? u4[i + 2] : u4[i];
+    u2[i] = keep + __shfl_xor(send, 16);
+  }
+  {
+    const double send = b3 ? u2[0] : u2[1];
+    const double keep = b3 ? u2[1] : u2[0];
+    u1 = keep + __shfl_xor(send, 8);
+  }
+  u1 += __shfl_xor(u1, 4);
+  u1 += __shfl_xor(u1, 2);
+  u1 += __shfl_xor(u1, 1);
+  const int idx = (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0);
+  if ((lane & 7) == 0 && e0 + idx < E) s_acc[e0 + idx] += u1;
 }
 
-// One wave: top-k of E logits (in LDS) by repeated wave-wide arg-max, ties to the lower expert index;
-// gates = softmax over the selected logits in fp32, summed in slot order.  Lane 0 writes the token's
-// ids and gates to global memory and, if given, to the LDS copies s_ids / s_gates.
-__device__ __forceinline__ void topk_gates_wave(const double* s_logit, const RouteArgs& g, int t, int lane,
-                                                int* s_ids, float* s_gates) {
-  const int E = g.E, top_k = g.top_k;
-  double v[kMaxExperts / 64];
-#pragma unroll
-  for (int q = 0; q < kMaxExperts / 64; ++q) {
-    const int e = lane + 64 * q;
-    double lv = e < E ? s_logit[e] : 0.0;
-    if (lv != lv) lv = -INFINITY;  // a NaN logit is never preferred
-    v[q] = lv;
-  }
-  unsigned taken = 0;
-  int sel_id = 0;      // lane i < top_k keeps the i-th pick
-  float sel_l = 0.f;
-  for (int i = 0; i < top_k; ++i) {
-    double bv = -INFINITY;
-    int be = INT_MAX;
-#pragma unroll
-    for (int q = 0; q < kMaxExperts / 64; ++q) {
-      const int e = lane + 64 * q;
-      if (e < E && !((taken >> q) & 1u) && (be == INT_MAX || v[q] > bv)) {
-        bv = v[q];
-        be = e;
-      }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const double ov = __shfl_xor(bv, o);
-      const int oe = __shfl_xor(be, o);
-      if (ov > bv || (ov == bv && oe < be)) {
-        bv = ov;
-        be = oe;
-      }
-    }
-    if ((be & 63) == lane) taken |= 1u << (be >> 6);
-    if (lane == i) {
-      sel_id = be;
-      sel_l = (float)bv;
-    }
-  }
-  // softmax over the picks: p_i = exp(l_i - l_0), sum in slot order (lane 0 adds them up one by one)
-  const float l0 = __shfl(sel_l, 0);
-  const float p = lane < top_k ? expf(sel_l - l0) : 0.f;
-  float sum = 0.f;
-  for (int i = 0; i < top_k; ++i) sum += __shfl(p, i);
-  if (lane < top_k) {
-    const float gate = p / sum;
-    const int a = t * top_k + lane;
-    g.ids_ws[a] = sel_id;
-    g.gates_ws[a] = gate;
-    if (g.ids_out) g.ids_out[a] = sel_id;
-    if (g.gates_out) g.gates_out[a] = gate;
-    if (s_ids) {
-      s_ids[a] = sel_id;
-      s_gates[a] = gate;
-    }
-  }
-}
-
-// One workgroup (4 waves) per token: the waves split d, their partial logits meet in LDS, wave 0 does
-// the top-k and the gates.  With a single token in flight (T = 1, no speculation) that one workgroup
-// already sees the whole routing, so the expert-union step runs right here; with more tokens it
-// needs the launch of its own that follows (group_kernel).
-__global__ __launch_bounds__(256) void route_kernel(RouteArgs g, GroupArgs grp) {
-  __shared__ double s_part[4][kMaxExperts];
+// One workgroup (16 waves) per token.  The (chunk of d, batch of 8 experts) work items are dealt
+// round-robin to the waves; partial logits meet in LDS and are summed in wave order.  Top-k by rank
+// counting: thread e counts the logits that beat its own (larger, or equal with a lower index), the
+// expert of rank i < top_k is pick i — no serial arg-max rounds.  Gates = softmax over the picked
+// logits in fp32, summed in pick order.  With a single token in flight (T = 1, no speculation) this
+// workgroup already sees the whole routing, so the expert-union step runs right here; with more
+// tokens it needs the launch of its own that follows (group_kernel).
+__global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, GroupArgs grp) {
+  __shared__ double s_part[kRouteWaves][kMaxExperts];
   __shared__ double s_logit[kMaxExperts];
   __shared__ int s_ids[kMaxTopK];
+  __shared__ float s_sel[kMaxTopK];
   __shared__ float s_gates[kMaxTopK];
   const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int E = g.E, top_k = g.top_k;
   const float* x = g.hidden + (size_t)t * g.d;
-  partial_logits_wave<16>(x, g.router_w, g.d, g.E, lane, wave, 4, s_part[wave]);
-  split_token(x, g.d, t, tid, 256, g.xf_hi, g.xf_lo);
+  const int n_batches = (E + kRouteBatch - 1) / kRouteBatch;
+  const int n_full = g.d >> 9;  // whole 512-element chunks
+  const int n_items = n_full * n_batches;
+  for (int e = lane; e < E; e += 64) s_part[wave][e] = 0.0;  // the wave's own row: no barrier needed
+  for (int it = wave; it < n_items; it += kRouteWaves)
+    route_item(x, g.router_w, g.d, E, lane, it / n_batches, (it % n_batches) * kRouteBatch, s_part[wave]);
+  if ((g.d & 511) && wave == kRouteWaves - 1) {
+    // ragged tail of d (a multiple of 32 elements): lanes walk it 8 elements at a time
+    for (int e = 0; e < E; ++e) {
+      double a = 0.0;
+      for (int j = (n_full << 9) + lane * 8; j < g.d; j += 512) {
+        const uint4 w = *reinterpret_cast<const uint4*>(g.router_w + (size_t)e * g.d + j);
+        const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+        const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+        a = fma((double)x0.x, (double)bf16_to_f32(w.x & 0xffffu), a);
+        a = fma((double)x0.y, (double)bf16_to_f32(w.x >> 16), a);
+        a = fma((double)x0.z, (double)bf16_to_f32(w.y & 0xffffu), a);
+        a = fma((double)x0.w, (double)bf16_to_f32(w.y >> 16), a);
+        a = fma((double)x1.x, (double)bf16_to_f32(w.z & 0xffffu), a);
+        a = fma((double)x1.y, (double)bf16_to_f32(w.z >> 16), a);
+        a = fma((double)x1.z, (double)bf16_to_f32(w.w & 0xffffu), a);
+        a = fma((double)x1.w, (double)bf16_to_f32(w.w >> 16), a);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+      if (lane == 0) s_part[wave][e] += a;
+    }
+  }
+  split_token(x, g.d, t, tid, 64 * kRouteWaves, g.xf_hi, g.xf_lo);
   __syncthreads();
-  for (int e = tid; e < g.E; e += 256) s_logit[e] = ((s_part[0][e] + s_part[1][e]) + s_part[2][e]) + s_part[3][e];
+  if (tid < E) {
+    double l = 0.0;
+#pragma unroll
+    for (int w = 0; w < kRouteWaves; ++w) l += s_part[w][tid];
+    if (l != l) l = -INFINITY;  // a NaN logit is never preferred
+    s_logit[tid] = l;
+  }
   __syncthreads();
-  const bool alone = gridDim.x == 1;
-  if (wave == 0) topk_gates_wave(s_logit, g, t, lane, alone ? s_ids : nullptr, alone ? s_gates : nullptr);
-  if (alone) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+  if (tid < E) {
+    const double mine = s_logit[tid];
+    int rank = 0;
+    for (int j = 0; j < E; ++j) {
+      const double o = s_logit[j];  // same address in every lane: an LDS broadcast
+      rank += (o > mine || (o == mine && j < tid)) ? 1 : 0;
+    }
+    if (rank < top_k) {
+      s_ids[rank] = tid;
+      s_sel[rank] = (float)mine;
+    }
+  }
+  __syncthreads();
+  if (tid < top_k) {
+    // softmax over the picks: p_i = exp(l_i - l_0), denominator summed in pick order
+    const float l0 = s_sel[0];
+    float sum = 0.f;
+    for (int i = 0; i < top_k; ++i) sum += expf(s_sel[i] - l0);
+    const float gate = expf(s_sel[tid] - l0) / sum;
+    const int a = t * top_k + tid, id = s_ids[tid];
+    g.ids_ws[a] = id;
+    g.gates_ws[a] = gate;
+    if (g.ids_out) g.ids_out[a] = id;
+    if (g.gates_out) g.gates_out[a] = gate;
+    s_gates[tid] = gate;
+  }
+  if (gridDim.x == 1) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
 }
 
 // ------------------------------------------------------------------------------------------
@@ -603,7 +636,7 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
     } else {
       y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
     }
-    if (r < g.T) {
+    if (live) {  // nobody reads the slab column of a token that was not routed here
       const size_t o = (((size_t)slot * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
       *reinterpret_cast<float4*>(g.partial + o) = y;
     }
@@ -611,31 +644,28 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Step 5: out[t,c] = sum over the slabs of live slots — routed slots 0 .. n_unique-1 (ascending expert
-// id), then shared experts — k-chunks ascending: a fixed order, so reruns are bit-identical and no
-// floating-point atomics are needed.
+// Step 5: out[t] = sum over the token's own picks i = 0 .. top_k-1 (the slot each landed in comes from
+// the grouping step), then the shared experts; k-chunks ascending inside each.  A fixed order — the
+// order of the defining sum — so reruns are bit-identical and no floating-point atomics are needed.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
-                                                      const int32_t* __restrict__ n_unique_p, float* __restrict__ out,
-                                                      int d, int T, int u_max, int n_shared, int max_tokens, int KS) {
+                                                      const int32_t* __restrict__ tok_slot, float* __restrict__ out,
+                                                      int d, int T, int top_k, int u_max, int n_shared,
+                                                      int max_tokens, int KS) {
   const int i = blockIdx.x * 256 + threadIdx.x;  // float4 index inside [T, d]
   const int per_tok = d >> 2;
   if (i >= T * per_tok) return;
   const int t = i / per_tok, c4 = i - t * per_tok;
-  const int n_unique = *n_unique_p;
   float4 s = float4{0.f, 0.f, 0.f, 0.f};
   const size_t slab = (size_t)max_tokens * d;
   const float* p0 = partial + (size_t)t * d + (size_t)c4 * 4;
-  for (int u = 0; u < n_unique; ++u)
+  for (int j = 0; j < top_k + n_shared; ++j) {
+    const int u = j < top_k ? tok_slot[t * top_k + j] : u_max + (j - top_k);
     for (int k = 0; k < KS; ++k) {
       const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
       s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
     }
-  for (int u = u_max; u < u_max + n_shared; ++u)
-    for (int k = 0; k < KS; ++k) {
-      const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
-      s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
-    }
+  }
   *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
 }
 
@@ -696,7 +726,7 @@ struct moe_ctx {
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
-  int32_t *ids, *n_unique, *slot_expert;
+  int32_t *ids, *n_unique, *slot_expert, *tok_slot;
   float *gates, *slot_gate, *partial;
   bool profiling;
   std::vector<hipEvent_t> events;  // kProfMarks per profiled layer-step
@@ -775,8 +805,8 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
   const moe_shape& s = c->s;
   RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, c->ids, ids, c->gates, gates, c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
-               c->n_unique, n_unique_extra, c->slot_expert, c->slot_gate};
-  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(256), 0, st, ra, ga);
+               c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
+  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(64 * kRouteWaves), 0, st, ra, ga);
   if (T > 1) hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, st, ga);  // T = 1: done inside route_kernel
 }
 
@@ -831,7 +861,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   mark(c, st);
   const int n4 = T * (s.d / 4);
   hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
-                     (const int32_t*)c->n_unique, out, s.d, T, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
+                     (const int32_t*)c->tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
   mark(c, st);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -916,7 +946,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   const size_t o_hh = carve(n_slots * s.ffn * kGateCols * 2);
   const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
   const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
-  const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4);
+  const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
   const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
   c->ws_bytes = off;
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
@@ -933,6 +963,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->n_unique = reinterpret_cast<int32_t*>(c->ws + o_nu);
   c->slot_expert = reinterpret_cast<int32_t*>(c->ws + o_se);
   c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
+  c->tok_slot = reinterpret_cast<int32_t*>(c->ws + o_ts);
   c->partial = reinterpret_cast<float*>(c->ws + o_part);
   if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
@@ -977,7 +1008,7 @@ moe_status moe_group(moe_ctx* c, const int32_t* ids, int32_t T, int32_t* unique_
   if (!c || !ids || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
   GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, unique_experts, n_unique, expert_count, expert_offset,
-               assign, nullptr, nullptr, nullptr, nullptr};
+               assign, nullptr, nullptr, nullptr, nullptr, nullptr};
   hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ga);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
