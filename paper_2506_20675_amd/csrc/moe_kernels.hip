@@ -457,9 +457,11 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   float gate;
   int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
   if (slot < g.routed_slots) {
-    if (slot >= *g.n_unique) return;  // beyond the union of this step
+    // three independent loads (one round trip); the tables are in bounds for every slot of the grid
+    const int nu = *g.n_unique;
     const int e = g.slot_expert[slot];
     gate = g.slot_gate[slot * kGateCols + r];
+    if (slot >= nu) return;  // beyond the union of this step
     W1 = reinterpret_cast<const char*>(g.w1) + e * per;
     W3 = reinterpret_cast<const char*>(g.w3) + e * per;
   } else {
@@ -573,9 +575,11 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   const size_t per = (size_t)g.ffn * g.d * 2;
   bool live;  // token column r contributes only if the token is routed to this expert
   if (slot < g.routed_slots) {
-    if (slot >= *g.n_unique) return;
+    const int nu = *g.n_unique;  // three independent loads, one round trip
+    const int e = g.slot_expert[slot];
     live = g.slot_gate[slot * kGateCols + r] != 0.f;  // 0 also for the padded columns r >= T
-    W2 = reinterpret_cast<const char*>(g.w2) + g.slot_expert[slot] * per;
+    if (slot >= nu) return;
+    W2 = reinterpret_cast<const char*>(g.w2) + e * per;
   } else {
     live = r < g.T;
     W2 = reinterpret_cast<const char*>(g.sw2) + (slot - g.routed_slots) * per;
@@ -659,12 +663,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
   float4 s = float4{0.f, 0.f, 0.f, 0.f};
   const size_t slab = (size_t)max_tokens * d;
   const float* p0 = partial + (size_t)t * d + (size_t)c4 * 4;
-  for (int j = 0; j < top_k + n_shared; ++j) {
+  // flat walk over (pick, k-chunk): unrolled by 8 so that eight slab loads are in flight at a time
+  const int n = (top_k + n_shared) * KS;
+#pragma unroll 8
+  for (int q = 0; q < n; ++q) {
+    const int j = q / KS, k = q - j * KS;
     const int u = j < top_k ? tok_slot[t * top_k + j] : u_max + (j - top_k);
-    for (int k = 0; k < KS; ++k) {
-      const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
-      s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
-    }
+    const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
+    s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
   }
   *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
 }
@@ -841,7 +847,9 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
   if (tiled) {
-    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);  // one wave per 16-row tile pair, whole d
+    // one wave per 16-row tile pair over the whole of d (splitting d over 2 or 4 waves when the union
+    // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
+    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
     hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true>), grid, dim3(64), 0, st, ga);
   } else {
     switch (p.gu_R) {
