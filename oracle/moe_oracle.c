@@ -207,3 +207,97 @@ int oracle_dense_masked(const float* hidden, int T, int d, int ffn, int E, int t
   free(acc);
   return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * FP8 expert weights (paper: Table 1 lists the Mixtral, Phi-3.5 and OLMoE checkpoints as FP8;
+ * Section 6.1, quantised models).  The paper does not define the format or the scaling; the
+ * reading taken here: weights are stored as 8-bit E4M3 codes with one fp32 scale per OUTPUT
+ * channel (row of the matrix), the effective weight is W[r][j] = scale[r] * value(code[r][j]),
+ * activations and arithmetic stay as in the bf16 layer, the router stays bf16.
+ *
+ * E4M3 as published for FP8 training/inference ("FP8 formats for deep learning", the OCP 8-bit
+ * floating point specification): 1 sign bit, 4 exponent bits with bias 7, 3 mantissa bits;
+ * exponent field 0 is subnormal (m/8 * 2^-6); there are no infinities; S.1111.111 is NaN; the
+ * largest finite value is S.1111.110 = 1.75 * 2^8 = 448.
+ * --------------------------------------------------------------------------------------------- */
+double oracle_fp8_e4m3_value(uint8_t code) {
+  const int sign = code >> 7, ex = (code >> 3) & 15, man = code & 7;
+  double v;
+  if (ex == 15 && man == 7) return NAN;
+  if (ex == 0)
+    v = ldexp((double)man / 8.0, -6);
+  else
+    v = ldexp(1.0 + (double)man / 8.0, ex - 7);
+  return sign ? -v : v;
+}
+
+/* One SwiGLU expert with FP8 weights: as oracle_expert_ffn, with every weight replaced by
+ * scale[row] * value(code).  q1, q3: [ffn, d] codes, s1, s3: [ffn]; q2: [d, ffn], s2: [d].
+ * (The 256 code values are tabulated once per call only to keep the loops quick.) */
+void oracle_expert_ffn_fp8(const float* x, const uint8_t* q1, const float* s1, const uint8_t* q3, const float* s3,
+                           const uint8_t* q2, const float* s2, int d, int ffn, REAL* h, REAL* y) {
+  REAL val[256];
+  for (int c = 0; c < 256; ++c) val[c] = (REAL)oracle_fp8_e4m3_value((uint8_t)c);
+  for (int r = 0; r < ffn; ++r) {
+    REAL g = 0, u = 0;
+    for (int j = 0; j < d; ++j) g += ((REAL)s1[r] * val[q1[(size_t)r * d + j]]) * (REAL)x[j];
+    for (int j = 0; j < d; ++j) u += ((REAL)s3[r] * val[q3[(size_t)r * d + j]]) * (REAL)x[j];
+    h[r] = (g / ((REAL)1 + real_exp(-g))) * u;
+  }
+  for (int c = 0; c < d; ++c) {
+    REAL s = 0;
+    for (int r = 0; r < ffn; ++r) s += ((REAL)s2[c] * val[q2[(size_t)c * ffn + r]]) * h[r];
+    y[c] = s;
+  }
+}
+
+/* Gate-weighted combine for a given routing, FP8 experts (same sum as oracle_combine).
+ * q1, q3: [E, ffn, d]; q2: [E, d, ffn]; s1, s3: [E, ffn]; s2: [E, d]; shared experts likewise. */
+int oracle_combine_fp8(const float* hidden, int T, int d, int ffn, int E, int top_k, int n_shared,
+                       const uint8_t* q1, const uint8_t* q3, const uint8_t* q2,
+                       const float* s1, const float* s3, const float* s2,
+                       const uint8_t* sq1, const uint8_t* sq3, const uint8_t* sq2,
+                       const float* ss1, const float* ss3, const float* ss2,
+                       const int32_t* ids, const float* gates, float* out) {
+  REAL* h = (REAL*)malloc(sizeof(REAL) * (size_t)ffn);
+  REAL* y = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  REAL* acc = (REAL*)malloc(sizeof(REAL) * (size_t)d);
+  const size_t per = (size_t)ffn * d;
+  int rc = 0;
+  for (int t = 0; t < T && rc == 0; ++t) {
+    const float* x = hidden + (size_t)t * d;
+    for (int c = 0; c < d; ++c) acc[c] = 0;
+    for (int i = 0; i < top_k; ++i) {
+      int e = ids[(size_t)t * top_k + i];
+      if (e < 0 || e >= E) { rc = -1; break; }
+      oracle_expert_ffn_fp8(x, q1 + e * per, s1 + (size_t)e * ffn, q3 + e * per, s3 + (size_t)e * ffn,
+                            q2 + e * per, s2 + (size_t)e * d, d, ffn, h, y);
+      REAL g = (REAL)gates[(size_t)t * top_k + i];
+      for (int c = 0; c < d; ++c) acc[c] += g * y[c];
+    }
+    for (int s = 0; s < n_shared; ++s) {
+      oracle_expert_ffn_fp8(x, sq1 + s * per, ss1 + (size_t)s * ffn, sq3 + s * per, ss3 + (size_t)s * ffn,
+                            sq2 + s * per, ss2 + (size_t)s * d, d, ffn, h, y);
+      for (int c = 0; c < d; ++c) acc[c] += y[c];
+    }
+    for (int c = 0; c < d; ++c) out[(size_t)t * d + c] = (float)acc[c];
+  }
+  free(h);
+  free(y);
+  free(acc);
+  return rc;
+}
+
+/* The whole FP8 layer: the (bf16) router, then the FP8 combine. */
+int oracle_layer_fp8(const float* hidden, int T, int d, int ffn, int E, int top_k, int n_shared,
+                     const uint16_t* router_w,
+                     const uint8_t* q1, const uint8_t* q3, const uint8_t* q2,
+                     const float* s1, const float* s3, const float* s2,
+                     const uint8_t* sq1, const uint8_t* sq3, const uint8_t* sq2,
+                     const float* ss1, const float* ss3, const float* ss2,
+                     int32_t* ids, float* gates, float* out) {
+  int rc = oracle_route(hidden, router_w, T, d, E, top_k, ids, gates, NULL);
+  if (rc) return rc;
+  return oracle_combine_fp8(hidden, T, d, ffn, E, top_k, n_shared, q1, q3, q2, s1, s3, s2, sq1, sq3, sq2, ss1, ss3,
+                            ss2, ids, gates, out);
+}

@@ -23,6 +23,7 @@ _u16p = ctypes.POINTER(ctypes.c_uint16)
 _f32p = ctypes.POINTER(ctypes.c_float)
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _f64p = ctypes.POINTER(ctypes.c_double)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
 
 
 def lib_path(precision: str) -> str:
@@ -58,6 +59,16 @@ def _load(path: str, precision: str):
     L.oracle_dense_masked.argtypes = comb
     L.oracle_layer.restype = ctypes.c_int
     L.oracle_layer.argtypes = [_f32p] + [ctypes.c_int] * 6 + [_u16p] * 7 + [_i32p, _f32p, _f32p]
+    L.oracle_fp8_e4m3_value.restype = ctypes.c_double
+    L.oracle_fp8_e4m3_value.argtypes = [ctypes.c_uint8]
+    L.oracle_expert_ffn_fp8.restype = None
+    L.oracle_expert_ffn_fp8.argtypes = [_f32p, _u8p, _f32p, _u8p, _f32p, _u8p, _f32p, ctypes.c_int, ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_void_p]
+    fp8w = [_u8p] * 3 + [_f32p] * 3 + [_u8p] * 3 + [_f32p] * 3
+    L.oracle_combine_fp8.restype = ctypes.c_int
+    L.oracle_combine_fp8.argtypes = [_f32p] + [ctypes.c_int] * 6 + fp8w + [_i32p, _f32p, _f32p]
+    L.oracle_layer_fp8.restype = ctypes.c_int
+    L.oracle_layer_fp8.argtypes = [_f32p] + [ctypes.c_int] * 6 + [_u16p] + fp8w + [_i32p, _f32p, _f32p]
     assert L.oracle_real_bytes() == (4 if precision == "f32" else 8)
     return L
 
@@ -194,4 +205,107 @@ def layer(hidden, W, top_k, n_shared=0, precision="f32"):
                                       out.ctypes.data_as(_f32p))
     if rc:
         raise ValueError("oracle_layer: bad sizes")
+    return out, ids, gates
+
+
+# ---------------------------------------------------------------------------------------------
+# FP8 (E4M3 codes + one fp32 scale per output channel) expert weights
+# ---------------------------------------------------------------------------------------------
+def _u8(a):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint8:
+        a = a.view(np.uint8)
+    return a, a.ctypes.data_as(_u8p)
+
+
+def _f32n(a):
+    if a is None:
+        return None, None
+    return _f32(a)
+
+
+def fp8_e4m3_values(codes=None, precision="f64"):
+    """Value of each E4M3 code (default: all 256) as fp64; the two NaN codes give NaN."""
+    L = _lib(precision)
+    codes = np.arange(256, dtype=np.uint8) if codes is None else np.asarray(codes, dtype=np.uint8)
+    return np.array([L.oracle_fp8_e4m3_value(int(c)) for c in codes.reshape(-1)], dtype=np.float64).reshape(codes.shape)
+
+
+def expert_ffn_fp8(x, q1, s1, q3, s3, q2, s2, precision="f32"):
+    """One FP8 SwiGLU expert on one token: q1/q3 [ffn,d] codes, s1/s3 [ffn]; q2 [d,ffn], s2 [d] -> y[d], h[ffn]."""
+    x, xp = _f32(x)
+    q1, p1 = _u8(q1)
+    q3, p3 = _u8(q3)
+    q2, p2 = _u8(q2)
+    s1, c1 = _f32(s1)
+    s3, c3 = _f32(s3)
+    s2, c2 = _f32(s2)
+    ffn, d = q1.shape
+    assert q3.shape == (ffn, d) and q2.shape == (d, ffn) and x.shape == (d,)
+    assert s1.shape == (ffn,) and s3.shape == (ffn,) and s2.shape == (d,)
+    dt = np.float32 if precision == "f32" else np.float64
+    h = np.empty(ffn, dt)
+    y = np.empty(d, dt)
+    _lib(precision).oracle_expert_ffn_fp8(xp, p1, c1, p3, c3, p2, c2, d, ffn, h.ctypes.data, y.ctypes.data)
+    return y.astype(np.float64), h.astype(np.float64)
+
+
+def _fp8_weight_args(W, E, ffn, d, n_shared):
+    """Marshal q1,q3,q2,s1,s3,s2 (+ sq*, ss* for shared experts) of a weight dict; returns (keepalive, pointers)."""
+    keep, ptrs = [], []
+    for name, shape in (("q1", (E, ffn, d)), ("q3", (E, ffn, d)), ("q2", (E, d, ffn))):
+        a, p = _u8(W[name])
+        assert a.shape == shape, (name, a.shape, shape)
+        keep.append(a), ptrs.append(p)
+    for name, shape in (("s1", (E, ffn)), ("s3", (E, ffn)), ("s2", (E, d))):
+        a, p = _f32(W[name])
+        assert a.shape == shape, (name, a.shape, shape)
+        keep.append(a), ptrs.append(p)
+    for name, shape in (("sq1", (n_shared, ffn, d)), ("sq3", (n_shared, ffn, d)), ("sq2", (n_shared, d, ffn))):
+        a, p = _u8(W.get(name) if n_shared else None)
+        if n_shared:
+            assert a.shape == shape, (name, a.shape, shape)
+        keep.append(a), ptrs.append(p)
+    for name, shape in (("ss1", (n_shared, ffn)), ("ss3", (n_shared, ffn)), ("ss2", (n_shared, d))):
+        a, p = _f32n(W.get(name) if n_shared else None)
+        if n_shared:
+            assert a.shape == shape, (name, a.shape, shape)
+        keep.append(a), ptrs.append(p)
+    return keep, ptrs
+
+
+def combine_fp8(hidden, W, ids, gates, n_shared=0, precision="f32"):
+    """out[T,d] for a GIVEN routing, FP8 experts.  W: q1,q3,q2 (uint8 codes), s1,s3,s2 (fp32 row scales), shared: sq*, ss*."""
+    hidden, hp = _f32(hidden)
+    T, d = hidden.shape
+    E, ffn, _ = np.asarray(W["q1"]).shape
+    keep, ptrs = _fp8_weight_args(W, E, ffn, d, n_shared)
+    ids, ip = _i32(ids)
+    gates, gp = _f32(gates)
+    top_k = ids.shape[1]
+    assert ids.shape == (T, top_k) and gates.shape == (T, top_k)
+    out = np.empty((T, d), np.float32)
+    rc = _lib(precision).oracle_combine_fp8(hp, T, d, ffn, E, top_k, n_shared, *ptrs, ip, gp, out.ctypes.data_as(_f32p))
+    if rc:
+        raise ValueError("oracle_combine_fp8: expert id out of range")
+    return out
+
+
+def layer_fp8(hidden, W, top_k, n_shared=0, precision="f32"):
+    """Route (bf16 router_w) + FP8 combine.  -> out, ids, gates."""
+    hidden, hp = _f32(hidden)
+    T, d = hidden.shape
+    rw, pr = _u16(W["router_w"])
+    E, ffn, _ = np.asarray(W["q1"]).shape
+    assert rw.shape == (E, d)
+    keep, ptrs = _fp8_weight_args(W, E, ffn, d, n_shared)
+    ids = np.empty((T, top_k), np.int32)
+    gates = np.empty((T, top_k), np.float32)
+    out = np.empty((T, d), np.float32)
+    rc = _lib(precision).oracle_layer_fp8(hp, T, d, ffn, E, top_k, n_shared, pr, *ptrs, ids.ctypes.data_as(_i32p),
+                                          gates.ctypes.data_as(_f32p), out.ctypes.data_as(_f32p))
+    if rc:
+        raise ValueError("oracle_layer_fp8: bad sizes")
     return out, ids, gates

@@ -39,6 +39,9 @@ _M2 = 0x94D049BB133111EB
 # tensor ids (one random stream per tensor)
 T_ROUTER, T_W1, T_W3, T_W2, T_SW1, T_SW3, T_SW2 = 1, 2, 3, 4, 5, 6, 7
 T_Z_SHARED, T_Z_TOKEN, T_ACCEPT, T_REGIME = 8, 9, 10, 11
+# FP8 variants of the expert tensors: code streams and per-row scale streams
+T_Q = {"q1": 12, "q3": 13, "q2": 14, "sq1": 15, "sq3": 16, "sq2": 17}
+T_S = {"s1": 18, "s3": 19, "s2": 20, "ss1": 21, "ss3": 22, "ss2": 23}
 
 SIGMA_EXPERT = 0.02
 SIGMA_ROUTER = 0.05
@@ -58,6 +61,10 @@ class MoEConfig:
     @property
     def expert_bytes(self) -> int:
         return 3 * self.d * self.ffn * 2
+
+    @property
+    def expert_bytes_fp8(self) -> int:
+        return 3 * self.d * self.ffn
 
 
 # The four single-layer workloads; the 32-layer stack reuses MIXTRAL with layer = 0..31.
@@ -208,6 +215,95 @@ def layer_weights_host(cfg: MoEConfig, layer: int = 0) -> dict:
     return out
 
 
+# ----------------------------------------------------------------------------
+# FP8 (E4M3) expert weights: 8-bit codes + one fp32 scale per output channel (storage format only)
+# ----------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+@lru_cache(maxsize=1)
+def e4m3_grid() -> np.ndarray:
+    """Value of each of the 256 E4M3 codes (sign, 4 exponent bits biased by 7, 3 mantissa bits, no
+    infinities, S.1111.111 = NaN).  Used only to pick codes for synthetic weights."""
+    c = np.arange(256)
+    ex, man = (c >> 3) & 15, c & 7
+    mag = np.where(ex == 0, man / 8.0 * 2.0 ** -6, (1.0 + man / 8.0) * 2.0 ** (ex - 7.0))
+    mag = np.where((ex == 15) & (man == 7), np.nan, mag)
+    return np.where(c >= 128, -mag, mag)
+
+
+@lru_cache(maxsize=1)
+def code_table_e4m3() -> np.ndarray:
+    """65536 E4M3 codes: the equiprobable N(0,1) quantile mid-points, stretched so that the outermost one
+    (4.32 sigma) lands on the largest finite value 448, each replaced by the nearest finite code."""
+    from scipy.special import ndtri
+    z = ndtri((np.arange(65536, dtype=np.float64) + 0.5) / 65536.0)
+    target = z * (E4M3_MAX / z[-1])
+    grid = e4m3_grid()
+    finite = np.flatnonzero(~np.isnan(grid) & ~((grid == 0) & (np.arange(256) >= 128)))  # drop NaNs and -0
+    order = finite[np.argsort(grid[finite], kind="stable")]
+    vals = grid[order]
+    hi = np.clip(np.searchsorted(vals, target), 1, len(vals) - 1)
+    lo = hi - 1
+    pick = np.where(np.abs(target - vals[lo]) <= np.abs(vals[hi] - target), lo, hi)
+    return order[pick].astype(np.uint8)
+
+
+def codes_e4m3(key: int, count: int, start: int = 0, force_numpy: bool = False) -> np.ndarray:
+    """`count` E4M3 codes (uint8) of stream `key`, elements start .. start+count-1: element i is
+    code_table_e4m3()[16-bit field (i % 4) of the hash of counter i // 4] — the same walk as normal_bf16."""
+    table = code_table_e4m3()
+    if not force_numpy and count >= (1 << 16) and os.path.exists(synth_lib_path()):
+        lib = _load_synth_lib()
+        lo = start % 4
+        buf = np.empty(count + lo, dtype=np.uint8)
+        rc = lib.synth_fill_u8_host(buf.ctypes.data_as(ctypes.c_void_p), ctypes.c_uint64(key),
+                                    ctypes.c_uint64(start - lo), ctypes.c_uint64(count + lo),
+                                    table.ctypes.data_as(ctypes.c_void_p), min(16, os.cpu_count() or 1))
+        if rc != 0:
+            raise RuntimeError("synth_fill_u8_host failed")
+        return buf[lo:]
+    b0 = start // 4
+    b1 = (start + count + 3) // 4
+    out = np.empty((b1 - b0) * 4, dtype=np.uint8)
+    step = 1 << 24
+    for s in range(b0, b1, step):
+        n = min(step, b1 - s)
+        h = hash_blocks(key, s, n)
+        idx = h.view(np.uint16).reshape(n, 4)
+        out[(s - b0) * 4:(s - b0 + n) * 4] = table[idx.reshape(-1)]
+    lo = start - b0 * 4
+    return out[lo:lo + count]
+
+
+def channel_scales(key: int, rows: int, sigma: float = SIGMA_EXPERT) -> np.ndarray:
+    """One fp32 scale per output channel: the value that maps code magnitude 448 to 4.32 sigma, times a
+    per-row factor uniform in [0.75, 1.25) (rows of a real checkpoint do not share one scale)."""
+    u = uniforms(key, rows)
+    base = sigma * 4.32 / E4M3_MAX
+    return (base * (0.75 + 0.5 * u)).astype(np.float32)
+
+
+def fp8_weight_spec(cfg: MoEConfig):
+    """(code tensor, scale tensor, code shape) of every FP8 expert tensor of a layer."""
+    spec = [("q1", "s1", (cfg.n_experts, cfg.ffn, cfg.d)), ("q3", "s3", (cfg.n_experts, cfg.ffn, cfg.d)),
+            ("q2", "s2", (cfg.n_experts, cfg.d, cfg.ffn))]
+    if cfg.n_shared:
+        spec += [("sq1", "ss1", (cfg.n_shared, cfg.ffn, cfg.d)), ("sq3", "ss3", (cfg.n_shared, cfg.ffn, cfg.d)),
+                 ("sq2", "ss2", (cfg.n_shared, cfg.d, cfg.ffn))]
+    return spec
+
+
+def layer_weights_fp8_host(cfg: MoEConfig, layer: int = 0) -> dict:
+    """FP8 layer: router_w as in layer_weights_host (bf16 bits); q* uint8 codes, row-major; s* fp32 [.., rows]."""
+    out = {"router_w": normal_bf16(weight_key(cfg, layer, T_ROUTER), SIGMA_ROUTER,
+                                   cfg.n_experts * cfg.d).reshape(cfg.n_experts, cfg.d)}
+    for qn, sn, shape in fp8_weight_spec(cfg):
+        out[qn] = codes_e4m3(weight_key(cfg, layer, T_Q[qn]), int(np.prod(shape))).reshape(shape)
+        out[sn] = channel_scales(weight_key(cfg, layer, T_S[sn]), shape[0] * shape[1]).reshape(shape[:2])
+    return out
+
+
 def hidden_host(cfg: MoEConfig, layer: int, iteration: int, T: int, rho: float) -> np.ndarray:
     """hidden[T, d] fp32.  Row t does not depend on T (nested K sweeps see nested inputs)."""
     d = cfg.d
@@ -278,6 +374,10 @@ def _load_synth_lib():
         lib.synth_fill_bf16_host.restype = ctypes.c_int
         lib.synth_fill_bf16_host.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                              ctypes.c_void_p, ctypes.c_int]
+        lib.synth_fill_u8.restype = ctypes.c_int
+        lib.synth_fill_u8.argtypes = lib.synth_fill_bf16.argtypes
+        lib.synth_fill_u8_host.restype = ctypes.c_int
+        lib.synth_fill_u8_host.argtypes = lib.synth_fill_bf16_host.argtypes
         _SYNTH_LIB = lib
     return _SYNTH_LIB
 
@@ -312,4 +412,36 @@ def layer_weights_device(cfg: MoEConfig, layer: int, device="cuda:0") -> dict:
         t = torch.empty(shape, dtype=torch.int16, device=device)
         fill_normal_bf16_device(t, weight_key(cfg, layer, tid), sigma)
         out[name] = t
+    return out
+
+
+def fill_codes_e4m3_device(dst, key: int, start: int = 0, stream_ptr: int = 0) -> None:
+    """Fill a contiguous torch uint8 CUDA tensor with elements start.. of code stream `key`."""
+    import torch
+    assert dst.is_cuda and dst.is_contiguous() and dst.element_size() == 1
+    lib = _load_synth_lib()
+    tkey = ("e4m3", dst.device.index)
+    if tkey not in _DEV_TABLES:
+        _DEV_TABLES[tkey] = torch.from_numpy(code_table_e4m3().copy()).to(dst.device)
+    tab = _DEV_TABLES[tkey]
+    if stream_ptr == 0:
+        stream_ptr = torch.cuda.current_stream(dst.device).cuda_stream
+    rc = lib.synth_fill_u8(ctypes.c_void_p(dst.data_ptr()), ctypes.c_uint64(key), ctypes.c_uint64(start),
+                           ctypes.c_uint64(dst.numel()), ctypes.c_void_p(tab.data_ptr()), ctypes.c_void_p(stream_ptr))
+    if rc != 0:
+        raise RuntimeError(f"synth_fill_u8 failed with HIP error {rc}")
+
+
+def layer_weights_fp8_device(cfg: MoEConfig, layer: int, device="cuda:0") -> dict:
+    """Same tensors as layer_weights_fp8_host: codes generated directly in HBM, scales and router uploaded."""
+    import torch
+    rw = torch.empty((cfg.n_experts, cfg.d), dtype=torch.int16, device=device)
+    fill_normal_bf16_device(rw, weight_key(cfg, layer, T_ROUTER), SIGMA_ROUTER)
+    out = {"router_w": rw}
+    for qn, sn, shape in fp8_weight_spec(cfg):
+        t = torch.empty(shape, dtype=torch.uint8, device=device)
+        fill_codes_e4m3_device(t, weight_key(cfg, layer, T_Q[qn]))
+        out[qn] = t
+        sc = channel_scales(weight_key(cfg, layer, T_S[sn]), shape[0] * shape[1]).reshape(shape[:2])
+        out[sn] = torch.from_numpy(sc).to(device)
     return out

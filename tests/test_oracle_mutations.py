@@ -8,6 +8,7 @@ import pytest
 
 from oracle import moe_oracle as orc
 import test_oracle_pins as pins
+import test_oracle_fp8_pins as fp8pins
 
 MUTANTS = {
     "swap_w1_w3_roles": ("h[r] = (g / ((REAL)1 + real_exp(-g))) * u;", "h[r] = (u / ((REAL)1 + real_exp(-u))) * g;"),
@@ -30,6 +31,32 @@ MUTANTS = {
                         "const float* x = hidden;\n    for (int c = 0; c < d; ++c) acc[c] = 0;\n    for (int i = 0; i < top_k; ++i) {"),
 }
 
+MUTANTS_FP8 = {
+    "fp8_exponent_bias_8": ("ldexp(1.0 + (double)man / 8.0, ex - 7)", "ldexp(1.0 + (double)man / 8.0, ex - 8)"),
+    "fp8_subnormal_read_as_normal": ("  if (ex == 0)\n    v = ldexp((double)man / 8.0, -6);\n  else\n", ""),
+    "fp8_subnormal_flushed": ("v = ldexp((double)man / 8.0, -6);", "v = 0.0;"),
+    "fp8_four_mantissa_bits": ("ldexp(1.0 + (double)man / 8.0, ex - 7)", "ldexp(1.0 + (double)man / 16.0, ex - 7)"),
+    "fp8_sign_ignored": ("return sign ? -v : v;", "return v;"),
+    "fp8_top_exponent_is_inf_nan": ("if (ex == 15 && man == 7) return NAN;", "if (ex == 15) return NAN;"),
+    "fp8_scale_per_column": ("((REAL)s1[r] * val[q1[(size_t)r * d + j]])", "((REAL)s1[j % ffn] * val[q1[(size_t)r * d + j]])"),
+    "fp8_w3_uses_w1_scale": ("((REAL)s3[r] * val[q3[(size_t)r * d + j]])", "((REAL)s1[r] * val[q3[(size_t)r * d + j]])"),
+    "fp8_down_scale_dropped": ("((REAL)s2[c] * val[q2[(size_t)c * ffn + r]])", "(val[q2[(size_t)c * ffn + r]])"),
+    "fp8_down_transposed": ("val[q2[(size_t)c * ffn + r]]", "val[q2[(size_t)r * d + c]]"),
+    "fp8_expert_scale_offset_missing": ("q1 + e * per, s1 + (size_t)e * ffn,", "q1 + e * per, s1,"),
+    "fp8_shared_scale_offset_missing": ("sq2 + s * per, ss2 + (size_t)s * d,", "sq2 + s * per, ss2,"),
+    "fp8_gate_dropped": ("      REAL g = (REAL)gates[(size_t)t * top_k + i];\n      for (int c = 0; c < d; ++c) acc[c] += g * y[c];\n    }\n    for (int s = 0; s < n_shared; ++s) {\n      oracle_expert_ffn_fp8",
+                         "      for (int c = 0; c < d; ++c) acc[c] += y[c];\n    }\n    for (int s = 0; s < n_shared; ++s) {\n      oracle_expert_ffn_fp8"),
+}
+
+PIN_CALLS_FP8 = [
+    lambda: fp8pins.test_e4m3_golden_corner_values(),
+    lambda: fp8pins.test_e4m3_all_codes_match_library_type_and_structure(),
+    lambda: fp8pins.test_fp8_ffn_equals_bf16_oracle_when_effective_weights_fit_bf16("f64"),
+    lambda: fp8pins.test_fp8_ffn_general_scales_is_three_library_gemvs(),
+    lambda: fp8pins.test_fp8_row_scales_closed_form("f64"),
+    lambda: fp8pins.test_fp8_combine_gate_weighting_experts_and_shared("f64"),
+]
+
 PIN_CALLS = [
     lambda: pins.test_route_brute_force("f64", 8, 2),
     lambda: pins.test_route_ties_go_to_lower_index_and_uniform_gates("f64"),
@@ -44,9 +71,10 @@ PIN_CALLS = [
 ]
 
 
-@pytest.mark.parametrize("name", sorted(MUTANTS))
+@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8))
 def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
-    old, new = MUTANTS[name]
+    old, new = (MUTANTS if name in MUTANTS else MUTANTS_FP8)[name]
+    calls = PIN_CALLS if name in MUTANTS else PIN_CALLS_FP8
     src = open(os.path.join(os.path.dirname(orc.__file__), "moe_oracle.c")).read()
     assert src.count(old) >= 1, f"mutation site for {name} not found"
     mutated = src.replace(old, new, 1)
@@ -59,7 +87,7 @@ def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
     orc._lib("f64")
     monkeypatch.setitem(orc._LIBS, "f64", mutant)
     caught = False
-    for call in PIN_CALLS:
+    for call in calls:
         try:
             call()
         except (AssertionError, ValueError):

@@ -81,3 +81,29 @@ def test_regimes_and_causal_acceptance():
             assert abs(tok.mean() - expect) < 0.12
     # nested in K: a longer draft never emits fewer tokens on the same iteration
     assert all(synth.tokens_emitted(u[i], 0.8, 8) >= synth.tokens_emitted(u[i], 0.8, 3) for i in range(200))
+
+
+def test_fp8_code_streams_and_scales():
+    """E4M3 code streams: finite codes only, numpy definition == threaded C twin, any slice regenerates, and the
+    effective weights scale * value(code) have the bf16 recipe's spread."""
+    tab = synth.code_table_e4m3()
+    grid = synth.e4m3_grid()
+    assert tab.dtype == np.uint8 and tab.shape == (65536,)
+    assert not np.isin(tab, (0x7F, 0xFF, 0x80)).any()                  # no NaN code, no negative zero
+    assert grid[tab[0]] == -448.0 and grid[tab[-1]] == 448.0
+    assert np.all(np.diff(grid[tab]) >= 0)                             # monotone in the quantile index
+    key = synth.stream_key(9, 9, 9)
+    a = synth.codes_e4m3(key, 70_001, 5, force_numpy=True)
+    assert np.array_equal(a[100:200], synth.codes_e4m3(key, 100, 105, force_numpy=True))
+    import os
+    if os.path.exists(synth.synth_lib_path()):
+        assert np.array_equal(a, synth.codes_e4m3(key, 70_001, 5))
+    W = synth.layer_weights_fp8_host(synth.TINY, 0)
+    assert W["q1"].shape == (8, 1024, 512) and W["s1"].shape == (8, 1024) and W["q2"].shape == (8, 512, 1024)
+    assert W["s2"].shape == (8, 512) and W["s1"].dtype == np.float32 and W["q3"].dtype == np.uint8
+    assert np.array_equal(W["router_w"], synth.layer_weights_host(synth.TINY, 0)["router_w"])
+    w = W["s1"].astype(np.float64)[:, :, None] * grid[W["q1"]]
+    assert abs(w.std() - synth.SIGMA_EXPERT) < 0.002 and abs(w.mean()) < 1e-4
+    base = synth.SIGMA_EXPERT * 4.32 / 448.0
+    assert W["s1"].min() >= 0.75 * base * 0.999 and W["s1"].max() <= 1.25 * base * 1.001
+    assert synth.MIXTRAL.expert_bytes_fp8 == 176_160_768
