@@ -96,32 +96,56 @@ moe_status moe_group(moe_ctx* ctx, const int32_t* ids, int32_t T, int32_t* uniqu
 
 /* Storage order of the expert matrices (the router is always row-major).
  * MOE_LAYOUT_ROW_MAJOR: dense row-major as listed below.
- * MOE_LAYOUT_TILED:     same bytes, re-ordered once by moe_pack_weights so that the 16-row x 32-column
- *                       block a wavefront consumes per step is 1 KB of contiguous memory (block
- *                       (i, s) = rows 16i..16i+15, columns 32s..32s+31 at block index i*(K/32)+s; inside
- *                       a block, 16-byte unit l = r + 16*g holds row 16i+r, columns 32s+8g..32s+8g+7).
+ * MOE_LAYOUT_TILED:     same bytes, re-ordered once by moe_pack_weights so that the block of 16 rows
+ *                       a wavefront consumes per step is 1 KB of contiguous memory.
+ *                       bf16: block (i, s) = rows 16i..16i+15, columns 32s..32s+31 at block index
+ *                       i*(K/32)+s; inside a block, 16-byte unit l = r + 16*g holds row 16i+r, columns
+ *                       32s+8g..32s+8g+7.
+ *                       FP8: block (i, p) = rows 16i..16i+15, columns 64p..64p+63 at block index
+ *                       i*(K/64)+p; unit l = r + 16*g holds row 16i+r, columns 64p+8g..64p+8g+7
+ *                       followed by columns 64p+32+8g..64p+32+8g+7.
  *                       Per-matrix and per-expert sizes are unchanged. */
 enum { MOE_LAYOUT_ROW_MAJOR = 0, MOE_LAYOUT_TILED = 1 };
 
-/* One layer's weights: DEVICE pointers, caller-owned, bf16, alive until the stream drains.
- * sw1/sw3/sw2 are required iff shape.n_shared > 0.  Every pointer must be 16-byte aligned. */
+/* Element type of the expert matrices (Table 1 of the paper lists bf16/fp16 and FP8 checkpoints;
+ * Section 6.1: quantised models).  The paper does not define the FP8 scheme; the one built here:
+ * MOE_WEIGHT_FP8_E4M3: one byte per weight, E4M3 (1 sign, 4 exponent bits biased by 7, 3 mantissa
+ *                      bits, no infinities, S.1111.111 = NaN, largest finite value 448), and one fp32
+ *                      scale per OUTPUT channel (matrix row): weight = scale[row] * value(code).
+ *                      Activations, accumulation and the router are as for bf16.  d and ffn must be
+ *                      multiples of 64.  moe_verify_layer / moe_verify_stack take FP8 weights in the
+ *                      TILED layout only (row-major FP8 returns MOE_ERR_UNIMPLEMENTED: pack first). */
+enum { MOE_WEIGHT_BF16 = 0, MOE_WEIGHT_FP8_E4M3 = 1 };
+
+/* One layer's weights: DEVICE pointers, caller-owned, alive until the stream drains.
+ * sw1/sw3/sw2 (and their scales) are required iff shape.n_shared > 0.  The scale pointers are read
+ * only for MOE_WEIGHT_FP8_E4M3 and are always plain row-major fp32.  Every pointer must be 16-byte
+ * aligned. */
 typedef struct {
-  const uint16_t* router_w; /* [E, d]              */
-  const uint16_t* w1;       /* [E, ffn, d]  gate   */
-  const uint16_t* w3;       /* [E, ffn, d]  up     */
-  const uint16_t* w2;       /* [E, d, ffn]  down   */
-  const uint16_t* sw1;      /* [n_shared, ffn, d]  */
-  const uint16_t* sw3;      /* [n_shared, ffn, d]  */
-  const uint16_t* sw2;      /* [n_shared, d, ffn]  */
-  int32_t layout;           /* MOE_LAYOUT_* of w1, w3, w2, sw1, sw3, sw2 */
+  const uint16_t* router_w; /* [E, d] bf16                               */
+  const void* w1;           /* [E, ffn, d]  gate   bf16 or FP8 codes      */
+  const void* w3;           /* [E, ffn, d]  up                            */
+  const void* w2;           /* [E, d, ffn]  down                          */
+  const void* sw1;          /* [n_shared, ffn, d]                         */
+  const void* sw3;          /* [n_shared, ffn, d]                         */
+  const void* sw2;          /* [n_shared, d, ffn]                         */
+  int32_t layout;           /* MOE_LAYOUT_* of w1, w3, w2, sw1, sw3, sw2  */
+  int32_t dtype;            /* MOE_WEIGHT_* of w1, w3, w2, sw1, sw3, sw2  */
+  const float* w1_scale;    /* [E, ffn]        FP8 only                   */
+  const float* w3_scale;    /* [E, ffn]                                   */
+  const float* w2_scale;    /* [E, d]                                     */
+  const float* sw1_scale;   /* [n_shared, ffn]                            */
+  const float* sw3_scale;   /* [n_shared, ffn]                            */
+  const float* sw2_scale;   /* [n_shared, d]                              */
 } moe_layer_weights;
 
 /* One-off static re-layout of a layer's expert weights for streaming (weights do not change while
  * serving, so this runs once at load time, outside the path the paper's Section 2.4 cost is about).
  * src: row-major weights.  dst: HOST struct whose DEVICE pointers the caller has set to buffers of
  * the same sizes as src's (dst->router_w may equal src->router_w; otherwise the router is copied).
- * On success dst->layout is set to MOE_LAYOUT_TILED.  Enqueues on `stream`; src and dst buffers
- * must not overlap. */
+ * On success dst->layout is set to MOE_LAYOUT_TILED, dst->dtype to src->dtype and the scale
+ * pointers of dst to those of src (scales are not re-ordered).  Enqueues on `stream`; src and dst
+ * buffers must not overlap. */
 moe_status moe_pack_weights(moe_ctx* ctx, const moe_layer_weights* src, moe_layer_weights* dst, void* stream);
 
 /* Steps 1-5 — the whole verification step of one MoE layer (Section 2.2: the target model

@@ -36,7 +36,13 @@ class MoeShape(ctypes.Structure):
 
 
 class MoeLayerWeights(ctypes.Structure):
-    _fields_ = [(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")] + [("layout", c_int32)]
+    _fields_ = ([(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")]
+                + [("layout", c_int32), ("dtype", c_int32)]
+                + [(n, c_void_p) for n in ("w1_scale", "w3_scale", "w2_scale", "sw1_scale", "sw3_scale", "sw2_scale")])
+
+
+MOE_LAYOUT_ROW_MAJOR, MOE_LAYOUT_TILED = 0, 1
+MOE_WEIGHT_BF16, MOE_WEIGHT_FP8_E4M3 = 0, 1
 
 
 class CascadeParams(ctypes.Structure):
@@ -152,22 +158,40 @@ def _want_bf16(t, shape, name):
 
 
 class LayerWeights:
-    """Device pointers of one layer's bf16 weights (tensors stay owned by the caller)."""
+    """Device pointers of one layer's weights (tensors stay owned by the caller).
+    dtype = MOE_WEIGHT_BF16: 16-bit expert tensors; MOE_WEIGHT_FP8_E4M3: uint8 codes + fp32 per-row `scales`
+    (w1_scale [E,ffn], w3_scale [E,ffn], w2_scale [E,d], then the three of the shared experts)."""
 
-    def __init__(self, shape: "MoeShape", router_w, w1, w3, w2, sw1=None, sw3=None, sw2=None, layout=0):
+    def __init__(self, shape: "MoeShape", router_w, w1, w3, w2, sw1=None, sw3=None, sw2=None, layout=0,
+                 dtype=MOE_WEIGHT_BF16, scales=None):
+        import torch
         E, d, f, ns = shape.n_experts, shape.d, shape.ffn, shape.n_shared
         _want_bf16(router_w, (E, d), "router_w")
-        _want_bf16(w1, (E, f, d), "w1")
-        _want_bf16(w3, (E, f, d), "w3")
-        _want_bf16(w2, (E, d, f), "w2")
+        if dtype == MOE_WEIGHT_BF16:
+            want = _want_bf16
+        else:
+            want = lambda t, shp, name: _want(t, torch.uint8, shp, name)
+        want(w1, (E, f, d), "w1")
+        want(w3, (E, f, d), "w3")
+        want(w2, (E, d, f), "w2")
         if ns:
-            _want_bf16(sw1, (ns, f, d), "sw1")
-            _want_bf16(sw3, (ns, f, d), "sw3")
-            _want_bf16(sw2, (ns, d, f), "sw2")
+            want(sw1, (ns, f, d), "sw1")
+            want(sw3, (ns, f, d), "sw3")
+            want(sw2, (ns, d, f), "sw2")
             if sw1 is None or sw3 is None or sw2 is None:
                 raise ValueError("shared expert weights required")
         self.tensors = (router_w, w1, w3, w2, sw1, sw3, sw2)
-        self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors], layout)
+        self.scales = tuple(scales) if scales is not None else (None,) * 6
+        if dtype == MOE_WEIGHT_FP8_E4M3:
+            shapes = ((E, f), (E, f), (E, d), (ns, f), (ns, f), (ns, d))
+            for t, shp, name in zip(self.scales, shapes, ("w1_scale", "w3_scale", "w2_scale", "sw1_scale", "sw3_scale",
+                                                          "sw2_scale")):
+                if t is None and (ns or not name.startswith("s")):
+                    raise ValueError(f"{name} required for FP8 weights")
+                _want(t, torch.float32, shp, name)
+        self.dtype = dtype
+        self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors], layout, dtype,
+                                 *[None if t is None else t.data_ptr() for t in self.scales])
 
 
 class MoeContext:
@@ -194,6 +218,12 @@ class MoeContext:
         return int(lib().moe_ctx_workspace_bytes(self._h))
 
     def weights(self, W: dict) -> LayerWeights:
+        """bf16 layer from a dict with router_w, w1, w3, w2 (sw1, sw3, sw2); FP8 layer from a dict with router_w,
+        q1, q3, q2 (uint8 codes), s1, s3, s2 (fp32 per-row scales) and sq*/ss* for shared experts."""
+        if "q1" in W:
+            return LayerWeights(self.shape, W["router_w"], W["q1"], W["q3"], W["q2"], W.get("sq1"), W.get("sq3"),
+                                W.get("sq2"), dtype=MOE_WEIGHT_FP8_E4M3,
+                                scales=(W["s1"], W["s3"], W["s2"], W.get("ss1"), W.get("ss3"), W.get("ss2")))
         return LayerWeights(self.shape, W["router_w"], W["w1"], W["w3"], W["w2"], W.get("sw1"), W.get("sw3"),
                             W.get("sw2"))
 
@@ -214,7 +244,7 @@ class MoeContext:
         import torch
         bufs = [None if t is None else torch.empty_like(t) for t in src.tensors]
         bufs[0] = src.tensors[0]            # router is shared, it stays row-major
-        dst = LayerWeights(self.shape, *bufs, layout=0)
+        dst = LayerWeights(self.shape, *bufs, layout=0, dtype=src.dtype, scales=src.scales)
         _check(lib().moe_pack_weights(self._h, byref(src.c), byref(dst.c), _stream_ptr(stream)), "moe_pack_weights")
         return dst
 

@@ -77,6 +77,21 @@ __device__ __forceinline__ size_t frag_unit(int k8, int n) {  // k8 = k / 8
   return (size_t)(k8 >> 2) * 64 + (size_t)(k8 & 3) * 16 + n;
 }
 
+// FP8 weights: the 16 bytes a lane loads are its 8 codes of one k-step followed by its 8 codes of the
+// next k-step.  Every E4M3 value is exactly a bf16 number, so the codes are widened in registers (two
+// codes per instruction) and fed to the same bf16 MFMA; the per-row scale is applied to the fp32 sums.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+template <bool HI>
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t v) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v, 1.0f, HI));
+}
+__device__ __forceinline__ void fp8x16_to_bf16(uint4 a, uint4& k0, uint4& k1) {
+  k0 = uint4{fp8x2_to_bf16x2<false>(a.x), fp8x2_to_bf16x2<true>(a.x), fp8x2_to_bf16x2<false>(a.y),
+             fp8x2_to_bf16x2<true>(a.y)};
+  k1 = uint4{fp8x2_to_bf16x2<false>(a.z), fp8x2_to_bf16x2<true>(a.z), fp8x2_to_bf16x2<false>(a.w),
+             fp8x2_to_bf16x2<true>(a.w)};
+}
+
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
                                                   0, 0);
@@ -374,19 +389,20 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
 
 // ------------------------------------------------------------------------------------------
 // Shared software pipeline of the two expert kernels.
-//   NA  A tiles (16 rows x 32 k) consumed per k-step, each with its own wave-uniform base pointer
-//   P   pipeline depth (k-steps of loads in flight per wave)
-// A stage holds one 128-bit load per tile plus the hi and lo activation fragments.
+//   NA  A tiles (16 rows) consumed per step, each with its own wave-uniform base pointer
+//   NB  k-steps (32 k) one 128-bit weight load covers: 1 for bf16, 2 for FP8
+//   P   pipeline depth (steps of loads in flight per wave)
+// A stage holds one 128-bit load per tile plus the hi and lo activation fragments of its NB k-steps.
 // ------------------------------------------------------------------------------------------
-template <int NA>
+template <int NA, int NB>
 struct Stage {
   uint4 a[NA];
-  uint4 bh, bl;
+  uint4 bh[NB], bl[NB];
 };
 
-template <int NA, int P, class Load, class Compute>
+template <int NA, int NB, int P, class Load, class Compute>
 __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
-  Stage<NA> st[P];
+  Stage<NA, NB> st[P];
   // The prologue loads are unconditional (a short wave re-reads its last valid step): a load that
   // is issued on only some paths makes the compiler's wait counters pessimistic inside the loop.
   const int last = nst > 0 ? nst - 1 : 0;
@@ -412,20 +428,21 @@ __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Weight addressing.  A k-step of a 16-row tile is 16 rows x 32 k = 1 KB of bf16.
-//   row-major [rows, K]:  lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg
-//   tiled              :  the same 1 KB stored contiguously, block index tile*(K/32) + s, lane l at
-//                         byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
+// Weight addressing.  A step of a 16-row tile is 1 KB: 16 rows x 32 k of bf16, or 16 rows x 64 k of FP8.
+//   row-major [rows, K]:  lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg   (bf16 only)
+//   tiled              :  the same 1 KB stored contiguously, block index tile*(steps per row) + s, lane
+//                         l at byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
 // ------------------------------------------------------------------------------------------
-template <bool TILED>
+template <bool TILED, bool FP8>
 struct WeightAddr {
   uint32_t lane_off, step_stride;
   size_t tile_stride;
   __device__ __forceinline__ WeightAddr(int K, int r, int kg, int lane) {
+    static_assert(TILED || !FP8, "FP8 weights are consumed in the tiled layout only");
     if constexpr (TILED) {
       lane_off = lane * 16;
       step_stride = 1024;
-      tile_stride = (size_t)(K >> 5) * 1024;
+      tile_stride = (size_t)(K >> (FP8 ? 6 : 5)) * 1024;
     } else {
       lane_off = ((uint32_t)r * K + kg * 8) * 2;
       step_stride = 64;
@@ -439,7 +456,8 @@ struct WeightAddr {
 // grid = (row blocks of 16*R rows of ffn, min(E, T*top_k) + n_shared slots); block = W waves that split d.
 // ------------------------------------------------------------------------------------------
 struct GateupArgs {
-  const uint16_t *w1, *w3, *sw1, *sw3;  // [E,ffn,d] / [n_shared,ffn,d]
+  const void *w1, *w3, *sw1, *sw3;      // [E,ffn,d] / [n_shared,ffn,d], bf16 or FP8 codes
+  const float *s1, *s3, *ss1, *ss3;     // FP8 only: per-row scales [E,ffn] / [n_shared,ffn]
   const uint16_t *xf_hi, *xf_lo;        // activation fragments, d*16 elements each
   const int32_t* n_unique;              // [1]        size of the union                   } written by the
   const int32_t* slot_expert;           // [u_max]    expert of slot u (ascending)        } grouping step
@@ -448,12 +466,14 @@ struct GateupArgs {
   int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
 };
 
-template <int R, int W, int P, bool TILED, bool NT>
+template <int R, int W, int P, bool TILED, bool NT, bool FP8>
 __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
+  constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const char *W1, *W3;
-  const size_t per = (size_t)g.ffn * g.d * 2;
+  const float *S1 = nullptr, *S3 = nullptr;  // FP8: scale rows of this expert
+  const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
   float gate;
   int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
   if (slot < g.routed_slots) {
@@ -464,18 +484,27 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
     if (slot >= nu) return;  // beyond the union of this step
     W1 = reinterpret_cast<const char*>(g.w1) + e * per;
     W3 = reinterpret_cast<const char*>(g.w3) + e * per;
+    if constexpr (FP8) {
+      S1 = g.s1 + (size_t)e * g.ffn;
+      S3 = g.s3 + (size_t)e * g.ffn;
+    }
   } else {
     gate = 1.f;  // shared expert: every token, gate 1
-    W1 = reinterpret_cast<const char*>(g.sw1) + (slot - g.routed_slots) * per;
-    W3 = reinterpret_cast<const char*>(g.sw3) + (slot - g.routed_slots) * per;
-    slot = g.u_max + (slot - g.routed_slots);  // buffers keep shared experts after the largest union
+    const int sh = slot - g.routed_slots;
+    W1 = reinterpret_cast<const char*>(g.sw1) + sh * per;
+    W3 = reinterpret_cast<const char*>(g.sw3) + sh * per;
+    if constexpr (FP8) {
+      S1 = g.ss1 + (size_t)sh * g.ffn;
+      S3 = g.ss3 + (size_t)sh * g.ffn;
+    }
+    slot = g.u_max + sh;  // buffers keep shared experts after the largest union
   }
   const int ntiles = g.ffn >> 4, tile0 = blockIdx.x * R;
-  const int nsteps = g.d >> 5, chunk = (nsteps + W - 1) / W;
+  const int nsteps = g.d >> (FP8 ? 6 : 5), chunk = (nsteps + W - 1) / W;
   const int nst = max(0, min(chunk, nsteps - wave * chunk));
   const int s_beg = min(wave * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
 
-  const WeightAddr<TILED> wa(g.d, r, kg, lane);
+  const WeightAddr<TILED, FP8> wa(g.d, r, kg, lane);
   const char* base[2 * R];
 #pragma unroll
   for (int j = 0; j < R; ++j) {
@@ -483,27 +512,42 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
     base[j] = W1 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
     base[R + j] = W3 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
   }
-  const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * 1024;
-  const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * 1024;
+  const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * (1024 * NB);
+  const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * (1024 * NB);
   const uint32_t b_off = lane * 16;
 
   f32x4 acc[2 * R];
 #pragma unroll
   for (int j = 0; j < 2 * R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  pipeline<2 * R, P>(
+  pipeline<2 * R, NB, P>(
       nst,
-      [&](Stage<2 * R>& st, int s) {
+      [&](Stage<2 * R, NB>& st, int s) {
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
-        st.bh = ld128<false>(XH, b_off + (uint32_t)s * 1024);
-        st.bl = ld128<false>(XL, b_off + (uint32_t)s * 1024);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          st.bh[b] = ld128<false>(XH, b_off + (uint32_t)(s * NB + b) * 1024);
+          st.bl[b] = ld128<false>(XL, b_off + (uint32_t)(s * NB + b) * 1024);
+        }
       },
-      [&](const Stage<2 * R>& st) {
+      [&](const Stage<2 * R, NB>& st) {
+        if constexpr (FP8) {
 #pragma unroll
-        for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh, acc[j]);
+          for (int j = 0; j < 2 * R; ++j) {
+            uint4 k0, k1;
+            fp8x16_to_bf16(st.a[j], k0, k1);
+            acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
+            acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+          }
+        } else {
 #pragma unroll
-        for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl, acc[j]);
+          for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+#pragma unroll
+          for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+        }
       });
 
   // reduce the W k-slices through LDS, then wave w finishes tiles w, w+W, ...
@@ -531,6 +575,12 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       G = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
       U = float4{acc[R + j][0], acc[R + j][1], acc[R + j][2], acc[R + j][3]};
     }
+    if constexpr (FP8) {  // the lane's four rows of the tile are consecutive: one 16-byte load per scale vector
+      const float4 c1 = *reinterpret_cast<const float4*>(S1 + (tile0 + j) * 16 + kg * 4);
+      const float4 c3 = *reinterpret_cast<const float4*>(S3 + (tile0 + j) * 16 + kg * 4);
+      G.x *= c1.x, G.y *= c1.y, G.z *= c1.z, G.w *= c1.w;
+      U.x *= c3.x, U.y *= c3.y, U.z *= c3.z, U.w *= c3.w;
+    }
     if (r < g.T && gate != 0.f) {
       // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r: four consecutive k of the
       // down projection, i.e. one half of a 16-byte fragment unit
@@ -556,7 +606,8 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
 // splitting the chunk.
 // ------------------------------------------------------------------------------------------
 struct DownArgs {
-  const uint16_t *w2, *sw2;       // [E,d,ffn] / [n_shared,d,ffn]
+  const void *w2, *sw2;           // [E,d,ffn] / [n_shared,d,ffn], bf16 or FP8 codes
+  const float *s2, *ss2;          // FP8 only: per-row scales [E,d] / [n_shared,d]
   const uint16_t *hf_hi, *hf_lo;  // [u_max + n_shared] fragments, ffn*16 elements each
   const int32_t* n_unique;
   const int32_t* slot_expert;
@@ -565,14 +616,16 @@ struct DownArgs {
   int d, ffn, T, routed_slots, u_max, max_tokens, KS;
 };
 
-template <int R, int W, int P, bool TILED, bool NT>
+template <int R, int W, int P, bool TILED, bool NT, bool FP8>
 __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
+  constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * R * 64 : 1];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int ks = blockIdx.z;
   int slot = blockIdx.y;
   const char* W2;
-  const size_t per = (size_t)g.ffn * g.d * 2;
+  const float* S2 = nullptr;
+  const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
   bool live;  // token column r contributes only if the token is routed to this expert
   if (slot < g.routed_slots) {
     const int nu = *g.n_unique;  // three independent loads, one round trip
@@ -580,46 +633,66 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
     live = g.slot_gate[slot * kGateCols + r] != 0.f;  // 0 also for the padded columns r >= T
     if (slot >= nu) return;
     W2 = reinterpret_cast<const char*>(g.w2) + e * per;
+    if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
   } else {
     live = r < g.T;
-    W2 = reinterpret_cast<const char*>(g.sw2) + (slot - g.routed_slots) * per;
-    slot = g.u_max + (slot - g.routed_slots);
+    const int sh = slot - g.routed_slots;
+    W2 = reinterpret_cast<const char*>(g.sw2) + sh * per;
+    if constexpr (FP8) S2 = g.ss2 + (size_t)sh * g.d;
+    slot = g.u_max + sh;
   }
   const int ntiles = g.d >> 4, tile0 = blockIdx.x * R;
-  const int nsteps = g.ffn >> 5, parts = g.KS * W, chunk = (nsteps + parts - 1) / parts;
+  const int nsteps = g.ffn >> (FP8 ? 6 : 5), parts = g.KS * W, chunk = (nsteps + parts - 1) / parts;
   const int nst = max(0, min(chunk, nsteps - (ks * W + wave) * chunk));
   const int s_beg = min((ks * W + wave) * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
 
-  const WeightAddr<TILED> wa(g.ffn, r, kg, lane);
+  const WeightAddr<TILED, FP8> wa(g.ffn, r, kg, lane);
   const char* base[R];
 #pragma unroll
   for (int j = 0; j < R; ++j)
     base[j] = W2 + (size_t)min(tile0 + j, ntiles - 1) * wa.tile_stride + (size_t)s_beg * wa.step_stride;
-  const char* HH = reinterpret_cast<const char*>(g.hf_hi) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * 512) * 2;
-  const char* HL = reinterpret_cast<const char*>(g.hf_lo) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * 512) * 2;
+  const char* HH =
+      reinterpret_cast<const char*>(g.hf_hi) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+  const char* HL =
+      reinterpret_cast<const char*>(g.hf_lo) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
   const uint32_t b_off = lane * 16;
 
   f32x4 acc[R];
 #pragma unroll
   for (int j = 0; j < R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  pipeline<R, P>(
+  pipeline<R, NB, P>(
       nst,
-      [&](Stage<R>& st, int s) {
+      [&](Stage<R, NB>& st, int s) {
 #pragma unroll
         for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
-        st.bh = uint4{0u, 0u, 0u, 0u};
-        st.bl = uint4{0u, 0u, 0u, 0u};
-        if (live) {  // H of a token that was not routed here was never written: do not read it
-          st.bh = ld128<false>(HH, b_off + (uint32_t)s * 1024);
-          st.bl = ld128<false>(HL, b_off + (uint32_t)s * 1024);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          st.bh[b] = uint4{0u, 0u, 0u, 0u};
+          st.bl[b] = uint4{0u, 0u, 0u, 0u};
+          if (live) {  // H of a token that was not routed here was never written: do not read it
+            st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+            st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+          }
         }
       },
-      [&](const Stage<R>& st) {
+      [&](const Stage<R, NB>& st) {
+        if constexpr (FP8) {
 #pragma unroll
-        for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh, acc[j]);
+          for (int j = 0; j < R; ++j) {
+            uint4 k0, k1;
+            fp8x16_to_bf16(st.a[j], k0, k1);
+            acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
+            acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+          }
+        } else {
 #pragma unroll
-        for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl, acc[j]);
+          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+#pragma unroll
+          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+        }
       });
 
   if constexpr (W > 1) {
@@ -639,6 +712,10 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       }
     } else {
       y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    }
+    if constexpr (FP8) {  // scaling each split-K partial sum by the row scale = scaling the whole sum
+      const float4 c2 = *reinterpret_cast<const float4*>(S2 + (tile0 + j) * 16 + kg * 4);
+      y.x *= c2.x, y.y *= c2.y, y.z *= c2.z, y.w *= c2.w;
     }
     if (live) {  // nobody reads the slab column of a token that was not routed here
       const size_t o = (((size_t)slot * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
@@ -684,6 +761,21 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint4* __restrict__ src
     const int l = (int)(q & 63), rr = l & 15, kk = l >> 4;
     const size_t tile = blk / nsteps, st = blk % nsteps;
     dst[q] = src[((tile * 16 + rr) * (size_t)K + st * 32 + kk * 8) >> 3];
+  }
+}
+
+// The same for FP8 codes: a 1 KB block holds 16 rows x 64 k; unit l = (r, kg) = the 8 codes of k-step
+// 2p followed by the 8 codes of k-step 2p+1.
+__global__ __launch_bounds__(256) void pack_kernel_fp8(const uint2* __restrict__ src, uint4* __restrict__ dst,
+                                                       size_t rows, int K) {
+  const size_t npairs = (size_t)(K >> 6), units = rows * (size_t)(K >> 4);
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < units; q += (size_t)gridDim.x * 256) {
+    const size_t blk = q >> 6;
+    const int l = (int)(q & 63), rr = l & 15, kk = l >> 4;
+    const size_t tile = blk / npairs, pr = blk % npairs;
+    const size_t i0 = ((tile * 16 + rr) * (size_t)K + pr * 64 + kk * 8) >> 3;
+    const uint2 a = src[i0], b = src[i0 + 4];
+    dst[q] = uint4{a.x, a.y, b.x, b.y};
   }
 }
 
@@ -743,6 +835,7 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
+constexpr int kFp8GateupDepth = 6;  // pipeline depth of the FP8 gate/up kernel (2 KB of codes + 4 KB of fragments per stage)
 
 // Launch plan of the two expert kernels for one (T, weight layout).
 //   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
@@ -754,14 +847,14 @@ struct Plan {
   int gu_R, dn_R, dn_KS;
 };
 
-int ks_cap_for(const moe_shape& s) {
-  const int nsteps = s.ffn / 32;
+int ks_cap_for(const moe_shape& s, bool fp8) {
+  const int nsteps = s.ffn / (fp8 ? 64 : 32);
   int cap = 1;
   while (cap < kMaxKS && nsteps / (kWaves * cap * 2) >= 4) cap *= 2;  // every wave keeps >= 4 k-steps
   return cap;
 }
 
-Plan plan_for(const moe_ctx* c, int T, bool tiled) {
+Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
   const moe_shape& s = c->s;
   // expected number of live expert slots for T tokens under uniform routing (balls into bins)
   double miss = 1.0;
@@ -769,7 +862,7 @@ Plan plan_for(const moe_ctx* c, int T, bool tiled) {
   const double slots = s.n_experts * (1.0 - miss) + s.n_shared;
   Plan p;
   p.gu_R = tiled ? 1 : ((s.ffn / 16 / 2) * kWaves * slots >= 1536 ? 2 : 1);
-  const int cap = ks_cap_for(s);
+  const int cap = ks_cap_for(s, fp8);
   p.dn_R = 1;
   p.dn_KS = cap;
   for (int R : {4, 2, 1}) {
@@ -817,19 +910,21 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
 }
 
 template <int R, int P>
-void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // row-major weights
+void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // row-major bf16 weights
   const dim3 grid((c->s.ffn / 16 + R - 1) / R, a.routed_slots + c->s.n_shared);
-  hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
+  hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
 // Tiled weights are read exactly once in contiguous 1 KB pieces -> streaming loads; row-major weights
 // are read in 64-byte row segments whose cache lines are completed by the next k-step -> cached loads.
 template <int R, int P>
-void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, hipStream_t st) {
+void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipStream_t st) {
   const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS);
-  if (tiled)
-    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true>), grid, dim3(64 * kWaves), 0, st, a);
+  if (fp8)  // tiled only (checked by the caller)
+    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true>), grid, dim3(64 * kWaves), 0, st, a);
+  else if (tiled)
+    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false>), grid, dim3(64 * kWaves), 0, st, a);
   else
-    hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false>), grid, dim3(64 * kWaves), 0, st, a);
+    hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
 
 // One layer-step after validation: router, gate/up, down, slab sum.  The expert-union step has no
@@ -838,19 +933,24 @@ void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, hipStream_t st
 moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
                         float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
   const moe_shape& s = c->s;
-  const bool tiled = w->layout == MOE_LAYOUT_TILED;
-  const Plan p = plan_for(c, T, tiled);
+  const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
+  if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;  // FP8 is streamed in the tiled layout only
+  const Plan p = plan_for(c, T, tiled, fp8);
   mark(c, st);
   launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st);
   mark(c, st);
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
-  GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
+  GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
+                c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
-  if (tiled) {
+  if (fp8) {
+    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
+    hipLaunchKernelGGL((gateup_kernel<1, 1, kFp8GateupDepth, true, true, true>), grid, dim3(64), 0, st, ga);
+  } else if (tiled) {
     // one wave per 16-row tile pair over the whole of d (splitting d over 2 or 4 waves when the union
     // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
     const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
-    hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true>), grid, dim3(64), 0, st, ga);
+    hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false>), grid, dim3(64), 0, st, ga);
   } else {
     switch (p.gu_R) {
       case 4: launch_gateup<4, 2>(c, ga, st); break;
@@ -859,12 +959,12 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     }
   }
   mark(c, st);
-  DownArgs da{w->w2, w->sw2, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert, c->slot_gate, c->partial,
-              s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
+  DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
+              c->slot_gate, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
-    case 4: launch_down<4, 3>(c, da, tiled, st); break;
-    case 2: launch_down<2, 4>(c, da, tiled, st); break;
-    default: launch_down<1, 8>(c, da, tiled, st); break;
+    case 4: launch_down<4, 3>(c, da, tiled, fp8, st); break;
+    case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
+    default: launch_down<1, 8>(c, da, tiled, fp8, st); break;
   }
   mark(c, st);
   const int n4 = T * (s.d / 4);
@@ -880,6 +980,16 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool weights_ok(const moe_ctx* c, const moe_layer_weights* w) {
   if (!w || !w->router_w || !w->w1 || !w->w3 || !w->w2) return false;
   if (w->layout != MOE_LAYOUT_ROW_MAJOR && w->layout != MOE_LAYOUT_TILED) return false;
+  if (w->dtype != MOE_WEIGHT_BF16 && w->dtype != MOE_WEIGHT_FP8_E4M3) return false;
+  if (w->dtype == MOE_WEIGHT_FP8_E4M3) {
+    if (c->s.d % 64 || c->s.ffn % 64) return false;
+    if (!w->w1_scale || !w->w3_scale || !w->w2_scale) return false;
+    if (!aligned16(w->w1_scale) || !aligned16(w->w3_scale) || !aligned16(w->w2_scale)) return false;
+    if (c->s.n_shared > 0) {
+      if (!w->sw1_scale || !w->sw3_scale || !w->sw2_scale) return false;
+      if (!aligned16(w->sw1_scale) || !aligned16(w->sw3_scale) || !aligned16(w->sw2_scale)) return false;
+    }
+  }
   if (!aligned16(w->router_w) || !aligned16(w->w1) || !aligned16(w->w3) || !aligned16(w->w2)) return false;
   if (c->s.n_shared > 0) {
     if (!w->sw1 || !w->sw3 || !w->sw2) return false;
@@ -904,7 +1014,7 @@ const char* moe_strerror(moe_status s) {
   return "unknown status";
 }
 
-int moe_abi_version(void) { return 1; }
+int moe_abi_version(void) { return 2; }
 
 moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (out) *out = nullptr;
@@ -937,10 +1047,11 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   // the slab buffer is sized for the largest split-K factor any T can ask for
   c->ks_alloc = 1;
   for (int T = 1; T <= s.max_tokens; ++T)
-    for (bool tiled : {false, true}) {
-      const int ks = plan_for(c, T, tiled).dn_KS;
-      if (ks > c->ks_alloc) c->ks_alloc = ks;
-    }
+    for (bool tiled : {false, true})
+      for (bool fp8 : {false, true}) {
+        const int ks = plan_for(c, T, tiled, fp8).dn_KS;
+        if (ks > c->ks_alloc) c->ks_alloc = ks;
+      }
 
   const size_t A = (size_t)s.max_tokens * s.top_k;
   size_t off = 0;
@@ -1035,8 +1146,10 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
                             float* out, int32_t* n_unique_per_layer_opt, void* stream) {
   if (!c || !layers || L < 1 || !hidden || !out || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
-  for (int l = 0; l < L; ++l)
+  for (int l = 0; l < L; ++l) {
     if (!weights_ok(c, layers + l)) return MOE_ERR_INVALID_ARG;
+    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
+  }
   if (moe_status st = check_stream_device(c)) return st;
   hipStream_t st = (hipStream_t)stream;
   const size_t per = (size_t)T * c->s.d;
@@ -1050,31 +1163,42 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
 
 moe_status moe_pack_weights(moe_ctx* c, const moe_layer_weights* src, moe_layer_weights* dst, void* stream) {
   if (!c || !weights_ok(c, src) || src->layout != MOE_LAYOUT_ROW_MAJOR || !dst) return MOE_ERR_INVALID_ARG;
-  moe_layer_weights chk = *dst;
+  moe_layer_weights chk = *dst;  // dst's buffers, seen with src's element type and scales
   chk.layout = MOE_LAYOUT_ROW_MAJOR;
+  chk.dtype = src->dtype;
+  chk.w1_scale = src->w1_scale, chk.w3_scale = src->w3_scale, chk.w2_scale = src->w2_scale;
+  chk.sw1_scale = src->sw1_scale, chk.sw3_scale = src->sw3_scale, chk.sw2_scale = src->sw2_scale;
   if (!weights_ok(c, &chk)) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
   const moe_shape& s = c->s;
   hipStream_t st = (hipStream_t)stream;
-  auto pack = [&](const uint16_t* a, uint16_t* b, size_t rows, int K) {
-    const size_t units = rows * (size_t)(K / 8);
+  const bool fp8 = src->dtype == MOE_WEIGHT_FP8_E4M3;
+  auto pack = [&](const void* a, const void* b, size_t rows, int K) {
+    const size_t units = rows * (size_t)(K / (fp8 ? 16 : 8));  // 16-byte units written
     const unsigned blocks = (unsigned)((units + 255) / 256 < 65536 ? (units + 255) / 256 : 65536);
-    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<const uint4*>(a),
-                       reinterpret_cast<uint4*>(b), rows, K);
+    if (fp8)
+      hipLaunchKernelGGL(pack_kernel_fp8, dim3(blocks), dim3(256), 0, st, static_cast<const uint2*>(a),
+                         static_cast<uint4*>(const_cast<void*>(b)), rows, K);
+    else
+      hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const uint4*>(a),
+                         static_cast<uint4*>(const_cast<void*>(b)), rows, K);
   };
   if (dst->router_w != src->router_w &&
       hipMemcpyAsync(const_cast<uint16_t*>(dst->router_w), src->router_w, (size_t)s.n_experts * s.d * 2,
                      hipMemcpyDeviceToDevice, st) != hipSuccess)
     return MOE_ERR_HIP;
-  pack(src->w1, const_cast<uint16_t*>(dst->w1), (size_t)s.n_experts * s.ffn, s.d);
-  pack(src->w3, const_cast<uint16_t*>(dst->w3), (size_t)s.n_experts * s.ffn, s.d);
-  pack(src->w2, const_cast<uint16_t*>(dst->w2), (size_t)s.n_experts * s.d, s.ffn);
+  pack(src->w1, dst->w1, (size_t)s.n_experts * s.ffn, s.d);
+  pack(src->w3, dst->w3, (size_t)s.n_experts * s.ffn, s.d);
+  pack(src->w2, dst->w2, (size_t)s.n_experts * s.d, s.ffn);
   if (s.n_shared > 0) {
-    pack(src->sw1, const_cast<uint16_t*>(dst->sw1), (size_t)s.n_shared * s.ffn, s.d);
-    pack(src->sw3, const_cast<uint16_t*>(dst->sw3), (size_t)s.n_shared * s.ffn, s.d);
-    pack(src->sw2, const_cast<uint16_t*>(dst->sw2), (size_t)s.n_shared * s.d, s.ffn);
+    pack(src->sw1, dst->sw1, (size_t)s.n_shared * s.ffn, s.d);
+    pack(src->sw3, dst->sw3, (size_t)s.n_shared * s.ffn, s.d);
+    pack(src->sw2, dst->sw2, (size_t)s.n_shared * s.d, s.ffn);
   }
   dst->layout = MOE_LAYOUT_TILED;
+  dst->dtype = src->dtype;
+  dst->w1_scale = src->w1_scale, dst->w3_scale = src->w3_scale, dst->w2_scale = src->w2_scale;
+  dst->sw1_scale = src->sw1_scale, dst->sw3_scale = src->sw3_scale, dst->sw2_scale = src->sw2_scale;
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 

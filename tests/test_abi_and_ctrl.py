@@ -28,7 +28,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(L, name), f"{name} declared in the header but not exported"
     assert sorted(binding.EXPORTS) == declared
-    assert L.moe_abi_version() == 1
+    assert L.moe_abi_version() == 2
     assert binding._strerror(0) == "ok" and "shape" in binding._strerror(-2)
 
 
