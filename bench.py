@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--fixed-k", type=int, default=-1, help="time a single K instead of cycling 0..8")
     ap.add_argument("--layout", choices=("tiled", "row"), default="tiled",
                     help="expert weight storage: tiled = re-ordered once at load time by moe_pack_weights")
+    ap.add_argument("--weights", choices=("bf16", "fp8"), default="bf16",
+                    help="expert weight type: bf16 (the headline workload) or fp8 = E4M3 codes + per-row scales")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build is single-GPU (no sharding, no collectives); --gpus {args.gpus} is not supported",
@@ -53,6 +55,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
+    fp8 = args.weights == "fp8"
+    if fp8 and args.layout != "tiled":
+        print("bench.py: FP8 weights are streamed in the tiled layout only", file=sys.stderr)
+        sys.exit(2)
+    expert_bytes = cfg.expert_bytes_fp8 if fp8 else cfg.expert_bytes
     L, K_steps, W_steps = args.layers, args.steps, args.warmup
     T_MAX = 9
 
@@ -60,7 +67,8 @@ def main():
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX)
     lw = []
     for l in range(L):
-        wd = synth.layer_weights_device(cfg, l)          # row-major, as the oracle sees them
+        # row-major, as the oracle sees them
+        wd = synth.layer_weights_fp8_device(cfg, l) if fp8 else synth.layer_weights_device(cfg, l)
         w = ctx.weights(wd)
         if args.layout == "tiled":
             w = ctx.moe_pack_weights(w)                   # one-off static re-layout, same bytes
@@ -96,7 +104,7 @@ def main():
 
     nu_h = nu.cpu().numpy()[W_steps:]
     ks = np.array([k_of(W_steps + j) for j in range(K_steps)])
-    ubytes = (nu_h.astype(np.int64) + cfg.n_shared) * cfg.expert_bytes
+    ubytes = (nu_h.astype(np.int64) + cfg.n_shared) * expert_bytes
     value = ubytes.sum() / wall / 1e9
 
     # ---- latency per layer vs K: the timed steps again, grouped by K, one event pair per group ----
@@ -130,7 +138,7 @@ def main():
     torch.cuda.synchronize()
     kms, n_prof = ctx.moe_ctx_profile_read()
     ctx.moe_ctx_profile(False)
-    gu_bytes_per_launch = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * 2 * cfg.d * cfg.ffn * 2
+    gu_bytes_per_launch = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * 2 * expert_bytes / 3
     gu_ms = kms["gateup"] / max(n_prof, 1)
     achieved = gu_bytes_per_launch / (gu_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "gateup_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -141,11 +149,11 @@ def main():
     # workload (summary committed under profiles/); reported only when the run matches that workload
     traffic_file = os.path.join(ROOT, "profiles", "gateup_kernel_mixtral_hbm_traffic.txt")
     if (cfg is synth.MIXTRAL and args.layout == "tiled" and args.rho == 0.5 and args.fixed_k < 0 and L == 8
-            and K_steps == 180 and os.path.exists(traffic_file)):
+            and K_steps == 180 and not fp8 and os.path.exists(traffic_file)):
         for line in open(traffic_file):
             if line.startswith("traffic_bytes_per_launch gateup_kernel"):
                 roofline["traffic"] = int(line.split()[-1])
-    dn_bytes = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * cfg.d * cfg.ffn * 2
+    dn_bytes = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * expert_bytes / 3
     roofline["down_kernel_GBps"] = round(dn_bytes / (kms["down"] / max(n_prof, 1) * 1e-3) / 1e9, 1)
 
     # ---- the box's plain read-stream rate, as a second denominator ---------------------------
@@ -160,21 +168,21 @@ def main():
         binding.moe_stream_read_probe(t, sink)
     e1.record()
     torch.cuda.synchronize()
-    stream_gbs = sum(t.numel() * 2 for t in probe) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    stream_gbs = sum(t.numel() * t.element_size() for t in probe) / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
     # ---- CPU oracle beside it (bounded sample, single thread) ---------------------------------
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as orc
-        Wh = synth.layer_weights_host(cfg, 0)
+        Wh = synth.layer_weights_fp8_host(cfg, 0) if fp8 else synth.layer_weights_host(cfg, 0)
         sample_T = tuple(range(1, T_MAX + 1)) + (T_MAX,)
         cbytes, csec = 0, 0.0
         for n, T in enumerate(sample_T):
             x = synth.hidden_host(cfg, 0, 10_000 + n, T, args.rho)
             c0 = time.perf_counter()
-            _, rids, _ = orc.layer(x, Wh, cfg.top_k, cfg.n_shared, "f32")
+            _, rids, _ = (orc.layer_fp8 if fp8 else orc.layer)(x, Wh, cfg.top_k, cfg.n_shared, "f32")
             csec += time.perf_counter() - c0
-            cbytes += (orc.union(rids, cfg.n_experts)["n_unique"] + cfg.n_shared) * cfg.expert_bytes
+            cbytes += (orc.union(rids, cfg.n_experts)["n_unique"] + cfg.n_shared) * expert_bytes
         cpu = {"value": round(cbytes / csec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"fp32 oracle, layer 0, rho={args.rho}, one layer-step each at T in {list(sample_T)}; "
                          f"{csec:.1f} s of CPU time; host has {os.cpu_count()} logical cores",
@@ -184,9 +192,9 @@ def main():
         "metric": "unique-expert GB/s (MoE verify step, sum of unique-expert weight bytes / time); latency/layer vs K in by_K",
         "value": round(float(value), 1), "unit": "GB/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": round(wall / K_steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "fp8_e4m3" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name} MoE layer d={cfg.d} E={cfg.n_experts} top{cfg.top_k} ffn={cfg.ffn} "
-                               f"shared={cfg.n_shared}, bf16 weights, T=K+1 with K "
+                               f"shared={cfg.n_shared}, {'FP8 E4M3 + per-row scale' if fp8 else 'bf16'} weights, T=K+1 with K "
                                + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
                                + f", rho={args.rho}, {L} rotating resident layers, {args.layout} weight layout"},
         "frac_hbm_peak": round(float(value / HBM_PEAK_GBS), 4),

@@ -73,6 +73,14 @@ __device__ __forceinline__ uint4 ld128(const char* base, uint32_t byte_off) {
 // the 8 values k = 32 s + 8 kg .. +7 of token column n.  Activations are therefore stored in that
 // order — unit q = s*64 + kg*16 + n holds those 8 bf16 (16 bytes) — so a wave fetches the whole
 // fragment of a k-step with ONE contiguous 1 KB load.  Token columns are padded to 16.
+//
+// Two arrangements of the bf16 hi + lo halves of the fp32 activations:
+//   split   (T > 8)   two fragment arrays, hi and lo; column n = token n; two MFMAs per weight tile
+//   packed  (T <= 8)  ONE array: column n < 8 = hi half of token n, column n + 8 = lo half of token n.
+//                     MFMA columns are independent, so one MFMA yields the hi and the lo contribution
+//                     in two columns, which the epilogue adds: half the fragment loads and half the
+//                     MFMAs for every speculation length up to K = 7.
+constexpr int kPackedTokens = 8;
 __device__ __forceinline__ size_t frag_unit(int k8, int n) {  // k8 = k / 8
   return (size_t)(k8 >> 2) * 64 + (size_t)(k8 & 3) * 16 + n;
 }
@@ -220,7 +228,7 @@ struct RouteArgs {
 
 // activations of token t -> bf16 hi/lo halves in fragment order (the MFMA B operand of the expert kernels)
 __device__ __forceinline__ void split_token(const float* __restrict__ x, int d, int t, int first, int stride,
-                                            uint16_t* __restrict__ xf_hi, uint16_t* __restrict__ xf_lo) {
+                                            uint16_t* __restrict__ xf_hi, uint16_t* __restrict__ xf_lo, bool packed) {
   for (int k8 = first; k8 < (d >> 3); k8 += stride) {
     const float4 v0 = *reinterpret_cast<const float4*>(x + k8 * 8);
     const float4 v1 = *reinterpret_cast<const float4*>(x + k8 * 8 + 4);
@@ -236,7 +244,10 @@ __device__ __forceinline__ void split_token(const float* __restrict__ x, int d, 
     }
     const size_t q = frag_unit(k8, t);
     reinterpret_cast<uint4*>(xf_hi)[q] = uint4{h[0], h[1], h[2], h[3]};
-    reinterpret_cast<uint4*>(xf_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
+    if (packed)
+      reinterpret_cast<uint4*>(xf_hi)[q + kPackedTokens] = uint4{l[0], l[1], l[2], l[3]};
+    else
+      reinterpret_cast<uint4*>(xf_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
   }
 }
 
@@ -348,7 +359,7 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
       if (lane == 0) s_part[wave][e] += a;
     }
   }
-  split_token(x, g.d, t, tid, 64 * kRouteWaves, g.xf_hi, g.xf_lo);
+  split_token(x, g.d, t, tid, 64 * kRouteWaves, g.xf_hi, g.xf_lo, g.T <= kPackedTokens);
   __syncthreads();
   if (tid < E) {
     double l = 0.0;
@@ -394,15 +405,16 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
 //   P   pipeline depth (steps of loads in flight per wave)
 // A stage holds one 128-bit load per tile plus the hi and lo activation fragments of its NB k-steps.
 // ------------------------------------------------------------------------------------------
-template <int NA, int NB>
+template <int NA, int NB, bool PK>
 struct Stage {
   uint4 a[NA];
-  uint4 bh[NB], bl[NB];
+  uint4 bh[NB];
+  uint4 bl[PK ? 1 : NB];  // unused when the halves are packed into bh
 };
 
-template <int NA, int NB, int P, class Load, class Compute>
+template <int NA, int NB, bool PK, int P, class Load, class Compute>
 __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
-  Stage<NA, NB> st[P];
+  Stage<NA, NB, PK> st[P];
   // The prologue loads are unconditional (a short wave re-reads its last valid step): a load that
   // is issued on only some paths makes the compiler's wait counters pessimistic inside the loop.
   const int last = nst > 0 ? nst - 1 : 0;
@@ -466,7 +478,7 @@ struct GateupArgs {
   int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
 };
 
-template <int R, int W, int P, bool TILED, bool NT, bool FP8>
+template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
 __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
@@ -480,7 +492,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
     // three independent loads (one round trip); the tables are in bounds for every slot of the grid
     const int nu = *g.n_unique;
     const int e = g.slot_expert[slot];
-    gate = g.slot_gate[slot * kGateCols + r];
+    gate = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)];
     if (slot >= nu) return;  // beyond the union of this step
     W1 = reinterpret_cast<const char*>(g.w1) + e * per;
     W3 = reinterpret_cast<const char*>(g.w3) + e * per;
@@ -520,33 +532,35 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
 #pragma unroll
   for (int j = 0; j < 2 * R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  pipeline<2 * R, NB, P>(
+  pipeline<2 * R, NB, PK, P>(
       nst,
-      [&](Stage<2 * R, NB>& st, int s) {
+      [&](Stage<2 * R, NB, PK>& st, int s) {
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
           st.bh[b] = ld128<false>(XH, b_off + (uint32_t)(s * NB + b) * 1024);
-          st.bl[b] = ld128<false>(XL, b_off + (uint32_t)(s * NB + b) * 1024);
+          if constexpr (!PK) st.bl[b] = ld128<false>(XL, b_off + (uint32_t)(s * NB + b) * 1024);
         }
       },
-      [&](const Stage<2 * R, NB>& st) {
+      [&](const Stage<2 * R, NB, PK>& st) {
         if constexpr (FP8) {
 #pragma unroll
           for (int j = 0; j < 2 * R; ++j) {
             uint4 k0, k1;
             fp8x16_to_bf16(st.a[j], k0, k1);
             acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
-            acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
             acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
-            acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
           }
         } else {
 #pragma unroll
           for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+          if constexpr (!PK) {
 #pragma unroll
-          for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+            for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+          }
         }
       });
 
@@ -575,13 +589,17 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       G = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
       U = float4{acc[R + j][0], acc[R + j][1], acc[R + j][2], acc[R + j][3]};
     }
+    if constexpr (PK) {  // column n + 8 carries the lo-half contribution of token n: fold it in
+      G.x += __shfl_xor(G.x, 8), G.y += __shfl_xor(G.y, 8), G.z += __shfl_xor(G.z, 8), G.w += __shfl_xor(G.w, 8);
+      U.x += __shfl_xor(U.x, 8), U.y += __shfl_xor(U.y, 8), U.z += __shfl_xor(U.z, 8), U.w += __shfl_xor(U.w, 8);
+    }
     if constexpr (FP8) {  // the lane's four rows of the tile are consecutive: one 16-byte load per scale vector
       const float4 c1 = *reinterpret_cast<const float4*>(S1 + (tile0 + j) * 16 + kg * 4);
       const float4 c3 = *reinterpret_cast<const float4*>(S3 + (tile0 + j) * 16 + kg * 4);
       G.x *= c1.x, G.y *= c1.y, G.z *= c1.z, G.w *= c1.w;
       U.x *= c3.x, U.y *= c3.y, U.z *= c3.z, U.w *= c3.w;
     }
-    if (r < g.T && gate != 0.f) {
+    if (r < g.T && (!PK || r < kPackedTokens) && gate != 0.f) {
       // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r: four consecutive k of the
       // down projection, i.e. one half of a 16-byte fragment unit
       uint16_t hi[4], lo[4];
@@ -593,7 +611,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       const size_t o = frag_unit(k >> 3, r) * 8 + (k & 4);
       *reinterpret_cast<uint2*>(HH + o) =
           uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-      *reinterpret_cast<uint2*>(HL + o) =
+      *reinterpret_cast<uint2*>((PK ? HH + kPackedTokens * 8 : HL) + o) =
           uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
     }
   }
@@ -616,7 +634,7 @@ struct DownArgs {
   int d, ffn, T, routed_slots, u_max, max_tokens, KS;
 };
 
-template <int R, int W, int P, bool TILED, bool NT, bool FP8>
+template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
 __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * R * 64 : 1];
@@ -630,12 +648,13 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   if (slot < g.routed_slots) {
     const int nu = *g.n_unique;  // three independent loads, one round trip
     const int e = g.slot_expert[slot];
-    live = g.slot_gate[slot * kGateCols + r] != 0.f;  // 0 also for the padded columns r >= T
+    // 0 also for the padded columns r >= T; packed: column n + 8 belongs to token n
+    live = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)] != 0.f;
     if (slot >= nu) return;
     W2 = reinterpret_cast<const char*>(g.w2) + e * per;
     if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
   } else {
-    live = r < g.T;
+    live = (PK ? (r & (kPackedTokens - 1)) : r) < g.T;
     const int sh = slot - g.routed_slots;
     W2 = reinterpret_cast<const char*>(g.sw2) + sh * per;
     if constexpr (FP8) S2 = g.ss2 + (size_t)sh * g.d;
@@ -661,37 +680,39 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 #pragma unroll
   for (int j = 0; j < R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  pipeline<R, NB, P>(
+  pipeline<R, NB, PK, P>(
       nst,
-      [&](Stage<R, NB>& st, int s) {
+      [&](Stage<R, NB, PK>& st, int s) {
 #pragma unroll
         for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
           st.bh[b] = uint4{0u, 0u, 0u, 0u};
-          st.bl[b] = uint4{0u, 0u, 0u, 0u};
+          if constexpr (!PK) st.bl[b] = uint4{0u, 0u, 0u, 0u};
           if (live) {  // H of a token that was not routed here was never written: do not read it
             st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
-            st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+            if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
           }
         }
       },
-      [&](const Stage<R, NB>& st) {
+      [&](const Stage<R, NB, PK>& st) {
         if constexpr (FP8) {
 #pragma unroll
           for (int j = 0; j < R; ++j) {
             uint4 k0, k1;
             fp8x16_to_bf16(st.a[j], k0, k1);
             acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
-            acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
             acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
-            acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
           }
         } else {
 #pragma unroll
           for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+          if constexpr (!PK) {
 #pragma unroll
-          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+            for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+          }
         }
       });
 
@@ -713,11 +734,13 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
     } else {
       y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
     }
+    if constexpr (PK)  // column n + 8 carries the lo-half contribution of token n
+      y.x += __shfl_xor(y.x, 8), y.y += __shfl_xor(y.y, 8), y.z += __shfl_xor(y.z, 8), y.w += __shfl_xor(y.w, 8);
     if constexpr (FP8) {  // scaling each split-K partial sum by the row scale = scaling the whole sum
       const float4 c2 = *reinterpret_cast<const float4*>(S2 + (tile0 + j) * 16 + kg * 4);
       y.x *= c2.x, y.y *= c2.y, y.z *= c2.z, y.w *= c2.w;
     }
-    if (live) {  // nobody reads the slab column of a token that was not routed here
+    if (live && (!PK || r < kPackedTokens)) {  // nobody reads the slab column of a token that was not routed here
       const size_t o = (((size_t)slot * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
       *reinterpret_cast<float4*>(g.partial + o) = y;
     }
@@ -912,19 +935,27 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
 template <int R, int P>
 void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // row-major bf16 weights
   const dim3 grid((c->s.ffn / 16 + R - 1) / R, a.routed_slots + c->s.n_shared);
-  hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false, false>), grid, dim3(64 * kWaves), 0, st, a);
+  if (a.T <= kPackedTokens)
+    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false, false, true>), grid, dim3(64 * kWaves), 0, st, a);
+  else
+    hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false, false, false>), grid, dim3(64 * kWaves), 0, st, a);
 }
 // Tiled weights are read exactly once in contiguous 1 KB pieces -> streaming loads; row-major weights
 // are read in 64-byte row segments whose cache lines are completed by the next k-step -> cached loads.
 template <int R, int P>
 void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipStream_t st) {
-  const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS);
-  if (fp8)  // tiled only (checked by the caller)
-    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true>), grid, dim3(64 * kWaves), 0, st, a);
-  else if (tiled)
-    hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false>), grid, dim3(64 * kWaves), 0, st, a);
-  else
-    hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false, false>), grid, dim3(64 * kWaves), 0, st, a);
+  const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS), block(64 * kWaves);
+  const bool pk = a.T <= kPackedTokens;
+  if (fp8) {  // tiled only (checked by the caller)
+    if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true, false>), grid, block, 0, st, a);
+  } else if (tiled) {
+    if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false, false>), grid, block, 0, st, a);
+  } else {
+    if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((down_kernel<R, kWaves, P, false, false, false, false>), grid, block, 0, st, a);
+  }
 }
 
 // One layer-step after validation: router, gate/up, down, slab sum.  The expert-union step has no
@@ -943,14 +974,17 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
                 c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
+  const bool pk = T <= kPackedTokens;  // must match what route_kernel wrote
   if (fp8) {
     const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
-    hipLaunchKernelGGL((gateup_kernel<1, 1, kFp8GateupDepth, true, true, true>), grid, dim3(64), 0, st, ga);
+    if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, true, true>), grid, dim3(64), 0, st, ga);
+    else hipLaunchKernelGGL((gateup_kernel<1, 1, kFp8GateupDepth, true, true, true, false>), grid, dim3(64), 0, st, ga);
   } else if (tiled) {
     // one wave per 16-row tile pair over the whole of d (splitting d over 2 or 4 waves when the union
     // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
     const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
-    hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false>), grid, dim3(64), 0, st, ga);
+    if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false, true>), grid, dim3(64), 0, st, ga);
+    else hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false, false>), grid, dim3(64), 0, st, ga);
   } else {
     switch (p.gu_R) {
       case 4: launch_gateup<4, 2>(c, ga, st); break;
