@@ -147,9 +147,9 @@ def main():
                 "kernel_us_per_step": {k: round(v / max(n_prof, 1) * 1e3, 2) for k, v in kms.items()}}
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same default
     # workload (summary committed under profiles/); reported only when the run matches that workload
-    traffic_file = os.path.join(ROOT, "profiles", "gateup_kernel_mixtral_hbm_traffic.txt")
+    traffic_file = os.path.join(ROOT, "profiles", f"gateup_kernel_mixtral{'_fp8' if fp8 else ''}_hbm_traffic.txt")
     if (cfg is synth.MIXTRAL and args.layout == "tiled" and args.rho == 0.5 and args.fixed_k < 0 and L == 8
-            and K_steps == 180 and not fp8 and os.path.exists(traffic_file)):
+            and K_steps == 180 and os.path.exists(traffic_file)):
         for line in open(traffic_file):
             if line.startswith("traffic_bytes_per_launch gateup_kernel"):
                 roofline["traffic"] = int(line.split()[-1])
