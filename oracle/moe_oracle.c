@@ -301,3 +301,28 @@ int oracle_layer_fp8(const float* hidden, int T, int d, int ffn, int E, int top_
   return oracle_combine_fp8(hidden, T, d, ffn, E, top_k, n_shared, q1, q3, q2, s1, s3, s2, sq1, sq3, sq2, ss1, ss3,
                             ss2, ids, gates, out);
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Gate variant: softmax over ALL E logits, the selected probabilities used as they are (they sum
+ * to less than 1).  Some of the Table 1 model families weight their picks this way instead of
+ * renormalising over the picks; the paper does not say which, so both are offered.  Selection is
+ * unchanged (same top-k, same tie rule):
+ *   gates[t,i] = exp(l_{ids[t,i]} - m) / sum_{e<E} exp(l_e - m),   m = the largest logit of token t,
+ * with l_e = (REAL)logit[t,e] and the sum taken in expert-index order.
+ * --------------------------------------------------------------------------------------------- */
+int oracle_route_softmax_all(const float* hidden, const uint16_t* router_w, int T, int d, int E, int top_k,
+                             int32_t* ids, float* gates, double* logits_out) {
+  if (T < 1 || d < 1 || E < 1 || top_k < 1 || top_k > E) return -1;
+  double* logit = logits_out ? logits_out : (double*)malloc(sizeof(double) * (size_t)T * E);
+  int rc = oracle_route(hidden, router_w, T, d, E, top_k, ids, gates, logit);
+  for (int t = 0; t < T && rc == 0; ++t) {
+    const double* l = logit + (size_t)t * E;
+    const REAL m = (REAL)l[ids[(size_t)t * top_k]]; /* the first pick is the arg-max */
+    REAL sum = 0;
+    for (int e = 0; e < E; ++e) sum += real_exp((REAL)l[e] - m);
+    for (int i = 0; i < top_k; ++i)
+      gates[(size_t)t * top_k + i] = (float)(real_exp((REAL)l[ids[(size_t)t * top_k + i]] - m) / sum);
+  }
+  if (!logits_out) free(logit);
+  return rc;
+}

@@ -47,6 +47,8 @@ def _load(path: str, precision: str):
     L.oracle_real_bytes.restype = ctypes.c_int
     L.oracle_route.restype = ctypes.c_int
     L.oracle_route.argtypes = [_f32p, _u16p] + [ctypes.c_int] * 4 + [_i32p, _f32p, _f64p]
+    L.oracle_route_softmax_all.restype = ctypes.c_int
+    L.oracle_route_softmax_all.argtypes = L.oracle_route.argtypes
     L.oracle_union.restype = ctypes.c_int
     L.oracle_union.argtypes = [_i32p] + [ctypes.c_int] * 3 + [_i32p] * 5
     L.oracle_expert_ffn.restype = None
@@ -101,8 +103,12 @@ def _i32(a):
     return a, a.ctypes.data_as(_i32p)
 
 
-def route(hidden, router_w, top_k, precision="f32"):
-    """-> ids[T,top_k] int32, gates[T,top_k] fp32, logits[T,E] fp64."""
+GATE_RENORM_TOPK, GATE_SOFTMAX_ALL = 0, 1
+
+
+def route(hidden, router_w, top_k, precision="f32", gate_mode=GATE_RENORM_TOPK):
+    """-> ids[T,top_k] int32, gates[T,top_k] fp32, logits[T,E] fp64.
+    gate_mode 0: gates = softmax over the selected logits; 1: softmax over all E logits, picks not renormalised."""
     hidden, hp = _f32(hidden)
     router_w, rp = _u16(router_w)
     T, d = hidden.shape
@@ -111,8 +117,11 @@ def route(hidden, router_w, top_k, precision="f32"):
     ids = np.empty((T, top_k), np.int32)
     gates = np.empty((T, top_k), np.float32)
     logits = np.empty((T, E), np.float64)
-    rc = _lib(precision).oracle_route(hp, rp, T, d, E, top_k, ids.ctypes.data_as(_i32p),
-                                      gates.ctypes.data_as(_f32p), logits.ctypes.data_as(_f64p))
+    if gate_mode not in (GATE_RENORM_TOPK, GATE_SOFTMAX_ALL):
+        raise ValueError(gate_mode)
+    fn = _lib(precision).oracle_route if gate_mode == GATE_RENORM_TOPK else _lib(precision).oracle_route_softmax_all
+    rc = fn(hp, rp, T, d, E, top_k, ids.ctypes.data_as(_i32p), gates.ctypes.data_as(_f32p),
+            logits.ctypes.data_as(_f64p))
     if rc:
         raise ValueError("oracle_route: bad sizes")
     return ids, gates, logits
@@ -182,8 +191,11 @@ def dense_masked(hidden, W, ids, gates, n_shared=0, precision="f32"):
     return _combine_like("oracle_dense_masked", hidden, W, ids, gates, np.asarray(ids).shape[1], n_shared, precision)
 
 
-def layer(hidden, W, top_k, n_shared=0, precision="f32"):
+def layer(hidden, W, top_k, n_shared=0, precision="f32", gate_mode=GATE_RENORM_TOPK):
     """Route + combine.  W: dict with router_w, w1, w3, w2 (and sw1, sw3, sw2).  -> out, ids, gates."""
+    if gate_mode != GATE_RENORM_TOPK:      # the other gate rule: its own routing call, then the same combine
+        ids, gates, _ = route(hidden, W["router_w"], top_k, precision, gate_mode)
+        return combine(hidden, W, ids, gates, n_shared, precision), ids, gates
     hidden, hp = _f32(hidden)
     T, d = hidden.shape
     rw, pr = _u16(W["router_w"])
@@ -293,8 +305,11 @@ def combine_fp8(hidden, W, ids, gates, n_shared=0, precision="f32"):
     return out
 
 
-def layer_fp8(hidden, W, top_k, n_shared=0, precision="f32"):
+def layer_fp8(hidden, W, top_k, n_shared=0, precision="f32", gate_mode=GATE_RENORM_TOPK):
     """Route (bf16 router_w) + FP8 combine.  -> out, ids, gates."""
+    if gate_mode != GATE_RENORM_TOPK:
+        ids, gates, _ = route(hidden, W["router_w"], top_k, precision, gate_mode)
+        return combine_fp8(hidden, W, ids, gates, n_shared, precision), ids, gates
     hidden, hp = _f32(hidden)
     T, d = hidden.shape
     rw, pr = _u16(W["router_w"])

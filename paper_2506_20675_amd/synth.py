@@ -57,6 +57,7 @@ class MoEConfig:
     n_experts: int
     top_k: int
     n_shared: int = 0
+    gate_mode: int = 0   # 0: softmax over the picked logits; 1: softmax over all experts, picks not renormalised
 
     @property
     def expert_bytes(self) -> int:
@@ -72,7 +73,11 @@ TINY = MoEConfig("tiny", 1, 512, 1024, 8, 2, 0)
 MIXTRAL = MoEConfig("mixtral-8x7b-shaped", 2, 4096, 14336, 8, 2, 0)
 OLMOE = MoEConfig("olmoe-like", 3, 2048, 1024, 64, 8, 0)
 DEEPSEEK = MoEConfig("deepseek-v2-lite-like", 4, 2048, 1408, 64, 6, 2)
-CONFIGS = {c.name: c for c in (TINY, MIXTRAL, OLMOE, DEEPSEEK)}
+# The two remaining rows of the paper's Table 1 (expert count, top-k, shared experts, hidden size from the table;
+# the expert intermediate sizes are not in the paper and are taken from the public model cards: 6400 and 1408).
+PHI35 = MoEConfig("phi-3.5-moe-like", 6, 4096, 6400, 16, 2, 0)
+QWEN15 = MoEConfig("qwen1.5-moe-like", 7, 2048, 1408, 60, 4, 4, gate_mode=1)
+CONFIGS = {c.name: c for c in (TINY, MIXTRAL, OLMOE, DEEPSEEK, PHI35, QWEN15)}
 
 
 # ----------------------------------------------------------------------------

@@ -48,6 +48,20 @@ MUTANTS_FP8 = {
                          "      for (int c = 0; c < d; ++c) acc[c] += y[c];\n    }\n    for (int s = 0; s < n_shared; ++s) {\n      oracle_expert_ffn_fp8"),
 }
 
+MUTANTS_GATE = {
+    "softmax_all_sums_only_the_picks": ("for (int e = 0; e < E; ++e) sum += real_exp((REAL)l[e] - m);",
+                                        "for (int i = 0; i < top_k; ++i) sum += real_exp((REAL)l[ids[(size_t)t * top_k + i]] - m);"),
+    "softmax_all_skips_last_expert": ("for (int e = 0; e < E; ++e) sum += real_exp((REAL)l[e] - m);",
+                                      "for (int e = 0; e < E - 1; ++e) sum += real_exp((REAL)l[e] - m);"),
+    "softmax_all_wrong_token_row": ("const double* l = logit + (size_t)t * E;", "const double* l = logit;"),
+    "softmax_all_numerator_is_one": ("(float)(real_exp((REAL)l[ids[(size_t)t * top_k + i]] - m) / sum);", "(float)((REAL)1 / sum);"),
+}
+
+PIN_CALLS_GATE = [
+    lambda: pins.test_softmax_all_gates_against_library_softmax_and_identities("f64"),
+    lambda: pins.test_softmax_all_layer_scales_each_token_by_its_pick_mass("f64"),
+]
+
 PIN_CALLS_FP8 = [
     lambda: fp8pins.test_e4m3_golden_corner_values(),
     lambda: fp8pins.test_e4m3_all_codes_match_library_type_and_structure(),
@@ -71,10 +85,14 @@ PIN_CALLS = [
 ]
 
 
-@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8))
+_GROUPS = ((MUTANTS, lambda: PIN_CALLS), (MUTANTS_FP8, lambda: PIN_CALLS_FP8), (MUTANTS_GATE, lambda: PIN_CALLS_GATE))
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8) + sorted(MUTANTS_GATE))
 def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
-    old, new = (MUTANTS if name in MUTANTS else MUTANTS_FP8)[name]
-    calls = PIN_CALLS if name in MUTANTS else PIN_CALLS_FP8
+    table, get_calls = next((m, c) for m, c in _GROUPS if name in m)
+    old, new = table[name]
+    calls = get_calls()
     src = open(os.path.join(os.path.dirname(orc.__file__), "moe_oracle.c")).read()
     assert src.count(old) >= 1, f"mutation site for {name} not found"
     mutated = src.replace(old, new, 1)

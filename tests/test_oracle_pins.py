@@ -307,3 +307,47 @@ def test_f32_oracle_close_to_f64_oracle_on_tiny_config():
     np.testing.assert_allclose(g32, g64, atol=2e-7)
     rel = np.sqrt(((o32.astype(np.float64) - o64) ** 2).sum() / (o64.astype(np.float64) ** 2).sum())
     assert rel < 1e-5
+
+
+# ---------------------------------------------------------------- gate variant: softmax over all experts
+@pytest.mark.parametrize("prec", PRECS)
+def test_softmax_all_gates_against_library_softmax_and_identities(prec):
+    """Same picks as the renormalised rule; gates = the library softmax over ALL logits read at the picks; the two rules
+    differ by exactly the probability mass of the picks; with top_k = E they coincide; E = 2, top-1 is the logistic."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(41)
+    T, d, E, k = 6, 20, 7, 3
+    x = rng.normal(size=(T, d)).astype(np.float32)
+    rw = _bf16(rng.normal(0, 0.6, (E, d)))
+    ids0, g0, logits = orc.route(x, rw, k, prec)
+    ids1, g1, logits1 = orc.route(x, rw, k, prec, gate_mode=orc.GATE_SOFTMAX_ALL)
+    np.testing.assert_array_equal(ids0, ids1)
+    np.testing.assert_array_equal(logits, logits1)
+    p = softmax(logits, axis=1)
+    tol = 3e-7 if prec == "f32" else 1e-7          # gates are stored as fp32
+    np.testing.assert_allclose(g1, np.take_along_axis(p, ids1, 1), rtol=0, atol=tol)
+    assert (g1.sum(axis=1) < 1.0).all()             # mass of the experts that were not picked is missing
+    mass = np.take_along_axis(p, ids1, 1).sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(g1, g0 * mass, rtol=0, atol=tol)
+    _, gE0, _ = orc.route(x, rw, E, prec)
+    _, gE1, _ = orc.route(x, rw, E, prec, gate_mode=orc.GATE_SOFTMAX_ALL)
+    np.testing.assert_allclose(gE1, gE0, rtol=0, atol=tol)
+    rw2 = _bf16(rng.normal(0, 0.6, (2, d)))
+    ids2, g2, l2 = orc.route(x, rw2, 1, prec, gate_mode=orc.GATE_SOFTMAX_ALL)
+    np.testing.assert_allclose(g2[:, 0], 1.0 / (1.0 + np.exp(-np.abs(l2[:, 0] - l2[:, 1]))), rtol=0, atol=tol)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_softmax_all_layer_scales_each_token_by_its_pick_mass(prec):
+    """The layer with the other gate rule = the renormalised layer with every token's routed sum scaled by the mass of
+    its picks (shared experts are not gated, so they are left out here)."""
+    from scipy.special import softmax
+    d, ffn, E, T, k = 24, 40, 6, 4, 2
+    W, rng = _rand_layer(43, d, ffn, E, sigma=0.2)
+    x = rng.normal(size=(T, d)).astype(np.float32)
+    out0, ids0, _ = orc.layer(x, W, k, 0, prec)
+    out1, ids1, g1 = orc.layer(x, W, k, 0, prec, gate_mode=orc.GATE_SOFTMAX_ALL)
+    np.testing.assert_array_equal(ids0, ids1)
+    _, _, logits = orc.route(x, W["router_w"], k, "f64")
+    mass = np.take_along_axis(softmax(logits, axis=1), ids1, 1).sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(out1, out0 * mass, rtol=2e-5 if prec == "f32" else 1e-6, atol=1e-6)

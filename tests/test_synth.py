@@ -62,7 +62,10 @@ def test_layer_weight_shapes():
     assert W["router_w"].shape == (8, 512) and W["w1"].shape == (8, 1024, 512) and W["w2"].shape == (8, 512, 1024)
     assert all(v.dtype == np.uint16 for v in W.values())
     assert synth.MIXTRAL.expert_bytes == 352_321_536
-    assert {c.name for c in synth.CONFIGS.values()} == {"tiny", "mixtral-8x7b-shaped", "olmoe-like", "deepseek-v2-lite-like"}
+    assert {c.name for c in synth.CONFIGS.values()} == {"tiny", "mixtral-8x7b-shaped", "olmoe-like", "deepseek-v2-lite-like",
+                                                        "phi-3.5-moe-like", "qwen1.5-moe-like"}
+    assert len({c.config_id for c in synth.CONFIGS.values()}) == len(synth.CONFIGS)
+    assert all(c.d % 64 == 0 and c.ffn % 64 == 0 for c in synth.CONFIGS.values())      # FP8 needs 64-wide steps
 
 
 def test_regimes_and_causal_acceptance():
