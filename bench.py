@@ -64,7 +64,7 @@ def main():
     T_MAX = 9
 
     # ---- resident inputs -------------------------------------------------------------------
-    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX, cfg.gate_mode)
     lw = []
     for l in range(L):
         # row-major, as the oracle sees them
@@ -180,7 +180,7 @@ def main():
         for n, T in enumerate(sample_T):
             x = synth.hidden_host(cfg, 0, 10_000 + n, T, args.rho)
             c0 = time.perf_counter()
-            _, rids, _ = (orc.layer_fp8 if fp8 else orc.layer)(x, Wh, cfg.top_k, cfg.n_shared, "f32")
+            _, rids, _ = (orc.layer_fp8 if fp8 else orc.layer)(x, Wh, cfg.top_k, cfg.n_shared, "f32", cfg.gate_mode)
             csec += time.perf_counter() - c0
             cbytes += (orc.union(rids, cfg.n_experts)["n_unique"] + cfg.n_shared) * expert_bytes
         cpu = {"value": round(cbytes / csec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",

@@ -57,7 +57,15 @@ typedef struct {
   int32_t top_k;      /* experts selected per token                    */
   int32_t n_shared;   /* always-on shared experts (same ffn), may be 0 */
   int32_t max_tokens; /* largest T that will be passed                 */
+  int32_t gate_mode;  /* MOE_GATE_*: how the picked experts are weighted */
 } moe_shape;
+
+/* Weighting of a token's top_k picks (the selection itself — top_k largest logits, ties to the lower
+ * index — is the same).  The paper's Table 1 families differ in this and the paper does not say:
+ * MOE_GATE_RENORM_TOPK: softmax over the top_k selected logits (gates sum to 1);
+ * MOE_GATE_SOFTMAX_ALL: softmax over all E logits, the picks' probabilities used as they are
+ *                       (gates sum to less than 1). */
+enum { MOE_GATE_RENORM_TOPK = 0, MOE_GATE_SOFTMAX_ALL = 1 };
 
 typedef struct moe_ctx moe_ctx; /* opaque: shape + device workspace */
 
@@ -73,7 +81,8 @@ int64_t moe_ctx_workspace_bytes(const moe_ctx* ctx);
  * activate a larger set of experts).
  *   logit[t,e] = sum_j hidden[t,j] * router_w[e,j], accumulated in fp64 (products are exact there)
  *   ids[t,0..top_k)   the top_k largest logits of token t in descending order; equal -> lower e
- *   gates[t,i]        softmax over the selected logits (fp32), sums to 1 per token
+ *   gates[t,i]        softmax over the selected logits (fp32), sums to 1 per token; or, with
+ *                     MOE_GATE_SOFTMAX_ALL, softmax over all E logits read at the picks
  *   unique_experts[E] ascending distinct ids in the first *n_unique entries, -1 after them
  * hidden [T,d] fp32, router_w [E,d] bf16: DEVICE, read-only.  ids [T,top_k] int32, gates
  * [T,top_k] fp32, unique_experts [E] int32, n_unique [1] int32: DEVICE outputs; any of the four

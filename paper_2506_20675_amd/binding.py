@@ -32,7 +32,7 @@ class MoeError(RuntimeError):
 
 
 class MoeShape(ctypes.Structure):
-    _fields_ = [(n, c_int32) for n in ("d", "ffn", "n_experts", "top_k", "n_shared", "max_tokens")]
+    _fields_ = [(n, c_int32) for n in ("d", "ffn", "n_experts", "top_k", "n_shared", "max_tokens", "gate_mode")]
 
 
 class MoeLayerWeights(ctypes.Structure):
@@ -43,6 +43,7 @@ class MoeLayerWeights(ctypes.Structure):
 
 MOE_LAYOUT_ROW_MAJOR, MOE_LAYOUT_TILED = 0, 1
 MOE_WEIGHT_BF16, MOE_WEIGHT_FP8_E4M3 = 0, 1
+MOE_GATE_RENORM_TOPK, MOE_GATE_SOFTMAX_ALL = 0, 1
 
 
 class CascadeParams(ctypes.Structure):
@@ -197,8 +198,8 @@ class LayerWeights:
 class MoeContext:
     """Owns a moe_ctx (device workspace for one layer geometry on the current device)."""
 
-    def __init__(self, d, ffn, n_experts, top_k, n_shared=0, max_tokens=9):
-        self.shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens)
+    def __init__(self, d, ffn, n_experts, top_k, n_shared=0, max_tokens=9, gate_mode=MOE_GATE_RENORM_TOPK):
+        self.shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens, gate_mode)
         self._h = c_void_p()
         _check(lib().moe_ctx_create(byref(self.shape), byref(self._h)), "moe_ctx_create")
 

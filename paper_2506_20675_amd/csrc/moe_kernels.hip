@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g,
 struct RouteArgs {
   const float* hidden;       // [T, d]
   const uint16_t* router_w;  // [E, d]
-  int d, E, top_k, T;
+  int d, E, top_k, T, gate_mode;
   int32_t *ids_ws, *ids_out;  // [T, top_k]; *_out optional
   float *gates_ws, *gates_out;
   uint16_t *xf_hi, *xf_lo;    // activation fragments
@@ -328,6 +328,7 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
   __shared__ int s_ids[kMaxTopK];
   __shared__ float s_sel[kMaxTopK];
   __shared__ float s_gates[kMaxTopK];
+  __shared__ float s_prob[kMaxExperts];
   const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int E = g.E, top_k = g.top_k;
   const float* x = g.hidden + (size_t)t * g.d;
@@ -382,11 +383,19 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
     }
   }
   __syncthreads();
+  const bool all = g.gate_mode == MOE_GATE_SOFTMAX_ALL;
+  if (all) {  // exp(l_e - max) of every expert, for the denominator over all E
+    if (tid < E) s_prob[tid] = expf((float)s_logit[tid] - s_sel[0]);
+    __syncthreads();
+  }
   if (tid < top_k) {
-    // softmax over the picks: p_i = exp(l_i - l_0), denominator summed in pick order
+    // p_i = exp(l_i - l_0); denominator summed in pick order over the picks, or in expert order over all experts
     const float l0 = s_sel[0];
     float sum = 0.f;
-    for (int i = 0; i < top_k; ++i) sum += expf(s_sel[i] - l0);
+    if (all)
+      for (int e = 0; e < E; ++e) sum += s_prob[e];
+    else
+      for (int i = 0; i < top_k; ++i) sum += expf(s_sel[i] - l0);
     const float gate = expf(s_sel[tid] - l0) / sum;
     const int a = t * top_k + tid, id = s_ids[tid];
     g.ids_ws[a] = id;
@@ -925,7 +934,8 @@ void mark(moe_ctx* c, hipStream_t st) {
 void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* router_w, int T, int32_t* ids,
                             float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
   const moe_shape& s = c->s;
-  RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, c->ids, ids, c->gates, gates, c->xf_hi, c->xf_lo};
+  RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, s.gate_mode, c->ids, ids, c->gates, gates,
+               c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
                c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
   hipLaunchKernelGGL(route_kernel, dim3(T), dim3(64 * kRouteWaves), 0, st, ra, ga);
@@ -1057,6 +1067,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (s.d < 32 || s.ffn < 32 || s.n_experts < 1 || s.top_k < 1 || s.n_shared < 0 || s.max_tokens < 1)
     return MOE_ERR_INVALID_ARG;
   if (s.top_k > s.n_experts) return MOE_ERR_INVALID_ARG;
+  if (s.gate_mode != MOE_GATE_RENORM_TOPK && s.gate_mode != MOE_GATE_SOFTMAX_ALL) return MOE_ERR_INVALID_ARG;
   if (s.d % 32 || s.ffn % 32 || s.n_experts > kMaxExperts || s.top_k > kMaxTopK || s.n_shared > kMaxShared ||
       s.max_tokens > kMaxTokens || (int64_t)s.d * s.ffn > (int64_t)1 << 30)
     return MOE_ERR_UNSUPPORTED_SHAPE;

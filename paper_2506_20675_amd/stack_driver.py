@@ -64,7 +64,7 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
     import torch
     own = ctx is None
     if own:
-        ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1)
+        ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode)
     if stack is None:
         stack = build_stack(cfg, layers, ctx, layout)
     if pool is None:
@@ -136,7 +136,7 @@ def main(argv=None):
     ap.add_argument("--log", default=None)
     a = ap.parse_args(argv)
     cfg = synth.CONFIGS[a.config]
-    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode)
     stack = build_stack(cfg, a.layers, ctx, a.layout)
     pool = HiddenPool(cfg, a.layers, a.rho)
     res = {"cascade": run(cfg, a.layers, a.iters, a.rho, a.layout, log=a.log, ctx=ctx, stack=stack, pool=pool)[0]}

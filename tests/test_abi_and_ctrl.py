@@ -47,7 +47,7 @@ def test_shape_validation_is_host_side():
     h = ctypes.c_void_p()
     for bad, code in (((500, 1024, 8, 2, 0, 9), -2), ((512, 1000, 8, 2, 0, 9), -2), ((512, 1024, 8, 9, 0, 9), -1),
                       ((512, 1024, 300, 2, 0, 9), -2), ((512, 1024, 8, 2, 0, 17), -2), ((512, 1024, 8, 0, 0, 9), -1),
-                      ((512, 1024, 8, 2, 9, 9), -2)):
+                      ((512, 1024, 8, 2, 9, 9), -2), ((512, 1024, 8, 2, 0, 9, 2), -1)):
         s = binding.MoeShape(*bad)
         assert L.moe_ctx_create(ctypes.byref(s), ctypes.byref(h)) == code
         assert not h.value
