@@ -126,6 +126,18 @@ def main():
         gbs = float(ubytes[m].mean()) / (lat_ms * 1e-3) / 1e9
         by_k[str(k)] = {"latency_us": round(lat_ms * 1e3, 1), "mean_unique": round(float(nu_h[m].mean()), 2),
                         "unique_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    # spread of single steps: one event pair per step (each pair puts extra packets into the chain, so these
+    # run ~3 us above the grouped figure; they are reported for the p10/p90 spread only)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
+    for j in range(K_steps):
+        evs[j][0].record()
+        step(W_steps + j)
+        evs[j][1].record()
+    torch.cuda.synchronize()
+    single = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+    for k in by_k:
+        v = single[ks == int(k)]
+        by_k[k]["single_step_us_p10_p50_p90"] = [round(float(np.percentile(v, q)), 1) for q in (10, 50, 90)]
     k0 = by_k.get("0", {}).get("latency_us")
     if k0:
         for k in by_k:

@@ -43,12 +43,15 @@ class HiddenPool:
         return self.dev[(i % self.n_pool, T)]
 
 
-def build_stack(cfg, layers, ctx, layout="tiled", first_layer=0):
-    """Generate `layers` layers of weights directly in HBM (and re-lay them out once if tiled)."""
+def build_stack(cfg, layers, ctx, layout="tiled", first_layer=0, weights="bf16"):
+    """Generate `layers` layers of weights directly in HBM (and re-lay them out once if tiled).
+    weights = "fp8": E4M3 codes + per-row scales (tiled layout only)."""
     import torch
+    if weights == "fp8" and layout != "tiled":
+        raise ValueError("FP8 weights are streamed in the tiled layout only")
     out = []
     for l in range(layers):
-        wd = synth.layer_weights_device(cfg, first_layer + l)
+        wd = (synth.layer_weights_fp8_device if weights == "fp8" else synth.layer_weights_device)(cfg, first_layer + l)
         w = ctx.weights(wd)
         if layout == "tiled":
             w = ctx.moe_pack_weights(w)
@@ -134,10 +137,11 @@ def main(argv=None):
     ap.add_argument("--layout", choices=("tiled", "row"), default="tiled")
     ap.add_argument("--static", type=str, default="", help="comma list of static K baselines to run too, e.g. 0,1,2,3")
     ap.add_argument("--log", default=None)
+    ap.add_argument("--weights", choices=("bf16", "fp8"), default="bf16")
     a = ap.parse_args(argv)
     cfg = synth.CONFIGS[a.config]
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode)
-    stack = build_stack(cfg, a.layers, ctx, a.layout)
+    stack = build_stack(cfg, a.layers, ctx, a.layout, weights=a.weights)
     pool = HiddenPool(cfg, a.layers, a.rho)
     res = {"cascade": run(cfg, a.layers, a.iters, a.rho, a.layout, log=a.log, ctx=ctx, stack=stack, pool=pool)[0]}
     for k in [int(v) for v in a.static.split(",") if v != ""]:
@@ -147,6 +151,8 @@ def main(argv=None):
     if base:
         for v in res.values():
             v["speedup_vs_no_spec"] = round(base["tpot_ms"] / v["tpot_ms"], 4)
+    for v in res.values():
+        v["weights"] = a.weights
     print(json.dumps(res))
     ctx.close()
     return 0
