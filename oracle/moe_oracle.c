@@ -326,3 +326,28 @@ int oracle_route_softmax_all(const float* hidden, const uint16_t* router_w, int 
   if (!logits_out) free(logit);
   return rc;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Chained decoder stack (the per-layer inputs are no longer independent: each MoE layer sits in a
+ * pre-norm residual block, as in the Table 1 model families):
+ *     n = RMSNorm(x) * gamma ;   x' = x + MoELayer(n)
+ * RMSNorm of one token: n_j = x_j / sqrt( (1/d) sum_j x_j^2 + eps ) * gamma_j, gamma in bf16, the sum
+ * taken in index order in REAL; n is rounded to fp32 because that is what the layer takes as hidden.
+ * The paper's cost model needs no chaining (the expert-layer latency is what varies with K); the
+ * chain is the alternative reading of how layer l+1 gets its input.
+ * --------------------------------------------------------------------------------------------- */
+void oracle_rmsnorm(const float* x, const uint16_t* gamma, int T, int d, double eps, float* y) {
+  for (int t = 0; t < T; ++t) {
+    const float* xt = x + (size_t)t * d;
+    REAL ss = 0;
+    for (int j = 0; j < d; ++j) ss += (REAL)xt[j] * (REAL)xt[j];
+    const REAL mean = ss / (REAL)d;
+    const REAL root = sizeof(REAL) == sizeof(float) ? (REAL)sqrtf((float)(mean + (REAL)eps)) : (REAL)sqrt((double)mean + eps);
+    for (int j = 0; j < d; ++j) y[(size_t)t * d + j] = (float)(((REAL)xt[j] / root) * (REAL)bf16_widen(gamma[j]));
+  }
+}
+
+/* x_out = x_in + delta, element by element in REAL, rounded to fp32 (the residual stream is fp32). */
+void oracle_residual_add(const float* x_in, const float* delta, size_t n, float* x_out) {
+  for (size_t i = 0; i < n; ++i) x_out[i] = (float)((REAL)x_in[i] + (REAL)delta[i]);
+}

@@ -61,6 +61,10 @@ def _load(path: str, precision: str):
     L.oracle_dense_masked.argtypes = comb
     L.oracle_layer.restype = ctypes.c_int
     L.oracle_layer.argtypes = [_f32p] + [ctypes.c_int] * 6 + [_u16p] * 7 + [_i32p, _f32p, _f32p]
+    L.oracle_rmsnorm.restype = None
+    L.oracle_rmsnorm.argtypes = [_f32p, _u16p, ctypes.c_int, ctypes.c_int, ctypes.c_double, _f32p]
+    L.oracle_residual_add.restype = None
+    L.oracle_residual_add.argtypes = [_f32p, _f32p, ctypes.c_size_t, _f32p]
     L.oracle_fp8_e4m3_value.restype = ctypes.c_double
     L.oracle_fp8_e4m3_value.argtypes = [ctypes.c_uint8]
     L.oracle_expert_ffn_fp8.restype = None
@@ -324,3 +328,46 @@ def layer_fp8(hidden, W, top_k, n_shared=0, precision="f32", gate_mode=GATE_RENO
     if rc:
         raise ValueError("oracle_layer_fp8: bad sizes")
     return out, ids, gates
+
+
+# ---------------------------------------------------------------------------------------------
+# Chained stack: pre-norm residual blocks  x' = x + Layer(RMSNorm(x) * gamma)
+# ---------------------------------------------------------------------------------------------
+def rmsnorm(x, gamma, eps=1e-5, precision="f32"):
+    """x[T,d] fp32, gamma[d] bf16 bits -> RMSNorm(x) * gamma, fp32 [T,d]."""
+    x, xp = _f32(x)
+    gamma, gp = _u16(gamma)
+    T, d = x.shape
+    assert gamma.shape == (d,)
+    y = np.empty((T, d), np.float32)
+    _lib(precision).oracle_rmsnorm(xp, gp, T, d, float(eps), y.ctypes.data_as(_f32p))
+    return y
+
+
+def residual_add(x, delta, precision="f32"):
+    x, xp = _f32(x)
+    delta, dp = _f32(delta)
+    assert x.shape == delta.shape
+    out = np.empty_like(x)
+    _lib(precision).oracle_residual_add(xp, dp, x.size, out.ctypes.data_as(_f32p))
+    return out
+
+
+def chained_block(x, W, gamma, top_k, n_shared=0, eps=1e-5, precision="f32", gate_mode=GATE_RENORM_TOPK):
+    """One pre-norm residual MoE block.  W: bf16 layer dict, or FP8 layer dict (has "q1").
+    -> x_out[T,d], normed[T,d] (what the layer saw), ids, gates."""
+    n = rmsnorm(x, gamma, eps, precision)
+    fn = layer_fp8 if "q1" in W else layer
+    m, ids, gates = fn(n, W, top_k, n_shared, precision, gate_mode)
+    return residual_add(x, m, precision), n, ids, gates
+
+
+def chained_stack(x0, layers, gammas, top_k, n_shared=0, eps=1e-5, precision="f32", gate_mode=GATE_RENORM_TOPK):
+    """Blocks applied one after another.  -> x_L, list of the residual stream entering each block, list of ids."""
+    x = np.ascontiguousarray(x0, dtype=np.float32)
+    trace, all_ids = [], []
+    for W, g in zip(layers, gammas):
+        trace.append(x)
+        x, _, ids, _ = chained_block(x, W, g, top_k, n_shared, eps, precision, gate_mode)
+        all_ids.append(ids)
+    return x, trace, all_ids

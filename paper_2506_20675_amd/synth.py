@@ -42,6 +42,7 @@ T_Z_SHARED, T_Z_TOKEN, T_ACCEPT, T_REGIME = 8, 9, 10, 11
 # FP8 variants of the expert tensors: code streams and per-row scale streams
 T_Q = {"q1": 12, "q3": 13, "q2": 14, "sq1": 15, "sq3": 16, "sq2": 17}
 T_S = {"s1": 18, "s3": 19, "s2": 20, "ss1": 21, "ss3": 22, "ss2": 23}
+T_GAMMA = 24   # RMSNorm weight of the block in front of a layer (chained stack)
 
 SIGMA_EXPERT = 0.02
 SIGMA_ROUTER = 0.05
@@ -307,6 +308,12 @@ def layer_weights_fp8_host(cfg: MoEConfig, layer: int = 0) -> dict:
         out[qn] = codes_e4m3(weight_key(cfg, layer, T_Q[qn]), int(np.prod(shape))).reshape(shape)
         out[sn] = channel_scales(weight_key(cfg, layer, T_S[sn]), shape[0] * shape[1]).reshape(shape[:2])
     return out
+
+
+def norm_gamma_host(cfg: MoEConfig, layer: int) -> np.ndarray:
+    """RMSNorm weight gamma[d] of the block in front of `layer`, bf16 bits: 1 + 0.1 z (trained norms sit near 1)."""
+    z = bf16_bits_to_f32(normal_bf16(weight_key(cfg, layer, T_GAMMA), 0.1, cfg.d, force_numpy=True))
+    return f32_to_bf16_bits(np.float32(1.0) + z)
 
 
 def hidden_host(cfg: MoEConfig, layer: int, iteration: int, T: int, rho: float) -> np.ndarray:

@@ -9,6 +9,7 @@ import pytest
 from oracle import moe_oracle as orc
 import test_oracle_pins as pins
 import test_oracle_fp8_pins as fp8pins
+import test_oracle_chain_pins as chainpins
 
 MUTANTS = {
     "swap_w1_w3_roles": ("h[r] = (g / ((REAL)1 + real_exp(-g))) * u;", "h[r] = (u / ((REAL)1 + real_exp(-u))) * g;"),
@@ -62,6 +63,22 @@ PIN_CALLS_GATE = [
     lambda: pins.test_softmax_all_layer_scales_each_token_by_its_pick_mass("f64"),
 ]
 
+MUTANTS_CHAIN = {
+    "rmsnorm_sum_not_mean": ("const REAL mean = ss / (REAL)d;", "const REAL mean = ss;"),
+    "rmsnorm_eps_outside_root": ("(REAL)sqrtf((float)(mean + (REAL)eps)) : (REAL)sqrt((double)mean + eps);",
+                                 "(REAL)(sqrtf((float)mean) + (float)eps) : (REAL)(sqrt((double)mean) + eps);"),
+    "rmsnorm_gamma_index_off_by_one": ("(REAL)bf16_widen(gamma[j]));", "(REAL)bf16_widen(gamma[(j + 1) % d]));"),
+    "rmsnorm_uses_first_token_stats": ("ss += (REAL)xt[j] * (REAL)xt[j];", "ss += (REAL)x[j] * (REAL)x[j];"),
+    "rmsnorm_no_root": ("y[(size_t)t * d + j] = (float)(((REAL)xt[j] / root)", "y[(size_t)t * d + j] = (float)(((REAL)xt[j] / (mean + (REAL)eps))"),
+    "residual_drops_skip_path": ("x_out[i] = (float)((REAL)x_in[i] + (REAL)delta[i]);", "x_out[i] = (float)((REAL)delta[i]);"),
+}
+
+PIN_CALLS_CHAIN = [
+    lambda: chainpins.test_rmsnorm_hand_values_and_invariants("f64"),
+    lambda: chainpins.test_rmsnorm_eps_sits_inside_the_root_next_to_the_mean("f64"),
+    lambda: chainpins.test_chained_block_wiring("f64"),
+]
+
 PIN_CALLS_FP8 = [
     lambda: fp8pins.test_e4m3_golden_corner_values(),
     lambda: fp8pins.test_e4m3_all_codes_match_library_type_and_structure(),
@@ -85,10 +102,11 @@ PIN_CALLS = [
 ]
 
 
-_GROUPS = ((MUTANTS, lambda: PIN_CALLS), (MUTANTS_FP8, lambda: PIN_CALLS_FP8), (MUTANTS_GATE, lambda: PIN_CALLS_GATE))
+_GROUPS = ((MUTANTS, lambda: PIN_CALLS), (MUTANTS_FP8, lambda: PIN_CALLS_FP8), (MUTANTS_GATE, lambda: PIN_CALLS_GATE),
+           (MUTANTS_CHAIN, lambda: PIN_CALLS_CHAIN))
 
 
-@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8) + sorted(MUTANTS_GATE))
+@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8) + sorted(MUTANTS_GATE) + sorted(MUTANTS_CHAIN))
 def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
     table, get_calls = next((m, c) for m, c in _GROUPS if name in m)
     old, new = table[name]
