@@ -177,6 +177,20 @@ moe_status moe_verify_layer(moe_ctx* ctx, const moe_layer_weights* w, const floa
 moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32_t L, const float* hidden,
                             int32_t T, float* out, int32_t* n_unique_per_layer_opt, void* stream);
 
+/* L pre-norm residual MoE blocks back to back on one stream, each feeding the next (the alternative to
+ * independent per-layer inputs; Table 1's model families are built from such blocks, and Section 2.2's
+ * verification step runs all of them for the K+1 tokens):
+ *   x_{l+1} = x_l + MoE_l( RMSNorm(x_l) * gamma_l ),   RMSNorm(x)_j = x_j / sqrt( mean_j x_j^2 + eps )
+ * with the MoE layer exactly as in moe_verify_layer.  The sum over a token's picks, the residual add and
+ * the next block's normalisation run in one kernel; the residual stream stays fp32.
+ * layers: HOST array of L structs (copied during the call).  gammas: HOST array of L DEVICE pointers to
+ * bf16 [d], 16-byte aligned.  x_in, x_out: DEVICE [T,d] fp32 (x_out = x_L; may equal x_in).
+ * trace_opt: DEVICE [L,T,d] fp32 or NULL; receives x_l, the stream entering block l (trace[0] = x_in).
+ * n_unique_per_layer_opt: DEVICE [L] int32 or NULL.  L = 1 is a single block.  Needs d <= 16384. */
+moe_status moe_chained_stack(moe_ctx* ctx, const moe_layer_weights* layers, const uint16_t* const* gammas, int32_t L,
+                             const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
+                             int32_t* n_unique_per_layer_opt, void* stream);
+
 /* Measurement aid: per-kernel timing.  While enabled, every moe_verify_layer / moe_verify_stack
  * layer records HIP events on its stream around each of its four kernels (route, gate/up with the
  * expert-union step, down, combine); this adds event packets between the kernels, so whole-step latency is measured with

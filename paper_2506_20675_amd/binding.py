@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
                 -4: "MOE_ERR_HIP", -5: "MOE_ERR_UNIMPLEMENTED"}
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
-           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_stream_read_probe",
+           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_stream_read_probe",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
            "cascade_next_k", "cascade_observe", "cascade_get_state")
@@ -87,6 +87,9 @@ def lib():
     L.moe_verify_layer.restype = ctypes.c_int
     L.moe_verify_layer.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_void_p, c_int32, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_chained_stack.restype = ctypes.c_int
+    L.moe_chained_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), POINTER(c_void_p), c_int32, c_void_p, c_int32,
+                                    ctypes.c_float, c_void_p, c_void_p, c_void_p, c_void_p]
     L.moe_verify_stack.restype = ctypes.c_int
     L.moe_verify_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_int32, c_void_p, c_int32, c_void_p,
                                    c_void_p, c_void_p]
@@ -303,6 +306,26 @@ class MoeContext:
         arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
         _check(lib().moe_verify_stack(self._h, arr, L, _ptr(hidden), T, _ptr(out), _ptr(n_unique_per_layer),
                                       _stream_ptr(stream)), "moe_verify_stack")
+
+
+    def moe_chained_stack(self, layers, gammas, x_in, x_out, eps=1e-5, trace=None, n_unique_per_layer=None,
+                          stream=None):
+        """L pre-norm residual MoE blocks, each feeding the next.  gammas: L CUDA tensors [d] (16-bit)."""
+        import torch
+        s = self.shape
+        L, T = len(layers), x_in.shape[0]
+        if len(gammas) != L:
+            raise ValueError("one norm weight per layer")
+        _want(x_in, torch.float32, (T, s.d), "x_in")
+        _want(x_out, torch.float32, (T, s.d), "x_out")
+        _want(trace, torch.float32, (L, T, s.d), "trace")
+        _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
+        for g in gammas:
+            _want_bf16(g, (s.d,), "gamma")
+        arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
+        garr = (c_void_p * L)(*[g.data_ptr() for g in gammas])
+        _check(lib().moe_chained_stack(self._h, arr, garr, L, _ptr(x_in), T, ctypes.c_float(eps), _ptr(x_out),
+                                       _ptr(trace), _ptr(n_unique_per_layer), _stream_ptr(stream)), "moe_chained_stack")
 
 
 def moe_stream_read_probe(src, sink, stream=None):

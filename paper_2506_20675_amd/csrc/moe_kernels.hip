@@ -784,6 +784,78 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
   *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
 }
 
+// ------------------------------------------------------------------------------------------
+// Chained stack: one workgroup per token finishes block l-1 and prepares block l in one pass over d:
+//   x_l = x_{l-1} + (slabs of the token's picks, as in combine_kernel)      -> resid_out
+//   n   = x_l / sqrt(mean(x_l^2) + eps) * gamma_l                           -> xn_out (the router's input)
+// partial == NULL: no MoE term (first block: x_0 is the caller's input).  gamma == NULL: no
+// normalisation (after the last block only the residual stream is wanted).
+// ------------------------------------------------------------------------------------------
+struct ChainArgs {
+  const float* partial;
+  const int32_t* tok_slot;
+  const float* resid_in;   // [T, d]
+  float* resid_out;        // [T, d] or NULL
+  const uint16_t* gamma;   // [d] bf16 or NULL
+  float* xn_out;           // [T, d], used with gamma
+  int d, T, top_k, u_max, n_shared, max_tokens, KS;
+  float eps;
+};
+constexpr int kChainThreads = 1024;
+constexpr int kChainVecs = 4;  // float4 per thread: d <= 4 * 4 * 1024
+
+__global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) {
+  __shared__ float s_ss[kChainThreads / 64];
+  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int per_tok = g.d >> 2;
+  const size_t slab = (size_t)g.max_tokens * g.d;
+  const int n = g.partial ? (g.top_k + g.n_shared) * g.KS : 0;
+  float4 v[kChainVecs];
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < kChainVecs; ++q) {
+    const int c4 = tid + q * kChainThreads;
+    v[q] = float4{0.f, 0.f, 0.f, 0.f};
+    if (c4 < per_tok) {
+      const size_t o = (size_t)t * g.d + (size_t)c4 * 4;
+      float4 m = float4{0.f, 0.f, 0.f, 0.f};  // the MoE term, summed as combine_kernel sums it
+#pragma unroll 8
+      for (int i = 0; i < n; ++i) {
+        const int j = i / g.KS, k = i - j * g.KS;
+        const int u = j < g.top_k ? g.tok_slot[t * g.top_k + j] : g.u_max + (j - g.top_k);
+        const float4 p = *reinterpret_cast<const float4*>(g.partial + o + ((size_t)u * g.KS + k) * slab);
+        m.x += p.x, m.y += p.y, m.z += p.z, m.w += p.w;
+      }
+      const float4 x = *reinterpret_cast<const float4*>(g.resid_in + o);
+      v[q] = float4{x.x + m.x, x.y + m.y, x.z + m.z, x.w + m.w};
+      if (g.resid_out) *reinterpret_cast<float4*>(g.resid_out + o) = v[q];
+      ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
+    }
+  }
+  if (!g.gamma) return;  // uniform over the grid
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if (lane == 0) s_ss[wave] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < kChainThreads / 64; ++w) tot += s_ss[w];
+  const float root = sqrtf(tot / (float)g.d + g.eps);
+#pragma unroll
+  for (int q = 0; q < kChainVecs; ++q) {
+    const int c4 = tid + q * kChainThreads;
+    if (c4 < per_tok) {
+      const uint2 gb = *reinterpret_cast<const uint2*>(g.gamma + (size_t)c4 * 4);
+      float4 y;
+      y.x = (v[q].x / root) * bf16_to_f32(gb.x & 0xffffu);
+      y.y = (v[q].y / root) * bf16_to_f32(gb.x >> 16);
+      y.z = (v[q].z / root) * bf16_to_f32(gb.y & 0xffffu);
+      y.w = (v[q].w / root) * bf16_to_f32(gb.y >> 16);
+      *reinterpret_cast<float4*>(g.xn_out + (size_t)t * g.d + (size_t)c4 * 4) = y;
+    }
+  }
+}
+
 // One-off re-layout of a row-major [rows, K] bf16 matrix into the tiled order (see WeightAddr).
 __global__ __launch_bounds__(256) void pack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t rows,
                                                    int K) {
@@ -858,6 +930,7 @@ struct moe_ctx {
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
   int32_t *ids, *n_unique, *slot_expert, *tok_slot;
   float *gates, *slot_gate, *partial;
+  float *xn, *resid[2];  // chained stack: normalised router input and the residual stream (ping-pong), [max_tokens, d]
   bool profiling;
   std::vector<hipEvent_t> events;  // kProfMarks per profiled layer-step
 };
@@ -971,8 +1044,11 @@ void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipS
 // One layer-step after validation: router, gate/up, down, slab sum.  The expert-union step has no
 // launch of its own: it is the liveness test at the top of the expert kernels.
 // unique / n_unique / n_unique_extra: optional DEVICE outputs.
+// out == NULL: the slabs are left for the caller (chained stack: chain_kernel sums them); *ks_used gets the
+// split-K factor they were written with.
 moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
-                        float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
+                        float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
+                        int* ks_used = nullptr) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
   if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;  // FP8 is streamed in the tiled layout only
@@ -1011,9 +1087,12 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     default: launch_down<1, 8>(c, da, tiled, fp8, st); break;
   }
   mark(c, st);
-  const int n4 = T * (s.d / 4);
-  hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
-                     (const int32_t*)c->tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
+  if (ks_used) *ks_used = p.dn_KS;
+  if (out) {
+    const int n4 = T * (s.d / 4);
+    hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
+                       (const int32_t*)c->tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
+  }
   mark(c, st);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -1112,6 +1191,8 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
   const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
   const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
+  const size_t o_xn = carve((size_t)s.max_tokens * s.d * 4);
+  const size_t o_r0 = carve((size_t)s.max_tokens * s.d * 4), o_r1 = carve((size_t)s.max_tokens * s.d * 4);
   c->ws_bytes = off;
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
@@ -1129,6 +1210,9 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
   c->tok_slot = reinterpret_cast<int32_t*>(c->ws + o_ts);
   c->partial = reinterpret_cast<float*>(c->ws + o_part);
+  c->xn = reinterpret_cast<float*>(c->ws + o_xn);
+  c->resid[0] = reinterpret_cast<float*>(c->ws + o_r0);
+  c->resid[1] = reinterpret_cast<float*>(c->ws + o_r1);
   if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
     delete c;
@@ -1204,6 +1288,45 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
       return rc;
   }
   return MOE_OK;
+}
+
+moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const uint16_t* const* gammas, int32_t L,
+                             const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
+                             int32_t* n_unique_per_layer_opt, void* stream) {
+  if (!c || !layers || !gammas || L < 1 || !x_in || !x_out || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
+  if (!(eps >= 0.f) || !aligned16(x_in) || !aligned16(x_out) || (trace_opt && !aligned16(trace_opt)))
+    return MOE_ERR_INVALID_ARG;
+  if (c->s.d > 4 * kChainVecs * kChainThreads) return MOE_ERR_UNSUPPORTED_SHAPE;
+  for (int l = 0; l < L; ++l) {
+    if (!weights_ok(c, layers + l) || !gammas[l] || !aligned16(gammas[l])) return MOE_ERR_INVALID_ARG;
+    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
+  }
+  if (moe_status st = check_stream_device(c)) return st;
+  hipStream_t st = (hipStream_t)stream;
+  const moe_shape& s = c->s;
+  const size_t per = (size_t)T * s.d;
+  const float* cur = x_in;  // x_{l-1}: the stream the pending MoE term is added to
+  int ks = 1;
+  for (int l = 0; l <= L; ++l) {
+    // finish block l-1 (if any) and, unless this is the end, normalise for block l
+    ChainArgs a{};
+    a.partial = l > 0 ? c->partial : nullptr;
+    a.tok_slot = c->tok_slot;
+    a.resid_in = cur;
+    float* dst = l == L ? x_out : (trace_opt ? trace_opt + (size_t)l * per : (l > 0 ? c->resid[l & 1] : nullptr));
+    a.resid_out = dst;  // l == 0 without a trace: x_0 stays where the caller has it
+    a.gamma = l < L ? gammas[l] : nullptr;
+    a.xn_out = c->xn;
+    a.d = s.d, a.T = T, a.top_k = s.top_k, a.u_max = c->u_max, a.n_shared = s.n_shared, a.max_tokens = s.max_tokens;
+    a.KS = ks, a.eps = eps;
+    if (l > 0 || dst || a.gamma) hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, a);
+    if (dst) cur = dst;
+    if (l == L) break;
+    if (moe_status rc = launch_layer(c, layers + l, c->xn, T, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks))
+      return rc;
+  }
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 moe_status moe_pack_weights(moe_ctx* c, const moe_layer_weights* src, moe_layer_weights* dst, void* stream) {

@@ -541,3 +541,101 @@ def test_layer_parity_remaining_table1_shapes(cfg, weights):
         else:
             _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared), W, x, ctx, Wd, gate_mode=cfg.gate_mode)
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# Chained stack: pre-norm residual MoE blocks, each feeding the next
+# ------------------------------------------------------------------------------------------
+def _routing_margin_ok(n, router_w, k, E, need=1e-4):
+    """The GPU normalises in another summation order than the oracle, so the two routers see inputs that differ in
+    the last bits; their picks agree whenever the k-th/(k+1)-th logit gap is far above that (seeds are screened)."""
+    if E <= k:
+        return True
+    _, _, logits = orc.route(n, router_w, k, "f64")
+    srt = np.sort(logits, axis=1)[:, ::-1]
+    return (srt[:, k - 1] - srt[:, k]).min() > need and (srt[:, :k - 1] - srt[:, 1:k]).min(initial=1.0) > need
+
+
+def _chain_block_check(ctx, lw, W, gam, gam_d, x, k, ns, eps=1e-5):
+    """One block, teacher-forced: the GPU gets the oracle's input x and must reproduce the oracle's x'."""
+    import torch
+    T, d = x.shape
+    xo = torch.full((T, d), float("nan"), dtype=torch.float32, device="cuda")
+    tr = torch.full((1, T, d), float("nan"), dtype=torch.float32, device="cuda")
+    nu = torch.full((1,), -3, dtype=torch.int32, device="cuda")
+    ctx.moe_chained_stack([lw], [gam_d], _dev(x), xo, eps, tr, nu)
+    torch.cuda.synchronize()
+    gm = ctx.shape.gate_mode
+    r32, n32, ids, _ = orc.chained_block(x, W, gam, k, ns, eps, "f32", gm)
+    r64, n64, ids64, _ = orc.chained_block(x, W, gam, k, ns, eps, "f64", gm)
+    assert _routing_margin_ok(n64, W["router_w"], k, ctx.shape.n_experts), "seed produces a routing near-tie; pick another"
+    np.testing.assert_array_equal(ids, ids64)
+    np.testing.assert_array_equal(tr[0].cpu().numpy(), x)                       # the stream entering the block
+    assert int(nu.item()) == orc.union(ids64, ctx.shape.n_experts)["n_unique"]
+    got = xo.cpu().numpy().astype(np.float64)
+    # the update x' - x is what the block computes: held to the same bars as a layer's output
+    _check_out((got - x).astype(np.float32), (r32.astype(np.float64) - x).astype(np.float32), r64.astype(np.float64) - x)
+    return r64
+
+
+@pytest.mark.parametrize("T", [1, 5, 9])
+def test_chained_block_parity_tiny(T):
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 5)
+    gam = synth.norm_gamma_host(cfg, 5)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    Wd = _weights_dev(W)
+    x = (synth.hidden_host(cfg, 5, 70 + T, T, 0.5) * np.float32(3.0)).astype(np.float32)
+    for lw in (ctx.weights(Wd), _tiled(ctx, Wd)):
+        _chain_block_check(ctx, lw, W, gam, _dev(gam), x, cfg.top_k, 0)
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg,weights", [(synth.DEEPSEEK, "bf16"), (synth.QWEN15, "fp8"), (synth.OLMOE, "fp8")],
+                         ids=lambda v: v if isinstance(v, str) else v.name)
+def test_chained_block_parity_full_size_shapes(cfg, weights):
+    W = synth.layer_weights_fp8_host(cfg, 2) if weights == "fp8" else synth.layer_weights_host(cfg, 2)
+    gam = synth.norm_gamma_host(cfg, 2)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 9, gate_mode=cfg.gate_mode)
+    Wd = _weights_dev(W)
+    lw = _tiled(ctx, Wd)
+    for it, T in enumerate((1, 6)):
+        x = (synth.hidden_host(cfg, 2, 700 + it, T, 0.5) * np.float32(0.25)).astype(np.float32)
+        _chain_block_check(ctx, lw, W, gam, _dev(gam), x, cfg.top_k, cfg.n_shared)
+    ctx.close()
+
+
+def test_chained_stack_teacher_forced_and_free_running():
+    """Four blocks: every block reproduces the oracle's next stream from the oracle's current one (teacher-forced), and
+    the free-running GPU chain ends where the oracle's chain ends (the routing agrees at every block on this seed)."""
+    import torch
+    cfg = synth.TINY
+    L, T = 4, 5
+    Ws = [synth.layer_weights_host(cfg, 30 + l) for l in range(L)]
+    gs = [synth.norm_gamma_host(cfg, 30 + l) for l in range(L)]
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    Wds = [_weights_dev(W) for W in Ws]
+    lws = [ctx.moe_pack_weights(ctx.weights(w)) for w in Wds]
+    gds = [_dev(g) for g in gs]
+    x0 = synth.hidden_host(cfg, 30, 0, T, 0.5)
+    xL, trace, ids = orc.chained_stack(x0, Ws, gs, cfg.top_k, 0, 1e-5, "f64")
+    for l in range(L):
+        nxt = _chain_block_check(ctx, lws[l], Ws[l], gs[l], gds[l], trace[l], cfg.top_k, 0)
+        np.testing.assert_array_equal(nxt, trace[l + 1] if l + 1 < L else xL)
+    out = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+    tr = torch.zeros((L, T, cfg.d), dtype=torch.float32, device="cuda")
+    nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+    ctx.moe_chained_stack(lws, gds, _dev(x0), out, 1e-5, tr, nu)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert int(nu[l].item()) == orc.union(ids[l], cfg.n_experts)["n_unique"]
+        e = tr[l].cpu().numpy().astype(np.float64) - trace[l]
+        assert np.sqrt((e ** 2).sum() / (trace[l].astype(np.float64) ** 2).sum()) <= 1e-4
+    e = out.cpu().numpy().astype(np.float64) - xL
+    assert np.sqrt((e ** 2).sum() / (xL.astype(np.float64) ** 2).sum()) <= 1e-4
+    # without a trace, and in place, the chain gives the same bits
+    out2 = _dev(x0).clone()
+    ctx.moe_chained_stack(lws, gds, out2, out2, 1e-5)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out2.cpu().numpy(), out.cpu().numpy())
+    ctx.close()
