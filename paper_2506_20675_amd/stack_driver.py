@@ -61,8 +61,10 @@ def build_stack(cfg, layers, ctx, layout="tiled", first_layer=0, weights="bf16")
 
 
 def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_field=0, params=None,
-        static_k=None, log=None, ctx=None, stack=None, pool=None):
+        static_k=None, log=None, ctx=None, stack=None, pool=None, gammas=None):
     """Runs the loop; static_k = None uses the controller, an int forces that K every iteration.
+    gammas (one RMSNorm weight tensor per layer) switches to the chained stack: the layers feed each other
+    through pre-norm residual blocks and only layer 0's pooled input is used.
     Returns (summary dict, per-iteration records)."""
     import torch
     own = ctx is None
@@ -79,7 +81,15 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
     nu = torch.zeros((layers,), dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     # warm-up: touch every layer once at the largest T
-    ctx.moe_verify_stack(stack, pool.get(0, pool.t_max), out[:, :pool.t_max].contiguous(), nu)
+    chain_out = torch.empty((synth.K_MAX + 1, cfg.d), dtype=torch.float32, device="cuda")
+
+    def step(hid, o, T):
+        if gammas is None:
+            ctx.moe_verify_stack(stack, hid, o, nu)
+        else:
+            ctx.moe_chained_stack(stack, gammas, hid[0], chain_out[:T], 1e-5, None, nu)
+
+    step(pool.get(0, pool.t_max), out[:, :pool.t_max].contiguous(), pool.t_max)
     torch.cuda.synchronize()
     recs = []
     t_wall = time.perf_counter()
@@ -89,7 +99,7 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
         hid = pool.get(i, T)
         o = out[:, :T].contiguous() if T != out.shape[1] else out
         e0.record()
-        ctx.moe_verify_stack(stack, hid, o, nu)
+        step(hid, o, T)
         e1.record()
         e1.synchronize()
         t_verify = e0.elapsed_time(e1) * 1e-3
@@ -111,6 +121,7 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
         by_k.setdefault(r["K"], []).append(r["t_verify_ms"])
     summary = {
         "policy": "cascade" if static_k is None else f"static K={static_k}", "layers": layers, "iters": iters,
+        "chained": gammas is not None,
         "rho": rho, "layout": layout, "tokens": tok, "t_verify_total_ms": round(tv, 3),
         "tpot_ms": round(tv / tok, 4), "etr": round(tok / iters, 4),
         "K_histogram": {str(k): len(v) for k, v in sorted(by_k.items())},
@@ -138,15 +149,22 @@ def main(argv=None):
     ap.add_argument("--static", type=str, default="", help="comma list of static K baselines to run too, e.g. 0,1,2,3")
     ap.add_argument("--log", default=None)
     ap.add_argument("--weights", choices=("bf16", "fp8"), default="bf16")
+    ap.add_argument("--chained", action="store_true",
+                    help="pre-norm residual blocks feeding each other (moe_chained_stack) instead of independent inputs")
     a = ap.parse_args(argv)
     cfg = synth.CONFIGS[a.config]
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode)
     stack = build_stack(cfg, a.layers, ctx, a.layout, weights=a.weights)
     pool = HiddenPool(cfg, a.layers, a.rho)
-    res = {"cascade": run(cfg, a.layers, a.iters, a.rho, a.layout, log=a.log, ctx=ctx, stack=stack, pool=pool)[0]}
+    gammas = None
+    if a.chained:
+        import torch
+        gammas = [torch.from_numpy(synth.norm_gamma_host(cfg, l).view(np.int16)).cuda() for l in range(a.layers)]
+    res = {"cascade": run(cfg, a.layers, a.iters, a.rho, a.layout, log=a.log, ctx=ctx, stack=stack, pool=pool,
+                          gammas=gammas)[0]}
     for k in [int(v) for v in a.static.split(",") if v != ""]:
         res[f"static_{k}"] = run(cfg, a.layers, a.iters, a.rho, a.layout, static_k=k, ctx=ctx, stack=stack,
-                                 pool=pool)[0]
+                                 pool=pool, gammas=gammas)[0]
     base = res.get("static_0")
     if base:
         for v in res.values():
