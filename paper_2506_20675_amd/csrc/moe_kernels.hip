@@ -940,7 +940,6 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
-constexpr int kFp8GateupDepth = 6;  // pipeline depth of the FP8 gate/up kernel (2 KB of codes + 4 KB of fragments per stage)
 
 // Launch plan of the two expert kernels for one (T, weight layout).
 //   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
@@ -1062,14 +1061,17 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
   const bool pk = T <= kPackedTokens;  // must match what route_kernel wrote
   if (fp8) {
-    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
-    if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, true, true>), grid, dim3(64), 0, st, ga);
-    else hipLaunchKernelGGL((gateup_kernel<1, 1, kFp8GateupDepth, true, true, true, false>), grid, dim3(64), 0, st, ga);
+    // FP8 needs twice the fragment bytes per weight byte, and those come from L2: two tile pairs per wave
+    // share each fragment load, and a shallow pipeline keeps four waves per SIMD (measured best of
+    // {1, 2, 4} tile pairs x depths 2..10)
+    const dim3 grid((s.ffn / 16 + 1) / 2, routed_slots + s.n_shared);
+    if (pk) hipLaunchKernelGGL((gateup_kernel<2, 1, 3, true, true, true, true>), grid, dim3(64), 0, st, ga);
+    else hipLaunchKernelGGL((gateup_kernel<2, 1, 3, true, true, true, false>), grid, dim3(64), 0, st, ga);
   } else if (tiled) {
     // one wave per 16-row tile pair over the whole of d (splitting d over 2 or 4 waves when the union
     // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
     const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
-    if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false, true>), grid, dim3(64), 0, st, ga);
+    if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 6, true, true, false, true>), grid, dim3(64), 0, st, ga);
     else hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false, false>), grid, dim3(64), 0, st, ga);
   } else {
     switch (p.gu_R) {
