@@ -945,8 +945,7 @@ constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 //   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
 //               deeper pipeline, same bytes in flight per wave)
 //   dn_KS       split-K factor of the down projection across workgroups
-// Chosen from measurements on Mixtral-shaped layers: tiled weights stream best with one tile per wave
-// and 8 k-steps in flight; the down projection wants about 4-5 thousand waves in the grid.
+// Chosen from measurements on Mixtral-shaped layers (see plan_for).
 struct Plan {
   int gu_R, dn_R, dn_KS;
 };
@@ -969,11 +968,15 @@ Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
   const int cap = ks_cap_for(s, fp8);
   p.dn_R = 1;
   p.dn_KS = cap;
+  // measured on Mixtral-shaped layers: 4 k-chunks per (row block, slot) is within 1 us of the best split for
+  // every T (1 chunk loses 10 %, 8 chunks make the slab sum longer than they shorten the projection); grids
+  // that already hold four thousand waves (many small experts) are not split, tiny grids are split further
+  // until about a thousand waves are in flight
   for (int R : {4, 2, 1}) {
     const double per_ks = (double)((s.d / 16 + R - 1) / R) * kWaves * slots;
     int ks = 1;
-    while (ks < cap && per_ks * ks < 3584) ks *= 2;
-    if (per_ks * ks >= 3072 || R == 1) {
+    while (ks < cap && per_ks * ks < (ks < 4 ? 4096 : 1024)) ks *= 2;
+    if (per_ks * ks >= 1024 || R == 1) {
       p.dn_R = R;
       p.dn_KS = ks;
       break;
@@ -1084,7 +1087,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
               c->slot_gate, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
-    case 4: launch_down<4, 3>(c, da, tiled, fp8, st); break;
+    case 4: launch_down<4, 4>(c, da, tiled, fp8, st); break;
     case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
     default: launch_down<1, 8>(c, da, tiled, fp8, st); break;
   }
