@@ -685,3 +685,33 @@ def test_layer_and_chain_replay_from_a_hip_graph():
             torch.cuda.synchronize()
             assert torch.equal(out_layer, a) and torch.equal(out_chain, b)
     ctx.close()
+
+
+def test_degenerate_routings_identical_tokens_and_largest_supported_shape():
+    """All in-flight tokens identical (the limit of perfect expert affinity): the union is one token's picks, every
+    pick is shared by all tokens, all rows of the output agree.  And the largest routing the library accepts
+    (256 experts, top-16, 16 tokens: up to 256 live slots) against the oracle."""
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 6)
+    x1 = synth.hidden_host(cfg, 6, 0, 1, 0.5)
+    x = np.repeat(x1, 9, axis=0)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    Wd = _weights_dev(W)
+    for tiled in (False, True):
+        out, ids, gates, uniq, nu = _run_layer(ctx, Wd, x, tiled)
+        assert nu == cfg.top_k and (ids == ids[0]).all() and (gates == gates[0]).all()
+        assert sorted(uniq[:nu].tolist()) == sorted(ids[0].tolist())
+        np.testing.assert_array_equal(out, np.repeat(out[:1], 9, axis=0))
+        ref64, _, _ = orc.layer(x1, W, cfg.top_k, 0, "f64")
+        assert np.sqrt(((out[0] - ref64[0]) ** 2).sum() / (ref64[0] ** 2).sum()) <= 5e-5
+    ctx.close()
+    d, ffn, E, k, T = 128, 64, 256, 16, 16
+    rng = np.random.default_rng(77)
+    bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+    Wb = dict(router_w=bf(rng.normal(0, 0.3, (E, d))), w1=bf(rng.normal(0, 0.1, (E, ffn, d))),
+              w3=bf(rng.normal(0, 0.1, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))))
+    xb = rng.normal(size=(T, d)).astype(np.float32)
+    ctx = binding.MoeContext(d, ffn, E, k, 0, 16)
+    assert ctx.workspace_bytes > 0
+    _check_layer((d, ffn, E, k, 0), Wb, xb, ctx, _weights_dev(Wb))
+    ctx.close()
