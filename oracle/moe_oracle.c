@@ -351,3 +351,65 @@ void oracle_rmsnorm(const float* x, const uint16_t* gamma, int T, int d, double 
 void oracle_residual_add(const float* x_in, const float* delta, size_t n, float* x_out) {
   for (size_t i = 0; i < n; ++i) x_out[i] = (float)((REAL)x_in[i] + (REAL)delta[i]);
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Attention stub of the chained decoder block.  The paper needs attention only as the part of an
+ * iteration whose cost does NOT grow with K (Section 2.4: the expert layers are what grows; attention
+ * is a small, constant share).  The stub is therefore the attention block's weight traffic with the
+ * smallest arithmetic that is still attention: causal multi-head self-attention AMONG THE T IN-FLIGHT
+ * TOKENS ONLY (no cache of earlier context, no positional rotation, no biases), grouped-query form:
+ *   q_t = Wq n_t  [H heads x dh],   k_t = Wk n_t,  v_t = Wv n_t  [Hkv heads x dh]
+ *   head h uses kv head h / (H / Hkv);  s_{t,u} = (q_t . k_u) / sqrt(dh) for u <= t
+ *   p_{t,.} = softmax over u <= t;  o_t = sum_u p_{t,u} v_u;  a_t = Wo concat_h(o_t)
+ * wqkv: [(H + 2 Hkv) dh, d] bf16, rows ordered q heads, then k heads, then v heads; wo: [d, H dh] bf16.
+ * n: [T, d] fp32 (already normalised); out a: [T, d] fp32.  All sums in REAL, index order.
+ * --------------------------------------------------------------------------------------------- */
+int oracle_attention_stub(const float* n, const uint16_t* wqkv, const uint16_t* wo, int T, int d, int H, int Hkv,
+                          int dh, float* a) {
+  if (T < 1 || d < 1 || H < 1 || Hkv < 1 || dh < 1 || H % Hkv) return -1;
+  const int nq = H * dh, nkv = Hkv * dh, nout = nq + 2 * nkv;
+  REAL* qkv = (REAL*)malloc(sizeof(REAL) * (size_t)T * nout);
+  REAL* o = (REAL*)malloc(sizeof(REAL) * (size_t)T * nq);
+  REAL* p = (REAL*)malloc(sizeof(REAL) * (size_t)T);
+  for (int t = 0; t < T; ++t)
+    for (int r = 0; r < nout; ++r) {
+      REAL s = 0;
+      for (int j = 0; j < d; ++j) s += (REAL)bf16_widen(wqkv[(size_t)r * d + j]) * (REAL)n[(size_t)t * d + j];
+      qkv[(size_t)t * nout + r] = s;
+    }
+  const REAL scale = (REAL)1 / (sizeof(REAL) == sizeof(float) ? (REAL)sqrtf((float)dh) : (REAL)sqrt((double)dh));
+  for (int h = 0; h < H; ++h) {
+    const int g = h / (H / Hkv);
+    for (int t = 0; t < T; ++t) {
+      const REAL* q = qkv + (size_t)t * nout + (size_t)h * dh;
+      REAL m = 0;
+      for (int u = 0; u <= t; ++u) {
+        const REAL* k = qkv + (size_t)u * nout + nq + (size_t)g * dh;
+        REAL s = 0;
+        for (int j = 0; j < dh; ++j) s += q[j] * k[j];
+        p[u] = s * scale;
+        if (u == 0 || p[u] > m) m = p[u];
+      }
+      REAL sum = 0;
+      for (int u = 0; u <= t; ++u) {
+        p[u] = real_exp(p[u] - m);
+        sum += p[u];
+      }
+      for (int j = 0; j < dh; ++j) {
+        REAL acc = 0;
+        for (int u = 0; u <= t; ++u) acc += (p[u] / sum) * qkv[(size_t)u * nout + nq + nkv + (size_t)g * dh + j];
+        o[(size_t)t * nq + (size_t)h * dh + j] = acc;
+      }
+    }
+  }
+  for (int t = 0; t < T; ++t)
+    for (int c = 0; c < d; ++c) {
+      REAL s = 0;
+      for (int j = 0; j < nq; ++j) s += (REAL)bf16_widen(wo[(size_t)c * nq + j]) * o[(size_t)t * nq + j];
+      a[(size_t)t * d + c] = (float)s;
+    }
+  free(qkv);
+  free(o);
+  free(p);
+  return 0;
+}

@@ -65,6 +65,8 @@ def _load(path: str, precision: str):
     L.oracle_rmsnorm.argtypes = [_f32p, _u16p, ctypes.c_int, ctypes.c_int, ctypes.c_double, _f32p]
     L.oracle_residual_add.restype = None
     L.oracle_residual_add.argtypes = [_f32p, _f32p, ctypes.c_size_t, _f32p]
+    L.oracle_attention_stub.restype = ctypes.c_int
+    L.oracle_attention_stub.argtypes = [_f32p, _u16p, _u16p] + [ctypes.c_int] * 5 + [_f32p]
     L.oracle_fp8_e4m3_value.restype = ctypes.c_double
     L.oracle_fp8_e4m3_value.argtypes = [ctypes.c_uint8]
     L.oracle_expert_ffn_fp8.restype = None
@@ -369,5 +371,44 @@ def chained_stack(x0, layers, gammas, top_k, n_shared=0, eps=1e-5, precision="f3
     for W, g in zip(layers, gammas):
         trace.append(x)
         x, _, ids, _ = chained_block(x, W, g, top_k, n_shared, eps, precision, gate_mode)
+        all_ids.append(ids)
+    return x, trace, all_ids
+
+
+# ---------------------------------------------------------------------------------------------
+# Decoder block with the attention stub:  h = x + Attn(RMSNorm(x) g_a) ;  x' = h + Layer(RMSNorm(h) g_m)
+# ---------------------------------------------------------------------------------------------
+def attention_stub(n, wqkv, wo, n_heads, n_kv_heads, head_dim, precision="f32"):
+    """Causal grouped-query self-attention among the T rows of n[T,d] (no cache, no rotation) -> a[T,d] fp32.
+    wqkv: [(H + 2 Hkv) dh, d] bf16 bits (q heads, k heads, v heads); wo: [d, H dh] bf16 bits."""
+    n, np_ = _f32(n)
+    wqkv, pq = _u16(wqkv)
+    wo, po = _u16(wo)
+    T, d = n.shape
+    assert wqkv.shape == ((n_heads + 2 * n_kv_heads) * head_dim, d) and wo.shape == (d, n_heads * head_dim)
+    a = np.empty((T, d), np.float32)
+    rc = _lib(precision).oracle_attention_stub(np_, pq, po, T, d, n_heads, n_kv_heads, head_dim, a.ctypes.data_as(_f32p))
+    if rc:
+        raise ValueError("oracle_attention_stub: bad sizes")
+    return a
+
+
+def decoder_block(x, A, W, top_k, n_shared=0, eps=1e-5, precision="f32", gate_mode=GATE_RENORM_TOPK):
+    """A: dict(wqkv, wo, gamma_attn, gamma_moe, n_heads, n_kv_heads, head_dim); W: the MoE layer (bf16 or FP8 dict).
+    -> x_out, h (the stream after the attention half), ids, gates."""
+    n = rmsnorm(x, A["gamma_attn"], eps, precision)
+    h = residual_add(x, attention_stub(n, A["wqkv"], A["wo"], A["n_heads"], A["n_kv_heads"], A["head_dim"], precision),
+                     precision)
+    x_out, _, ids, gates = chained_block(h, W, A["gamma_moe"], top_k, n_shared, eps, precision, gate_mode)
+    return x_out, h, ids, gates
+
+
+def decoder_stack(x0, attn, layers, top_k, n_shared=0, eps=1e-5, precision="f32", gate_mode=GATE_RENORM_TOPK):
+    """-> x_L, list of the stream entering each block, list of ids."""
+    x = np.ascontiguousarray(x0, dtype=np.float32)
+    trace, all_ids = [], []
+    for A, W in zip(attn, layers):
+        trace.append(x)
+        x, _, ids, _ = decoder_block(x, A, W, top_k, n_shared, eps, precision, gate_mode)
         all_ids.append(ids)
     return x, trace, all_ids

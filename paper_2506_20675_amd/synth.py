@@ -43,6 +43,7 @@ T_Z_SHARED, T_Z_TOKEN, T_ACCEPT, T_REGIME = 8, 9, 10, 11
 T_Q = {"q1": 12, "q3": 13, "q2": 14, "sq1": 15, "sq3": 16, "sq2": 17}
 T_S = {"s1": 18, "s3": 19, "s2": 20, "ss1": 21, "ss3": 22, "ss2": 23}
 T_GAMMA = 24   # RMSNorm weight of the block in front of a layer (chained stack)
+T_WQKV, T_WO, T_GAMMA_ATTN = 25, 26, 27   # attention stub of the decoder block
 
 SIGMA_EXPERT = 0.02
 SIGMA_ROUTER = 0.05
@@ -314,6 +315,26 @@ def norm_gamma_host(cfg: MoEConfig, layer: int) -> np.ndarray:
     """RMSNorm weight gamma[d] of the block in front of `layer`, bf16 bits: 1 + 0.1 z (trained norms sit near 1)."""
     z = bf16_bits_to_f32(normal_bf16(weight_key(cfg, layer, T_GAMMA), 0.1, cfg.d, force_numpy=True))
     return f32_to_bf16_bits(np.float32(1.0) + z)
+
+
+def attn_geometry(cfg: MoEConfig):
+    """(query heads, kv heads, head dim) of the attention stub: head dim 128, hidden/128 query heads, a quarter as
+    many kv heads (the grouped-query shape of the Mixtral family: 32 / 8 / 128 at hidden 4096)."""
+    dh = 128 if cfg.d % 128 == 0 else 64
+    H = cfg.d // dh
+    return H, max(1, H // 4), dh
+
+
+def attn_weights_host(cfg: MoEConfig, layer: int) -> dict:
+    """Attention stub weights of block `layer`: wqkv [(H + 2 Hkv) dh, d], wo [d, H dh] ~ N(0, 0.02^2) bf16 bits, the
+    two norm weights, and the geometry."""
+    H, Hkv, dh = attn_geometry(cfg)
+    nq, nout = H * dh, (H + 2 * Hkv) * dh
+    g = bf16_bits_to_f32(normal_bf16(weight_key(cfg, layer, T_GAMMA_ATTN), 0.1, cfg.d, force_numpy=True))
+    return {"wqkv": normal_bf16(weight_key(cfg, layer, T_WQKV), SIGMA_EXPERT, nout * cfg.d).reshape(nout, cfg.d),
+            "wo": normal_bf16(weight_key(cfg, layer, T_WO), SIGMA_EXPERT, cfg.d * nq).reshape(cfg.d, nq),
+            "gamma_attn": f32_to_bf16_bits(np.float32(1.0) + g), "gamma_moe": norm_gamma_host(cfg, layer),
+            "n_heads": H, "n_kv_heads": Hkv, "head_dim": dh}
 
 
 def hidden_host(cfg: MoEConfig, layer: int, iteration: int, T: int, rho: float) -> np.ndarray:

@@ -96,3 +96,81 @@ def test_chained_stack_is_the_blocks_in_order_and_fp8_variant_runs():
     m8, j8, _ = orc.layer_fp8(n8, W8, cfg.top_k, 0, "f64")
     np.testing.assert_array_equal(i8, j8)
     np.testing.assert_allclose(x8, x0 + m8, rtol=0, atol=1e-6 * np.abs(x8).max())
+
+
+# ---------------------------------------------------------------- attention stub of the decoder block
+def _attn_case(seed, T=5, d=32, H=4, Hkv=2, dh=8):
+    rng = np.random.default_rng(seed)
+    wqkv = _bf16(rng.normal(0, 0.3, ((H + 2 * Hkv) * dh, d)))
+    wo = _bf16(rng.normal(0, 0.3, (d, H * dh)))
+    n = rng.normal(size=(T, d)).astype(np.float32)
+    return n, wqkv, wo, (H, Hkv, dh)
+
+
+def _f64(b):
+    return synth.bf16_bits_to_f32(b).astype(np.float64)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_attention_stub_matches_the_tensor_library_attention(prec):
+    """Projections by library GEMMs, the core by the tensor library's own causal scaled-dot-product attention with the
+    kv heads repeated over their query groups — nothing of the oracle's loops is reused."""
+    import torch
+    n, wqkv, wo, (H, Hkv, dh) = _attn_case(61)
+    T = n.shape[0]
+    a = orc.attention_stub(n, wqkv, wo, H, Hkv, dh, prec)
+    qkv = torch.from_numpy(n.astype(np.float64) @ _f64(wqkv).T)
+    q = qkv[:, :H * dh].reshape(T, H, dh).transpose(0, 1)
+    k = qkv[:, H * dh:(H + Hkv) * dh].reshape(T, Hkv, dh).transpose(0, 1).repeat_interleave(H // Hkv, 0)
+    v = qkv[:, (H + Hkv) * dh:].reshape(T, Hkv, dh).transpose(0, 1).repeat_interleave(H // Hkv, 0)
+    o = torch.nn.functional.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True)[0]
+    ref = o.transpose(0, 1).reshape(T, H * dh).numpy() @ _f64(wo).T
+    np.testing.assert_allclose(a, ref, rtol=0, atol=(3e-5 if prec == "f32" else 1e-6) * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_attention_stub_special_cases(prec):
+    n, wqkv, wo, (H, Hkv, dh) = _attn_case(62)
+    T, d = n.shape
+    a = orc.attention_stub(n, wqkv, wo, H, Hkv, dh, prec)
+    # one token attends to itself only: a = Wo . repeat(Wv n); also what row 0 of any longer call gives (causality)
+    a1 = orc.attention_stub(n[:1], wqkv, wo, H, Hkv, dh, prec)
+    v0 = _f64(wqkv)[(H + Hkv) * dh:] @ n[0].astype(np.float64)
+    o0 = np.concatenate([v0[(h // (H // Hkv)) * dh:(h // (H // Hkv) + 1) * dh] for h in range(H)])
+    np.testing.assert_allclose(a1[0], _f64(wo) @ o0, rtol=0, atol=(3e-5 if prec == "f32" else 1e-6) * np.abs(a1).max())
+    np.testing.assert_array_equal(a[0], a1[0])
+    # causal: changing later tokens leaves earlier rows untouched, bit for bit
+    n2 = n.copy()
+    n2[3:] += 1.0
+    a2 = orc.attention_stub(n2, wqkv, wo, H, Hkv, dh, prec)
+    np.testing.assert_array_equal(a2[:3], a[:3])
+    assert np.abs(a2[3:] - a[3:]).max() > 1e-3
+    # zero query weights: all scores equal, so every token gets the running mean of the values up to itself
+    wz = wqkv.copy()
+    wz[:H * dh] = 0
+    az = orc.attention_stub(n, wz, wo, H, Hkv, dh, prec)
+    vs = n.astype(np.float64) @ _f64(wqkv)[(H + Hkv) * dh:].T                 # [T, Hkv dh]
+    for t in range(T):
+        vm = vs[:t + 1].mean(axis=0)
+        o = np.concatenate([vm[(h // (H // Hkv)) * dh:(h // (H // Hkv) + 1) * dh] for h in range(H)])
+        np.testing.assert_allclose(az[t], _f64(wo) @ o, rtol=0, atol=(3e-5 if prec == "f32" else 1e-6) * np.abs(az).max())
+
+
+def test_decoder_block_wiring():
+    cfg = synth.TINY
+    A = synth.attn_weights_host(cfg, 7)
+    W = synth.layer_weights_host(cfg, 7)
+    assert (A["n_heads"], A["n_kv_heads"], A["head_dim"]) == (4, 1, 128)
+    x = synth.hidden_host(cfg, 7, 0, 3, 0.5)
+    xo, h, ids, _ = orc.decoder_block(x, A, W, cfg.top_k, 0, 1e-5, "f64")
+    a = orc.attention_stub(orc.rmsnorm(x, A["gamma_attn"], 1e-5, "f64"), A["wqkv"], A["wo"], 4, 1, 128, "f64")
+    np.testing.assert_allclose(h, x + a, rtol=0, atol=1e-6 * np.abs(h).max())
+    xo2, _, ids2, _ = orc.chained_block(h, W, A["gamma_moe"], cfg.top_k, 0, 1e-5, "f64")
+    np.testing.assert_array_equal(xo, xo2)
+    np.testing.assert_array_equal(ids, ids2)
+    assert np.abs(a).max() > 1e-2 and np.abs(xo - h).max() > 1e-2          # both halves contribute
+    Az = dict(A)
+    Az["wo"] = np.zeros_like(A["wo"])                                       # dead attention half: plain chained block
+    xz, hz, *_ = orc.decoder_block(x, Az, W, cfg.top_k, 0, 1e-5, "f64")
+    np.testing.assert_array_equal(hz, x)
+    np.testing.assert_array_equal(xz, orc.chained_block(x, W, A["gamma_moe"], cfg.top_k, 0, 1e-5, "f64")[0])

@@ -73,6 +73,22 @@ MUTANTS_CHAIN = {
     "residual_drops_skip_path": ("x_out[i] = (float)((REAL)x_in[i] + (REAL)delta[i]);", "x_out[i] = (float)((REAL)delta[i]);"),
 }
 
+MUTANTS_ATTN = {
+    "attn_no_scale": ("p[u] = s * scale;", "p[u] = s;"),
+    "attn_values_of_later_tokens_leak": ("for (int u = 0; u <= t; ++u) acc += (p[u] / sum) *", "for (int u = 0; u < T; ++u) acc += (p[u < t ? u : t] / sum) *"),
+    "attn_denominator_over_all_tokens": ("for (int u = 0; u <= t; ++u) {\n        p[u] = real_exp(p[u] - m);", "for (int u = 0; u < T; ++u) {\n        p[u] = real_exp(p[u < t ? u : t] - m);"),
+    "attn_kv_head_of_query_head": ("const int g = h / (H / Hkv);", "const int g = h % Hkv;"),
+    "attn_value_rows_are_key_rows": ("qkv[(size_t)u * nout + nq + nkv + (size_t)g * dh + j];", "qkv[(size_t)u * nout + nq + (size_t)g * dh + j];"),
+    "attn_softmax_not_normalised": ("acc += (p[u] / sum) *", "acc += p[u] *"),
+    "attn_out_projection_transposed": ("wo[(size_t)c * nq + j]", "wo[(size_t)j * d + c]"),
+    "attn_query_is_token_zero": ("const REAL* q = qkv + (size_t)t * nout + (size_t)h * dh;", "const REAL* q = qkv + (size_t)h * dh;"),
+}
+
+PIN_CALLS_ATTN = [
+    lambda: chainpins.test_attention_stub_matches_the_tensor_library_attention("f64"),
+    lambda: chainpins.test_attention_stub_special_cases("f64"),
+]
+
 PIN_CALLS_CHAIN = [
     lambda: chainpins.test_rmsnorm_hand_values_and_invariants("f64"),
     lambda: chainpins.test_rmsnorm_eps_sits_inside_the_root_next_to_the_mean("f64"),
@@ -103,10 +119,11 @@ PIN_CALLS = [
 
 
 _GROUPS = ((MUTANTS, lambda: PIN_CALLS), (MUTANTS_FP8, lambda: PIN_CALLS_FP8), (MUTANTS_GATE, lambda: PIN_CALLS_GATE),
-           (MUTANTS_CHAIN, lambda: PIN_CALLS_CHAIN))
+           (MUTANTS_CHAIN, lambda: PIN_CALLS_CHAIN), (MUTANTS_ATTN, lambda: PIN_CALLS_ATTN))
 
 
-@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8) + sorted(MUTANTS_GATE) + sorted(MUTANTS_CHAIN))
+@pytest.mark.parametrize("name", sorted(MUTANTS) + sorted(MUTANTS_FP8) + sorted(MUTANTS_GATE) + sorted(MUTANTS_CHAIN)
+                         + sorted(MUTANTS_ATTN))
 def test_pins_catch_planted_mistake(name, tmp_path, monkeypatch):
     table, get_calls = next((m, c) for m, c in _GROUPS if name in m)
     old, new = table[name]
