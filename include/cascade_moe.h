@@ -49,7 +49,8 @@ int moe_abi_version(void);
 
 /* Geometry of one MoE layer (paper: Table 1 lists the shapes the method was evaluated on).
  * Supported: d % 32 == 0, ffn % 32 == 0, 1 <= top_k <= min(n_experts, 16), n_experts <= 256,
- * 0 <= n_shared <= 8, 1 <= max_tokens <= 16 (T = K+1 tokens in flight, K <= 15). */
+ * 0 <= n_shared <= 8, 1 <= max_tokens <= 16 (T = K+1 tokens in flight, K <= 15); attention stub either absent
+ * (n_heads = n_kv_heads = head_dim = 0) or n_heads % n_kv_heads == 0, head_dim in {32, 64, 96, 128}. */
 typedef struct {
   int32_t d;          /* hidden size                                   */
   int32_t ffn;        /* expert intermediate size                      */
@@ -58,6 +59,9 @@ typedef struct {
   int32_t n_shared;   /* always-on shared experts (same ffn), may be 0 */
   int32_t max_tokens; /* largest T that will be passed                 */
   int32_t gate_mode;  /* MOE_GATE_*: how the picked experts are weighted */
+  int32_t n_heads;    /* attention stub (moe_decoder_stack only): query heads, 0 = no attention workspace */
+  int32_t n_kv_heads; /*   key/value heads, divides n_heads                                              */
+  int32_t head_dim;   /*   multiple of 32, <= 128                                                        */
 } moe_shape;
 
 /* Weighting of a token's top_k picks (the selection itself — top_k largest logits, ties to the lower
@@ -188,6 +192,32 @@ moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32
  * trace_opt: DEVICE [L,T,d] fp32 or NULL; receives x_l, the stream entering block l (trace[0] = x_in).
  * n_unique_per_layer_opt: DEVICE [L] int32 or NULL.  L = 1 is a single block.  Needs d <= 16384. */
 moe_status moe_chained_stack(moe_ctx* ctx, const moe_layer_weights* layers, const uint16_t* const* gammas, int32_t L,
+                             const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
+                             int32_t* n_unique_per_layer_opt, void* stream);
+
+/* Attention stub of a decoder block (moe_decoder_stack).  The paper needs attention only as the share of an
+ * iteration that does not grow with K (Section 2.4); the stub streams the attention block's weights and does
+ * the smallest thing that is still attention: causal grouped-query self-attention among the T in-flight
+ * tokens (no cache of earlier context, no rotation, no biases).  DEVICE pointers, bf16, 16-byte aligned;
+ * wqkv and wo in the TILED layout (moe_pack_matrix); geometry as in the moe_shape of the context. */
+typedef struct {
+  const uint16_t* wqkv;       /* [(H + 2 Hkv) dh, d]: rows of the query heads, then key heads, then value heads */
+  const uint16_t* wo;         /* [d, H dh]                                                                       */
+  const uint16_t* gamma_attn; /* [d] RMSNorm weight in front of the attention half                               */
+  const uint16_t* gamma_moe;  /* [d] RMSNorm weight in front of the MoE half                                     */
+} moe_attn_weights;
+
+/* Re-order one row-major [rows, K] matrix (rows % 16 == 0; K % 32 == 0 for bf16, % 64 for FP8) into the TILED
+ * layout described at MOE_LAYOUT_TILED.  src, dst: DEVICE, same size, not overlapping.  dtype: MOE_WEIGHT_*. */
+moe_status moe_pack_matrix(moe_ctx* ctx, const void* src, void* dst, int64_t rows, int32_t K, int32_t dtype,
+                           void* stream);
+
+/* L decoder blocks back to back, each feeding the next:
+ *   h       = x_l + Wo . Attn( Wqkv . (RMSNorm(x_l) * gamma_attn) )         attention stub, see moe_attn_weights
+ *   x_{l+1} = h   + MoE_l( RMSNorm(h) * gamma_moe )                          as in moe_chained_stack
+ * Arguments as for moe_chained_stack, with attn: HOST array of L structs.  The context must have been created
+ * with the attention geometry in its moe_shape (n_heads > 0). */
+moe_status moe_decoder_stack(moe_ctx* ctx, const moe_layer_weights* layers, const moe_attn_weights* attn, int32_t L,
                              const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
                              int32_t* n_unique_per_layer_opt, void* stream);
 

@@ -19,7 +19,8 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
                 -4: "MOE_ERR_HIP", -5: "MOE_ERR_UNIMPLEMENTED"}
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
-           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_stream_read_probe",
+           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
+           "moe_stream_read_probe",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
            "cascade_next_k", "cascade_observe", "cascade_get_state")
@@ -32,13 +33,18 @@ class MoeError(RuntimeError):
 
 
 class MoeShape(ctypes.Structure):
-    _fields_ = [(n, c_int32) for n in ("d", "ffn", "n_experts", "top_k", "n_shared", "max_tokens", "gate_mode")]
+    _fields_ = [(n, c_int32) for n in ("d", "ffn", "n_experts", "top_k", "n_shared", "max_tokens", "gate_mode",
+                                       "n_heads", "n_kv_heads", "head_dim")]
 
 
 class MoeLayerWeights(ctypes.Structure):
     _fields_ = ([(n, c_void_p) for n in ("router_w", "w1", "w3", "w2", "sw1", "sw3", "sw2")]
                 + [("layout", c_int32), ("dtype", c_int32)]
                 + [(n, c_void_p) for n in ("w1_scale", "w3_scale", "w2_scale", "sw1_scale", "sw3_scale", "sw2_scale")])
+
+
+class MoeAttnWeights(ctypes.Structure):
+    _fields_ = [(n, c_void_p) for n in ("wqkv", "wo", "gamma_attn", "gamma_moe")]
 
 
 MOE_LAYOUT_ROW_MAJOR, MOE_LAYOUT_TILED = 0, 1
@@ -90,6 +96,11 @@ def lib():
     L.moe_chained_stack.restype = ctypes.c_int
     L.moe_chained_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), POINTER(c_void_p), c_int32, c_void_p, c_int32,
                                     ctypes.c_float, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_decoder_stack.restype = ctypes.c_int
+    L.moe_decoder_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), POINTER(MoeAttnWeights), c_int32, c_void_p,
+                                    c_int32, ctypes.c_float, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_pack_matrix.restype = ctypes.c_int
+    L.moe_pack_matrix.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_void_p]
     L.moe_verify_stack.restype = ctypes.c_int
     L.moe_verify_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_int32, c_void_p, c_int32, c_void_p,
                                    c_void_p, c_void_p]
@@ -201,8 +212,9 @@ class LayerWeights:
 class MoeContext:
     """Owns a moe_ctx (device workspace for one layer geometry on the current device)."""
 
-    def __init__(self, d, ffn, n_experts, top_k, n_shared=0, max_tokens=9, gate_mode=MOE_GATE_RENORM_TOPK):
-        self.shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens, gate_mode)
+    def __init__(self, d, ffn, n_experts, top_k, n_shared=0, max_tokens=9, gate_mode=MOE_GATE_RENORM_TOPK,
+                 n_heads=0, n_kv_heads=0, head_dim=0):
+        self.shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens, gate_mode, n_heads, n_kv_heads, head_dim)
         self._h = c_void_p()
         _check(lib().moe_ctx_create(byref(self.shape), byref(self._h)), "moe_ctx_create")
 
@@ -326,6 +338,53 @@ class MoeContext:
         garr = (c_void_p * L)(*[g.data_ptr() for g in gammas])
         _check(lib().moe_chained_stack(self._h, arr, garr, L, _ptr(x_in), T, ctypes.c_float(eps), _ptr(x_out),
                                        _ptr(trace), _ptr(n_unique_per_layer), _stream_ptr(stream)), "moe_chained_stack")
+
+
+    def moe_pack_matrix(self, src, stream=None):
+        """Tiled copy of one row-major 2-D weight matrix (16-bit tensor: bf16; uint8 tensor: FP8 codes)."""
+        import torch
+        if not (isinstance(src, torch.Tensor) and src.is_cuda and src.is_contiguous() and src.dim() == 2):
+            raise ValueError("src: contiguous 2-D CUDA tensor expected")
+        dtype = MOE_WEIGHT_FP8_E4M3 if src.element_size() == 1 else MOE_WEIGHT_BF16
+        dst = torch.empty_like(src)
+        _check(lib().moe_pack_matrix(self._h, _ptr(src), _ptr(dst), src.shape[0], src.shape[1], dtype,
+                                     _stream_ptr(stream)), "moe_pack_matrix")
+        return dst
+
+    def attn_weights(self, A: dict, stream=None) -> "AttnWeights":
+        """Attention stub weights from a dict with row-major wqkv, wo (packed here) and gamma_attn, gamma_moe."""
+        s = self.shape
+        nq, nqkv = s.n_heads * s.head_dim, (s.n_heads + 2 * s.n_kv_heads) * s.head_dim
+        _want_bf16(A["wqkv"], (nqkv, s.d), "wqkv")
+        _want_bf16(A["wo"], (s.d, nq), "wo")
+        _want_bf16(A["gamma_attn"], (s.d,), "gamma_attn")
+        _want_bf16(A["gamma_moe"], (s.d,), "gamma_moe")
+        return AttnWeights(self.moe_pack_matrix(A["wqkv"], stream), self.moe_pack_matrix(A["wo"], stream),
+                           A["gamma_attn"], A["gamma_moe"])
+
+    def moe_decoder_stack(self, layers, attn, x_in, x_out, eps=1e-5, trace=None, n_unique_per_layer=None, stream=None):
+        """L decoder blocks (attention stub + MoE), each feeding the next.  attn: L AttnWeights."""
+        import torch
+        s = self.shape
+        L, T = len(layers), x_in.shape[0]
+        if len(attn) != L:
+            raise ValueError("one set of attention weights per layer")
+        _want(x_in, torch.float32, (T, s.d), "x_in")
+        _want(x_out, torch.float32, (T, s.d), "x_out")
+        _want(trace, torch.float32, (L, T, s.d), "trace")
+        _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
+        arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
+        aarr = (MoeAttnWeights * L)(*[a.c for a in attn])
+        _check(lib().moe_decoder_stack(self._h, arr, aarr, L, _ptr(x_in), T, ctypes.c_float(eps), _ptr(x_out),
+                                       _ptr(trace), _ptr(n_unique_per_layer), _stream_ptr(stream)), "moe_decoder_stack")
+
+
+class AttnWeights:
+    """Device pointers of one block's attention stub (tiled wqkv, wo; norm weights); keeps the tensors alive."""
+
+    def __init__(self, wqkv_tiled, wo_tiled, gamma_attn, gamma_moe):
+        self.tensors = (wqkv_tiled, wo_tiled, gamma_attn, gamma_moe)
+        self.c = MoeAttnWeights(*[t.data_ptr() for t in self.tensors])
 
 
 def moe_stream_read_probe(src, sink, stream=None):

@@ -797,7 +797,8 @@ struct ChainArgs {
   const float* resid_in;   // [T, d]
   float* resid_out;        // [T, d] or NULL
   const uint16_t* gamma;   // [d] bf16 or NULL
-  float* xn_out;           // [T, d], used with gamma
+  float* xn_out;           // [T, d] fp32 normalised output, or NULL
+  uint16_t *xf_hi, *xf_lo; // or: the normalised output as bf16 hi/lo fragments (MFMA B operand), or NULL
   int d, T, top_k, u_max, n_shared, max_tokens, KS;
   float eps;
 };
@@ -851,8 +852,152 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) {
       y.y = (v[q].y / root) * bf16_to_f32(gb.x >> 16);
       y.z = (v[q].z / root) * bf16_to_f32(gb.y & 0xffffu);
       y.w = (v[q].w / root) * bf16_to_f32(gb.y >> 16);
-      *reinterpret_cast<float4*>(g.xn_out + (size_t)t * g.d + (size_t)c4 * 4) = y;
+      if (g.xn_out) *reinterpret_cast<float4*>(g.xn_out + (size_t)t * g.d + (size_t)c4 * 4) = y;
+      if (g.xf_hi) {  // this thread's 4 values are one half of the 8-value fragment unit k8 = c4 / 2
+        uint16_t hi[4], lo[4];
+        split_bf16(y.x, hi[0], lo[0]);
+        split_bf16(y.y, hi[1], lo[1]);
+        split_bf16(y.z, hi[2], lo[2]);
+        split_bf16(y.w, hi[3], lo[3]);
+        const bool packed = g.T <= kPackedTokens;
+        const size_t o = frag_unit(c4 >> 1, t) * 8 + (c4 & 1) * 4;
+        *reinterpret_cast<uint2*>(g.xf_hi + o) =
+            uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+        *reinterpret_cast<uint2*>((packed ? g.xf_hi + kPackedTokens * 8 : g.xf_lo) + o) =
+            uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+      }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention stub.  linear_kernel: out[t, row] = sum_k W[row, k] X[t, k] (+ resid[t, row]) for a tiled bf16
+// matrix and activation fragments — the down projection without slots or slabs: one workgroup per 16-row
+// tile, its 4 waves split K, LDS reduce, wave 0 writes.  grid = rows / 16.
+// ------------------------------------------------------------------------------------------
+struct LinearArgs {
+  const uint16_t* w;             // [rows, K] tiled
+  const uint16_t *xf_hi, *xf_lo; // fragments of X, K*16 elements each
+  const float* resid;            // [T, rows] or NULL
+  float* out;                    // [T, rows]
+  int rows, K, T;
+};
+
+template <bool PK>
+__global__ __launch_bounds__(256) void linear_kernel(LinearArgs g) {
+  constexpr int W = 4, P = 6;
+  __shared__ float4 red[W * 64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int nsteps = g.K >> 5, chunk = (nsteps + W - 1) / W;
+  const int nst = max(0, min(chunk, nsteps - wave * chunk));
+  const int s_beg = min(wave * chunk, nsteps - 1);
+  const char* base = reinterpret_cast<const char*>(g.w) + (size_t)blockIdx.x * nsteps * 1024 + (size_t)s_beg * 1024;
+  const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * 1024;
+  const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * 1024;
+  const uint32_t off = lane * 16;
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  pipeline<1, 1, PK, P>(
+      nst,
+      [&](Stage<1, 1, PK>& st, int s) {
+        st.a[0] = ld128<true>(base, off + (uint32_t)s * 1024);
+        st.bh[0] = ld128<false>(XH, off + (uint32_t)s * 1024);
+        if constexpr (!PK) st.bl[0] = ld128<false>(XL, off + (uint32_t)s * 1024);
+      },
+      [&](const Stage<1, 1, PK>& st) {
+        acc = mfma_bf16(st.a[0], st.bh[0], acc);
+        if constexpr (!PK) acc = mfma_bf16(st.a[0], st.bl[0], acc);
+      });
+  red[wave * 64 + lane] = float4{acc[0], acc[1], acc[2], acc[3]};
+  __syncthreads();
+  if (wave != 0) return;
+  float4 y = red[lane];
+  for (int w = 1; w < W; ++w) {
+    const float4 y2 = red[w * 64 + lane];
+    y.x += y2.x, y.y += y2.y, y.z += y2.z, y.w += y2.w;
+  }
+  if constexpr (PK)
+    y.x += __shfl_xor(y.x, 8), y.y += __shfl_xor(y.y, 8), y.z += __shfl_xor(y.z, 8), y.w += __shfl_xor(y.w, 8);
+  if (r < g.T && (!PK || r < kPackedTokens)) {
+    const size_t o = (size_t)r * g.rows + (size_t)blockIdx.x * 16 + kg * 4;  // the lane's 4 rows are consecutive
+    if (g.resid) {
+      const float4 x = *reinterpret_cast<const float4*>(g.resid + o);
+      y.x += x.x, y.y += x.y, y.z += x.z, y.w += x.w;
+    }
+    *reinterpret_cast<float4*>(g.out + o) = y;
+  }
+}
+
+// Attention core of the stub: one workgroup per query head.  q, k, v of its (kv) head for the T in-flight tokens
+// sit in LDS; scores, the causal softmax and the weighted sum of values are plain fp32 loops in index order
+// (T <= 16, head_dim <= 128: a few thousand multiply-adds per head).  The head's output goes out as bf16 hi/lo
+// fragments, the B operand of the output projection.
+struct AttnArgs {
+  const float* qkv;               // [T, (H + 2 Hkv) dh]
+  uint16_t *of_hi, *of_lo;        // fragments of concat_h(o), H*dh*16 elements each
+  int T, H, Hkv, dh;
+};
+
+__global__ __launch_bounds__(256) void attn_core_kernel(AttnArgs g) {
+  __shared__ float s_q[kMaxTokens * 128], s_k[kMaxTokens * 128], s_v[kMaxTokens * 128];
+  __shared__ float s_p[kMaxTokens * kMaxTokens];
+  const int h = blockIdx.x, tid = threadIdx.x, T = g.T, dh = g.dh;
+  const int kvh = h / (g.H / g.Hkv), nq = g.H * dh, nkv = g.Hkv * dh, nout = nq + 2 * nkv;
+  for (int i = tid; i < T * dh; i += 256) {
+    const int t = i / dh, j = i - t * dh;
+    const float* row = g.qkv + (size_t)t * nout;
+    s_q[i] = row[h * dh + j];
+    s_k[i] = row[nq + kvh * dh + j];
+    s_v[i] = row[nq + nkv + kvh * dh + j];
+  }
+  __syncthreads();
+  const float scale = 1.f / sqrtf((float)dh);
+  for (int i = tid; i < T * T; i += 256) {
+    const int t = i / T, u = i - t * T;
+    if (u <= t) {
+      float s = 0.f;
+      for (int j = 0; j < dh; ++j) s += s_q[t * dh + j] * s_k[u * dh + j];
+      s_p[t * kMaxTokens + u] = s * scale;
+    }
+  }
+  __syncthreads();
+  if (tid < T) {  // row tid: max, exponentials, sum in index order, normalise
+    float* p = s_p + tid * kMaxTokens;
+    float m = p[0];
+    for (int u = 1; u <= tid; ++u) m = fmaxf(m, p[u]);
+    float sum = 0.f;
+    for (int u = 0; u <= tid; ++u) {
+      p[u] = expf(p[u] - m);
+      sum += p[u];
+    }
+    for (int u = 0; u <= tid; ++u) p[u] = p[u] / sum;
+  }
+  __syncthreads();
+  const bool packed = T <= kPackedTokens;
+  for (int i = tid; i < T * (dh >> 3); i += 256) {  // (token, unit of 8 output dims)
+    const int t = i / (dh >> 3), j0 = (i - t * (dh >> 3)) * 8;
+    float o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = 0.f;
+    for (int u = 0; u <= t; ++u) {
+      const float pu = s_p[t * kMaxTokens + u];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] += pu * s_v[u * dh + j0 + j];
+    }
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint16_t h0, l0, h1, l1;
+      split_bf16(o[2 * j], h0, l0);
+      split_bf16(o[2 * j + 1], h1, l1);
+      hi[j] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      lo[j] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    const size_t q = frag_unit((h * dh + j0) >> 3, t);
+    reinterpret_cast<uint4*>(g.of_hi)[q] = uint4{hi[0], hi[1], hi[2], hi[3]};
+    if (packed)
+      reinterpret_cast<uint4*>(g.of_hi)[q + kPackedTokens] = uint4{lo[0], lo[1], lo[2], lo[3]};
+    else
+      reinterpret_cast<uint4*>(g.of_lo)[q] = uint4{lo[0], lo[1], lo[2], lo[3]};
   }
 }
 
@@ -931,6 +1076,8 @@ struct moe_ctx {
   int32_t *ids, *n_unique, *slot_expert, *tok_slot;
   float *gates, *slot_gate, *partial;
   float *xn, *resid[2];  // chained stack: normalised router input and the residual stream (ping-pong), [max_tokens, d]
+  float *hbuf, *qkv;     // decoder stack: stream after the attention half [max_tokens, d]; q|k|v [max_tokens, (H+2Hkv) dh]
+  uint16_t *af_hi, *af_lo;  // decoder stack: fragments of the attention output, H*dh*16 elements each
   bool profiling;
   std::vector<hipEvent_t> events;  // kProfMarks per profiled layer-step
 };
@@ -1152,6 +1299,12 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
     return MOE_ERR_INVALID_ARG;
   if (s.top_k > s.n_experts) return MOE_ERR_INVALID_ARG;
   if (s.gate_mode != MOE_GATE_RENORM_TOPK && s.gate_mode != MOE_GATE_SOFTMAX_ALL) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads < 0 || s.n_kv_heads < 0 || s.head_dim < 0) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads == 0 && (s.n_kv_heads != 0 || s.head_dim != 0)) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads > 0) {
+    if (s.n_kv_heads < 1 || s.n_heads % s.n_kv_heads) return MOE_ERR_INVALID_ARG;
+    if (s.head_dim < 32 || s.head_dim > 128 || s.head_dim % 32 || s.n_heads > 1024) return MOE_ERR_UNSUPPORTED_SHAPE;
+  }
   if (s.d % 32 || s.ffn % 32 || s.n_experts > kMaxExperts || s.top_k > kMaxTopK || s.n_shared > kMaxShared ||
       s.max_tokens > kMaxTokens || (int64_t)s.d * s.ffn > (int64_t)1 << 30)
     return MOE_ERR_UNSUPPORTED_SHAPE;
@@ -1198,6 +1351,9 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
   const size_t o_xn = carve((size_t)s.max_tokens * s.d * 4);
   const size_t o_r0 = carve((size_t)s.max_tokens * s.d * 4), o_r1 = carve((size_t)s.max_tokens * s.d * 4);
+  const size_t nq = (size_t)s.n_heads * s.head_dim, nqkv = nq + 2 * (size_t)s.n_kv_heads * s.head_dim;
+  const size_t o_hb = carve((size_t)s.max_tokens * s.d * 4), o_qkv = carve((size_t)s.max_tokens * nqkv * 4 + 16);
+  const size_t o_ah = carve(nq * kGateCols * 2 + 16), o_al = carve(nq * kGateCols * 2 + 16);
   c->ws_bytes = off;
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
@@ -1218,6 +1374,10 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->xn = reinterpret_cast<float*>(c->ws + o_xn);
   c->resid[0] = reinterpret_cast<float*>(c->ws + o_r0);
   c->resid[1] = reinterpret_cast<float*>(c->ws + o_r1);
+  c->hbuf = reinterpret_cast<float*>(c->ws + o_hb);
+  c->qkv = reinterpret_cast<float*>(c->ws + o_qkv);
+  c->af_hi = reinterpret_cast<uint16_t*>(c->ws + o_ah);
+  c->af_lo = reinterpret_cast<uint16_t*>(c->ws + o_al);
   if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
     delete c;
@@ -1327,6 +1487,91 @@ moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const 
     if (l > 0 || dst || a.gamma) hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, a);
     if (dst) cur = dst;
     if (l == L) break;
+    if (moe_status rc = launch_layer(c, layers + l, c->xn, T, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks))
+      return rc;
+  }
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status moe_pack_matrix(moe_ctx* c, const void* src, void* dst, int64_t rows, int32_t K, int32_t dtype,
+                           void* stream) {
+  if (!c || !src || !dst || rows < 16 || rows % 16 || K < 32 || !aligned16(src) || !aligned16(dst)) return MOE_ERR_INVALID_ARG;
+  if (dtype != MOE_WEIGHT_BF16 && dtype != MOE_WEIGHT_FP8_E4M3) return MOE_ERR_INVALID_ARG;
+  const bool fp8 = dtype == MOE_WEIGHT_FP8_E4M3;
+  if (K % (fp8 ? 64 : 32) || rows * (int64_t)K > (int64_t)1 << 34) return MOE_ERR_INVALID_ARG;
+  if (moe_status st = check_stream_device(c)) return st;
+  const size_t units = (size_t)rows * (size_t)(K / (fp8 ? 16 : 8));
+  const unsigned blocks = (unsigned)((units + 255) / 256 < 65536 ? (units + 255) / 256 : 65536);
+  if (fp8)
+    hipLaunchKernelGGL(pack_kernel_fp8, dim3(blocks), dim3(256), 0, (hipStream_t)stream, static_cast<const uint2*>(src),
+                       static_cast<uint4*>(dst), (size_t)rows, K);
+  else
+    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), (size_t)rows, K);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status moe_decoder_stack(moe_ctx* c, const moe_layer_weights* layers, const moe_attn_weights* attn, int32_t L,
+                             const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
+                             int32_t* n_unique_per_layer_opt, void* stream) {
+  if (!c || !layers || !attn || L < 1 || !x_in || !x_out || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
+  if (!(eps >= 0.f) || !aligned16(x_in) || !aligned16(x_out) || (trace_opt && !aligned16(trace_opt)))
+    return MOE_ERR_INVALID_ARG;
+  const moe_shape& s = c->s;
+  if (s.n_heads < 1) return MOE_ERR_INVALID_ARG;  // the context was created without the attention geometry
+  if (s.d > 4 * kChainVecs * kChainThreads) return MOE_ERR_UNSUPPORTED_SHAPE;
+  for (int l = 0; l < L; ++l) {
+    if (!weights_ok(c, layers + l)) return MOE_ERR_INVALID_ARG;
+    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
+    const moe_attn_weights& a = attn[l];
+    if (!a.wqkv || !a.wo || !a.gamma_attn || !a.gamma_moe) return MOE_ERR_INVALID_ARG;
+    if (!aligned16(a.wqkv) || !aligned16(a.wo) || !aligned16(a.gamma_attn) || !aligned16(a.gamma_moe))
+      return MOE_ERR_INVALID_ARG;
+  }
+  if (moe_status st = check_stream_device(c)) return st;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t per = (size_t)T * s.d;
+  const int nq = s.n_heads * s.head_dim, nqkv = nq + 2 * s.n_kv_heads * s.head_dim;
+  const bool pk = T <= kPackedTokens;
+  auto linear = [&](const LinearArgs& a) {
+    if (pk) hipLaunchKernelGGL(linear_kernel<true>, dim3(a.rows / 16), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(linear_kernel<false>, dim3(a.rows / 16), dim3(256), 0, st, a);
+  };
+  ChainArgs base{};
+  base.tok_slot = c->tok_slot;
+  base.d = s.d, base.T = T, base.top_k = s.top_k, base.u_max = c->u_max, base.n_shared = s.n_shared;
+  base.max_tokens = s.max_tokens, base.eps = eps;
+  const float* cur = x_in;  // the stream the pending MoE term (if any) is added to
+  int ks = 1;
+  for (int l = 0; l <= L; ++l) {
+    // x_l = (stream after the previous attention half) + (previous MoE term); normalise for this block's attention
+    ChainArgs a = base;
+    a.partial = l > 0 ? c->partial : nullptr;
+    a.KS = ks;
+    a.resid_in = cur;
+    float* dst = l == L ? x_out : (trace_opt ? trace_opt + (size_t)l * per : (l > 0 ? c->resid[l & 1] : nullptr));
+    a.resid_out = dst;
+    if (l < L) {
+      a.gamma = attn[l].gamma_attn;
+      a.xf_hi = c->xf_hi, a.xf_lo = c->xf_lo;
+    }
+    if (l > 0 || dst || a.gamma) hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, a);
+    if (dst) cur = dst;
+    if (l == L) break;
+    // attention half: q|k|v projection, core, output projection + residual -> h
+    linear(LinearArgs{attn[l].wqkv, c->xf_hi, c->xf_lo, nullptr, c->qkv, nqkv, s.d, T});
+    hipLaunchKernelGGL(attn_core_kernel, dim3(s.n_heads), dim3(256), 0, st,
+                       AttnArgs{c->qkv, c->af_hi, c->af_lo, T, s.n_heads, s.n_kv_heads, s.head_dim});
+    linear(LinearArgs{attn[l].wo, c->af_hi, c->af_lo, cur, c->hbuf, s.d, nq, T});
+    // MoE half on RMSNorm(h)
+    ChainArgs m = base;
+    m.KS = 1;
+    m.resid_in = c->hbuf;
+    m.gamma = attn[l].gamma_moe;
+    m.xn_out = c->xn;
+    hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, m);
+    cur = c->hbuf;
     if (moe_status rc = launch_layer(c, layers + l, c->xn, T, nullptr, nullptr, nullptr, nullptr, nullptr,
                                      n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks))
       return rc;

@@ -27,7 +27,7 @@ from . import binding, synth
 
 # Measured on MI355X, rho = 0.5.  *-layer: `python bench.py [--weights fp8]`, by_K latency_us of one
 # Mixtral-shaped layer-step.  *-stack32: `python -m paper_2506_20675_amd.stack_driver --iters 600 --layers 32
-# --static 0,1,2,3 [--weights fp8 | --chained]`, median ms per iteration (K = 0..3 from the static runs, K = 4, 5
+# --static 0,1,2,3 [--weights fp8 | --chained | --decoder]`, median ms per iteration (K = 0..3 from the static runs, K = 4, 5
 # from the controller run where it chose them).
 MEASURED = {
     "mixtral-bf16-layer": [122.7, 186.6, 226.8, 237.5, 240.7, 289.8, 288.1, 318.2, 299.2],
@@ -35,6 +35,7 @@ MEASURED = {
     "mixtral-bf16-stack32": [3.93, 5.87, 7.17, 8.03, 8.68, 9.11],
     "mixtral-fp8-stack32": [2.46, 3.42, 4.15, 4.60, 4.89],
     "mixtral-bf16-stack32-chained": [3.97, 6.54, 8.53, 9.97],
+    "mixtral-bf16-stack32-decoder": [4.81, 6.90, 8.23, 9.36],     # --decoder: attention stub + MoE per block
 }
 
 

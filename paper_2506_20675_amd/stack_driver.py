@@ -61,10 +61,11 @@ def build_stack(cfg, layers, ctx, layout="tiled", first_layer=0, weights="bf16")
 
 
 def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_field=0, params=None,
-        static_k=None, log=None, ctx=None, stack=None, pool=None, gammas=None):
+        static_k=None, log=None, ctx=None, stack=None, pool=None, gammas=None, attn=None):
     """Runs the loop; static_k = None uses the controller, an int forces that K every iteration.
     gammas (one RMSNorm weight tensor per layer) switches to the chained stack: the layers feed each other
-    through pre-norm residual blocks and only layer 0's pooled input is used.
+    through pre-norm residual blocks and only layer 0's pooled input is used.  attn (one AttnWeights per layer)
+    adds the attention stub in front of every MoE block (moe_decoder_stack; the context must carry the geometry).
     Returns (summary dict, per-iteration records)."""
     import torch
     own = ctx is None
@@ -84,7 +85,9 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
     chain_out = torch.empty((synth.K_MAX + 1, cfg.d), dtype=torch.float32, device="cuda")
 
     def step(hid, o, T):
-        if gammas is None:
+        if attn is not None:
+            ctx.moe_decoder_stack(stack, attn, hid[0], chain_out[:T], 1e-5, None, nu)
+        elif gammas is None:
             ctx.moe_verify_stack(stack, hid, o, nu)
         else:
             ctx.moe_chained_stack(stack, gammas, hid[0], chain_out[:T], 1e-5, None, nu)
@@ -121,7 +124,7 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
         by_k.setdefault(r["K"], []).append(r["t_verify_ms"])
     summary = {
         "policy": "cascade" if static_k is None else f"static K={static_k}", "layers": layers, "iters": iters,
-        "chained": gammas is not None,
+        "chained": gammas is not None or attn is not None, "attention_stub": attn is not None,
         "rho": rho, "layout": layout, "tokens": tok, "t_verify_total_ms": round(tv, 3),
         "tpot_ms": round(tv / tok, 4), "etr": round(tok / iters, 4),
         "K_histogram": {str(k): len(v) for k, v in sorted(by_k.items())},
@@ -149,22 +152,35 @@ def main(argv=None):
     ap.add_argument("--static", type=str, default="", help="comma list of static K baselines to run too, e.g. 0,1,2,3")
     ap.add_argument("--log", default=None)
     ap.add_argument("--weights", choices=("bf16", "fp8"), default="bf16")
+    ap.add_argument("--decoder", action="store_true",
+                    help="full decoder blocks: attention stub + MoE, each feeding the next (moe_decoder_stack)")
     ap.add_argument("--chained", action="store_true",
                     help="pre-norm residual blocks feeding each other (moe_chained_stack) instead of independent inputs")
     a = ap.parse_args(argv)
     cfg = synth.CONFIGS[a.config]
-    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode)
+    H, Hkv, dh = synth.attn_geometry(cfg) if a.decoder else (0, 0, 0)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode,
+                             H, Hkv, dh)
     stack = build_stack(cfg, a.layers, ctx, a.layout, weights=a.weights)
     pool = HiddenPool(cfg, a.layers, a.rho)
     gammas = None
     if a.chained:
         import torch
         gammas = [torch.from_numpy(synth.norm_gamma_host(cfg, l).view(np.int16)).cuda() for l in range(a.layers)]
+    attn = None
+    if a.decoder:
+        import torch
+        attn = []
+        for l in range(a.layers):
+            A = synth.attn_weights_host(cfg, l)
+            attn.append(ctx.attn_weights({k: torch.from_numpy(v.view(np.int16)).cuda() for k, v in A.items()
+                                          if isinstance(v, np.ndarray)}))
+        torch.cuda.synchronize()
     res = {"cascade": run(cfg, a.layers, a.iters, a.rho, a.layout, log=a.log, ctx=ctx, stack=stack, pool=pool,
-                          gammas=gammas)[0]}
+                          gammas=gammas, attn=attn)[0]}
     for k in [int(v) for v in a.static.split(",") if v != ""]:
         res[f"static_{k}"] = run(cfg, a.layers, a.iters, a.rho, a.layout, static_k=k, ctx=ctx, stack=stack,
-                                 pool=pool, gammas=gammas)[0]
+                                 pool=pool, gammas=gammas, attn=attn)[0]
     base = res.get("static_0")
     if base:
         for v in res.values():

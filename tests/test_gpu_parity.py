@@ -715,3 +715,109 @@ def test_degenerate_routings_identical_tokens_and_largest_supported_shape():
     assert ctx.workspace_bytes > 0
     _check_layer((d, ffn, E, k, 0), Wb, xb, ctx, _weights_dev(Wb))
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# Decoder stack: attention stub + MoE per block
+# ------------------------------------------------------------------------------------------
+def _attn_dev(ctx, A):
+    return ctx.attn_weights({k: _dev(v) for k, v in A.items() if isinstance(v, np.ndarray)})
+
+
+def _decoder_block_check(ctx, lw, aw, W, A, x, k, ns, eps=1e-5):
+    """One block, teacher-forced on the oracle's input stream."""
+    import torch
+    T, d = x.shape
+    xo = torch.full((T, d), float("nan"), dtype=torch.float32, device="cuda")
+    nu = torch.full((1,), -3, dtype=torch.int32, device="cuda")
+    ctx.moe_decoder_stack([lw], [aw], _dev(x), xo, eps, None, nu)
+    torch.cuda.synchronize()
+    gm = ctx.shape.gate_mode
+    r32, h32, ids, _ = orc.decoder_block(x, A, W, k, ns, eps, "f32", gm)
+    r64, h64, ids64, _ = orc.decoder_block(x, A, W, k, ns, eps, "f64", gm)
+    n64 = orc.rmsnorm(h64, A["gamma_moe"], eps, "f64")
+    assert _routing_margin_ok(n64, W["router_w"], k, ctx.shape.n_experts), "seed produces a routing near-tie; pick another"
+    np.testing.assert_array_equal(ids, ids64)
+    assert int(nu.item()) == orc.union(ids64, ctx.shape.n_experts)["n_unique"]
+    got = xo.cpu().numpy().astype(np.float64)
+    _check_out((got - x).astype(np.float32), (r32.astype(np.float64) - x).astype(np.float32), r64.astype(np.float64) - x)
+    return r64
+
+
+@pytest.mark.parametrize("T", [1, 4, 9])
+def test_decoder_block_parity_tiny(T):
+    cfg = synth.TINY
+    H, Hkv, dh = synth.attn_geometry(cfg)
+    W = synth.layer_weights_host(cfg, 8)
+    A = synth.attn_weights_host(cfg, 8)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9, n_heads=H, n_kv_heads=Hkv, head_dim=dh)
+    Wd = _weights_dev(W)
+    x = (synth.hidden_host(cfg, 8, 80 + T, T, 0.5) * np.float32(2.0)).astype(np.float32)
+    _decoder_block_check(ctx, _tiled(ctx, Wd), _attn_dev(ctx, A), W, A, x, cfg.top_k, 0)
+    ctx.close()
+
+
+def test_decoder_block_parity_other_geometries():
+    """Several kv heads, head dims 32 and 96, T = 16, shared experts, FP8 experts."""
+    rng = np.random.default_rng(91)
+    bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+    for (d, ffn, E, k, ns, T, H, Hkv, dh, fp8) in ((192, 128, 6, 2, 1, 16, 6, 3, 32, False), (384, 192, 5, 3, 0, 7, 4, 2, 96, True)):
+        A = dict(wqkv=bf(rng.normal(0, 0.08, ((H + 2 * Hkv) * dh, d))), wo=bf(rng.normal(0, 0.08, (d, H * dh))),
+                 gamma_attn=bf(1 + 0.1 * rng.normal(size=d)), gamma_moe=bf(1 + 0.1 * rng.normal(size=d)),
+                 n_heads=H, n_kv_heads=Hkv, head_dim=dh)
+        if fp8:
+            finite = np.array([c for c in range(256) if c not in (0x7F, 0xFF)], dtype=np.uint8)
+            W = dict(router_w=bf(rng.normal(0, 0.3, (E, d))))
+            for q, s, shp in (("q1", "s1", (E, ffn, d)), ("q3", "s3", (E, ffn, d)), ("q2", "s2", (E, d, ffn))):
+                W[q] = rng.choice(finite, shp)
+                W[s] = (1e-4 * 10.0 ** rng.uniform(-0.5, 0.5, shp[:2])).astype(np.float32)
+        else:
+            W = dict(router_w=bf(rng.normal(0, 0.3, (E, d))), w1=bf(rng.normal(0, 0.1, (E, ffn, d))),
+                     w3=bf(rng.normal(0, 0.1, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))),
+                     sw1=bf(rng.normal(0, 0.1, (ns, ffn, d))), sw3=bf(rng.normal(0, 0.1, (ns, ffn, d))),
+                     sw2=bf(rng.normal(0, 0.1, (ns, d, ffn))))
+        x = rng.normal(size=(T, d)).astype(np.float32)
+        ctx = binding.MoeContext(d, ffn, E, k, ns, 16, n_heads=H, n_kv_heads=Hkv, head_dim=dh)
+        Wd = _weights_dev(W)
+        _decoder_block_check(ctx, _tiled(ctx, Wd), _attn_dev(ctx, A), W, A, x, k, ns)
+        ctx.close()
+
+
+def test_decoder_stack_teacher_forced_and_free_running():
+    import torch
+    cfg = synth.TINY
+    H, Hkv, dh = synth.attn_geometry(cfg)
+    L, T = 3, 4
+    Ws = [synth.layer_weights_host(cfg, 50 + l) for l in range(L)]
+    As = [synth.attn_weights_host(cfg, 50 + l) for l in range(L)]
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9, n_heads=H, n_kv_heads=Hkv, head_dim=dh)
+    Wds = [_weights_dev(W) for W in Ws]
+    lws = [ctx.moe_pack_weights(ctx.weights(w)) for w in Wds]
+    aws = [_attn_dev(ctx, A) for A in As]
+    x0 = synth.hidden_host(cfg, 50, 0, T, 0.5)
+    xL, trace, ids = orc.decoder_stack(x0, As, Ws, cfg.top_k, 0, 1e-5, "f64")
+    for l in range(L):
+        nxt = _decoder_block_check(ctx, lws[l], aws[l], Ws[l], As[l], trace[l], cfg.top_k, 0)
+        np.testing.assert_array_equal(nxt, trace[l + 1] if l + 1 < L else xL)
+    out = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+    tr = torch.zeros((L, T, cfg.d), dtype=torch.float32, device="cuda")
+    nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+    ctx.moe_decoder_stack(lws, aws, _dev(x0), out, 1e-5, tr, nu)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(tr[0].cpu().numpy(), x0)
+    for l in range(L):
+        assert int(nu[l].item()) == orc.union(ids[l], cfg.n_experts)["n_unique"]
+        e = tr[l].cpu().numpy().astype(np.float64) - trace[l]
+        assert np.sqrt((e ** 2).sum() / (trace[l].astype(np.float64) ** 2).sum()) <= 1e-4
+    e = out.cpu().numpy().astype(np.float64) - xL
+    assert np.sqrt((e ** 2).sum() / (xL.astype(np.float64) ** 2).sum()) <= 1e-4
+    out2 = _dev(x0).clone()
+    ctx.moe_decoder_stack(lws, aws, out2, out2, 1e-5)                # no trace, in place: same bits
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out2.cpu().numpy(), out.cpu().numpy())
+    plain = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    with pytest.raises(binding.MoeError) as err:                     # a context without the attention geometry refuses
+        plain.moe_decoder_stack(lws[:1], aws[:1], out2, out2)
+    assert err.value.status == -1
+    plain.close()
+    ctx.close()
