@@ -1,0 +1,347 @@
+// Steps 3 to 5: gate/up projection with SiLU*mul, split-K down projection, slab sum; and the one-off re-layout
+// kernels of the tiled weight format.  Part of the single translation unit moe_kernels.hip.
+#pragma once
+#include "moe_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Step 3: gate/up projections + SiLU*mul for every unique expert (and shared expert).
+// grid = (row blocks of 16*R rows of ffn, min(E, T*top_k) + n_shared slots); block = W waves that split d.
+// ------------------------------------------------------------------------------------------
+struct GateupArgs {
+  const void *w1, *w3, *sw1, *sw3;      // [E,ffn,d] / [n_shared,ffn,d], bf16 or FP8 codes
+  const float *s1, *s3, *ss1, *ss3;     // FP8 only: per-row scales [E,ffn] / [n_shared,ffn]
+  const uint16_t *xf_hi, *xf_lo;        // activation fragments, d*16 elements each
+  const int32_t* n_unique;              // [1]        size of the union                   } written by the
+  const int32_t* slot_expert;           // [u_max]    expert of slot u (ascending)        } grouping step
+  const float* slot_gate;               // [u_max+n_shared, 16] gate of token column n, 0 = not routed
+  uint16_t *hf_hi, *hf_lo;              // [u_max + n_shared] fragments of gate*silu(G)*U, ffn*16 elements each
+  int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
+};
+
+template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
+__global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
+  constexpr int NB = FP8 ? 2 : 1;
+  __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const char *W1, *W3;
+  const float *S1 = nullptr, *S3 = nullptr;  // FP8: scale rows of this expert
+  const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
+  float gate;
+  int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
+  if (slot < g.routed_slots) {
+    // three independent loads (one round trip); the tables are in bounds for every slot of the grid
+    const int nu = *g.n_unique;
+    const int e = g.slot_expert[slot];
+    gate = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)];
+    if (slot >= nu) return;  // beyond the union of this step
+    W1 = reinterpret_cast<const char*>(g.w1) + e * per;
+    W3 = reinterpret_cast<const char*>(g.w3) + e * per;
+    if constexpr (FP8) {
+      S1 = g.s1 + (size_t)e * g.ffn;
+      S3 = g.s3 + (size_t)e * g.ffn;
+    }
+  } else {
+    gate = 1.f;  // shared expert: every token, gate 1
+    const int sh = slot - g.routed_slots;
+    W1 = reinterpret_cast<const char*>(g.sw1) + sh * per;
+    W3 = reinterpret_cast<const char*>(g.sw3) + sh * per;
+    if constexpr (FP8) {
+      S1 = g.ss1 + (size_t)sh * g.ffn;
+      S3 = g.ss3 + (size_t)sh * g.ffn;
+    }
+    slot = g.u_max + sh;  // buffers keep shared experts after the largest union
+  }
+  const int ntiles = g.ffn >> 4, tile0 = blockIdx.x * R;
+  const int nsteps = g.d >> (FP8 ? 6 : 5), chunk = (nsteps + W - 1) / W;
+  const int nst = max(0, min(chunk, nsteps - wave * chunk));
+  const int s_beg = min(wave * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
+
+  const WeightAddr<TILED, FP8> wa(g.d, r, kg, lane);
+  const char* base[2 * R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    const size_t t = (size_t)min(tile0 + j, ntiles - 1);  // ragged last block: re-read a valid tile, result unused
+    base[j] = W1 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
+    base[R + j] = W3 + t * wa.tile_stride + (size_t)s_beg * wa.step_stride;
+  }
+  const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * (1024 * NB);
+  const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * (1024 * NB);
+  const uint32_t b_off = lane * 16;
+
+  f32x4 acc[2 * R];
+#pragma unroll
+  for (int j = 0; j < 2 * R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  pipeline<2 * R, NB, PK, P>(
+      nst,
+      [&](Stage<2 * R, NB, PK>& st, int s) {
+#pragma unroll
+        for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          st.bh[b] = ld128<false>(XH, b_off + (uint32_t)(s * NB + b) * 1024);
+          if constexpr (!PK) st.bl[b] = ld128<false>(XL, b_off + (uint32_t)(s * NB + b) * 1024);
+        }
+      },
+      [&](const Stage<2 * R, NB, PK>& st) {
+        if constexpr (FP8) {
+#pragma unroll
+          for (int j = 0; j < 2 * R; ++j) {
+            uint4 k0, k1;
+            fp8x16_to_bf16(st.a[j], k0, k1);
+            acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+          if constexpr (!PK) {
+#pragma unroll
+            for (int j = 0; j < 2 * R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+          }
+        }
+      });
+
+  // reduce the W k-slices through LDS, then wave w finishes tiles w, w+W, ...
+  if constexpr (W > 1) {
+#pragma unroll
+    for (int j = 0; j < 2 * R; ++j)
+      red[(wave * 2 * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    __syncthreads();
+  }
+  uint16_t* HH = g.hf_hi + (size_t)slot * g.ffn * 16;
+  uint16_t* HL = g.hf_lo + (size_t)slot * g.ffn * 16;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j % W != wave || tile0 + j >= ntiles) continue;
+    float4 G, U;
+    if constexpr (W > 1) {
+      G = red[j * 64 + lane];
+      U = red[(R + j) * 64 + lane];
+      for (int w = 1; w < W; ++w) {
+        const float4 g2 = red[(w * 2 * R + j) * 64 + lane], u2 = red[(w * 2 * R + R + j) * 64 + lane];
+        G.x += g2.x, G.y += g2.y, G.z += g2.z, G.w += g2.w;
+        U.x += u2.x, U.y += u2.y, U.z += u2.z, U.w += u2.w;
+      }
+    } else {
+      G = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+      U = float4{acc[R + j][0], acc[R + j][1], acc[R + j][2], acc[R + j][3]};
+    }
+    if constexpr (PK) {  // column n + 8 carries the lo-half contribution of token n: fold it in
+      G.x += __shfl_xor(G.x, 8), G.y += __shfl_xor(G.y, 8), G.z += __shfl_xor(G.z, 8), G.w += __shfl_xor(G.w, 8);
+      U.x += __shfl_xor(U.x, 8), U.y += __shfl_xor(U.y, 8), U.z += __shfl_xor(U.z, 8), U.w += __shfl_xor(U.w, 8);
+    }
+    if constexpr (FP8) {  // the lane's four rows of the tile are consecutive: one 16-byte load per scale vector
+      const float4 c1 = *reinterpret_cast<const float4*>(S1 + (tile0 + j) * 16 + kg * 4);
+      const float4 c3 = *reinterpret_cast<const float4*>(S3 + (tile0 + j) * 16 + kg * 4);
+      G.x *= c1.x, G.y *= c1.y, G.z *= c1.z, G.w *= c1.w;
+      U.x *= c3.x, U.y *= c3.y, U.z *= c3.z, U.w *= c3.w;
+    }
+    if (r < g.T && (!PK || r < kPackedTokens) && gate != 0.f) {
+      // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r: four consecutive k of the
+      // down projection, i.e. one half of a 16-byte fragment unit
+      uint16_t hi[4], lo[4];
+      split_bf16(gate * (G.x / (1.f + expf(-G.x))) * U.x, hi[0], lo[0]);
+      split_bf16(gate * (G.y / (1.f + expf(-G.y))) * U.y, hi[1], lo[1]);
+      split_bf16(gate * (G.z / (1.f + expf(-G.z))) * U.z, hi[2], lo[2]);
+      split_bf16(gate * (G.w / (1.f + expf(-G.w))) * U.w, hi[3], lo[3]);
+      const int k = (tile0 + j) * 16 + kg * 4;
+      const size_t o = frag_unit(k >> 3, r) * 8 + (k & 4);
+      *reinterpret_cast<uint2*>(HH + o) =
+          uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+      *reinterpret_cast<uint2*>((PK ? HH + kPackedTokens * 8 : HL) + o) =
+          uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Step 4: down projection, split-K over (expert, k-chunk).  The gate is already folded into H, so
+// every slab is a plain partial sum of out.
+// grid = (row blocks of 16*R rows of d, min(E, T*top_k) + n_shared slots, KS k-chunks); block = W waves
+// splitting the chunk.
+// ------------------------------------------------------------------------------------------
+struct DownArgs {
+  const void *w2, *sw2;           // [E,d,ffn] / [n_shared,d,ffn], bf16 or FP8 codes
+  const float *s2, *ss2;          // FP8 only: per-row scales [E,d] / [n_shared,d]
+  const uint16_t *hf_hi, *hf_lo;  // [u_max + n_shared] fragments, ffn*16 elements each
+  const int32_t* n_unique;
+  const int32_t* slot_expert;
+  const float* slot_gate;
+  float* partial;                 // [(u_max + n_shared)*KS, max_tokens, d]
+  int d, ffn, T, routed_slots, u_max, max_tokens, KS;
+};
+
+template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
+__global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
+  constexpr int NB = FP8 ? 2 : 1;
+  __shared__ float4 red[W > 1 ? W * R * 64 : 1];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int ks = blockIdx.z;
+  int slot = blockIdx.y;
+  const char* W2;
+  const float* S2 = nullptr;
+  const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
+  bool live;  // token column r contributes only if the token is routed to this expert
+  if (slot < g.routed_slots) {
+    const int nu = *g.n_unique;  // three independent loads, one round trip
+    const int e = g.slot_expert[slot];
+    // 0 also for the padded columns r >= T; packed: column n + 8 belongs to token n
+    live = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)] != 0.f;
+    if (slot >= nu) return;
+    W2 = reinterpret_cast<const char*>(g.w2) + e * per;
+    if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
+  } else {
+    live = (PK ? (r & (kPackedTokens - 1)) : r) < g.T;
+    const int sh = slot - g.routed_slots;
+    W2 = reinterpret_cast<const char*>(g.sw2) + sh * per;
+    if constexpr (FP8) S2 = g.ss2 + (size_t)sh * g.d;
+    slot = g.u_max + sh;
+  }
+  const int ntiles = g.d >> 4, tile0 = blockIdx.x * R;
+  const int nsteps = g.ffn >> (FP8 ? 6 : 5), parts = g.KS * W, chunk = (nsteps + parts - 1) / parts;
+  const int nst = max(0, min(chunk, nsteps - (ks * W + wave) * chunk));
+  const int s_beg = min((ks * W + wave) * chunk, nsteps - 1);  // a wave without work still issues in-bounds loads
+
+  const WeightAddr<TILED, FP8> wa(g.ffn, r, kg, lane);
+  const char* base[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j)
+    base[j] = W2 + (size_t)min(tile0 + j, ntiles - 1) * wa.tile_stride + (size_t)s_beg * wa.step_stride;
+  const char* HH =
+      reinterpret_cast<const char*>(g.hf_hi) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+  const char* HL =
+      reinterpret_cast<const char*>(g.hf_lo) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+  const uint32_t b_off = lane * 16;
+
+  f32x4 acc[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  pipeline<R, NB, PK, P>(
+      nst,
+      [&](Stage<R, NB, PK>& st, int s) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          st.bh[b] = uint4{0u, 0u, 0u, 0u};
+          if constexpr (!PK) st.bl[b] = uint4{0u, 0u, 0u, 0u};
+          if (live) {  // H of a token that was not routed here was never written: do not read it
+            st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+            if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+          }
+        }
+      },
+      [&](const Stage<R, NB, PK>& st) {
+        if constexpr (FP8) {
+#pragma unroll
+          for (int j = 0; j < R; ++j) {
+            uint4 k0, k1;
+            fp8x16_to_bf16(st.a[j], k0, k1);
+            acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
+            acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+          if constexpr (!PK) {
+#pragma unroll
+            for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+          }
+        }
+      });
+
+  if constexpr (W > 1) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) red[(wave * R + j) * 64 + lane] = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j % W != wave || tile0 + j >= ntiles) continue;
+    float4 y;
+    if constexpr (W > 1) {
+      y = red[j * 64 + lane];
+      for (int w = 1; w < W; ++w) {
+        const float4 y2 = red[(w * R + j) * 64 + lane];
+        y.x += y2.x, y.y += y2.y, y.z += y2.z, y.w += y2.w;
+      }
+    } else {
+      y = float4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+    }
+    if constexpr (PK)  // column n + 8 carries the lo-half contribution of token n
+      y.x += __shfl_xor(y.x, 8), y.y += __shfl_xor(y.y, 8), y.z += __shfl_xor(y.z, 8), y.w += __shfl_xor(y.w, 8);
+    if constexpr (FP8) {  // scaling each split-K partial sum by the row scale = scaling the whole sum
+      const float4 c2 = *reinterpret_cast<const float4*>(S2 + (tile0 + j) * 16 + kg * 4);
+      y.x *= c2.x, y.y *= c2.y, y.z *= c2.z, y.w *= c2.w;
+    }
+    if (live && (!PK || r < kPackedTokens)) {  // nobody reads the slab column of a token that was not routed here
+      const size_t o = (((size_t)slot * g.KS + ks) * g.max_tokens + r) * g.d + (size_t)(tile0 + j) * 16 + kg * 4;
+      *reinterpret_cast<float4*>(g.partial + o) = y;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Step 5: out[t] = sum over the token's own picks i = 0 .. top_k-1 (the slot each landed in comes from
+// the grouping step), then the shared experts; k-chunks ascending inside each.  A fixed order — the
+// order of the defining sum — so reruns are bit-identical and no floating-point atomics are needed.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
+                                                      const int32_t* __restrict__ tok_slot, float* __restrict__ out,
+                                                      int d, int T, int top_k, int u_max, int n_shared,
+                                                      int max_tokens, int KS) {
+  const int i = blockIdx.x * 256 + threadIdx.x;  // float4 index inside [T, d]
+  const int per_tok = d >> 2;
+  if (i >= T * per_tok) return;
+  const int t = i / per_tok, c4 = i - t * per_tok;
+  float4 s = float4{0.f, 0.f, 0.f, 0.f};
+  const size_t slab = (size_t)max_tokens * d;
+  const float* p0 = partial + (size_t)t * d + (size_t)c4 * 4;
+  // flat walk over (pick, k-chunk): unrolled by 8 so that eight slab loads are in flight at a time
+  const int n = (top_k + n_shared) * KS;
+#pragma unroll 8
+  for (int q = 0; q < n; ++q) {
+    const int j = q / KS, k = q - j * KS;
+    const int u = j < top_k ? tok_slot[t * top_k + j] : u_max + (j - top_k);
+    const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
+    s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+  }
+  *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
+}
+
+// One-off re-layout of a row-major [rows, K] bf16 matrix into the tiled order (see WeightAddr).
+__global__ __launch_bounds__(256) void pack_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t rows,
+                                                   int K) {
+  const size_t nsteps = (size_t)(K >> 5), units = rows * (size_t)(K >> 3);
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < units; q += (size_t)gridDim.x * 256) {
+    const size_t blk = q >> 6;
+    const int l = (int)(q & 63), rr = l & 15, kk = l >> 4;
+    const size_t tile = blk / nsteps, st = blk % nsteps;
+    dst[q] = src[((tile * 16 + rr) * (size_t)K + st * 32 + kk * 8) >> 3];
+  }
+}
+
+// The same for FP8 codes: a 1 KB block holds 16 rows x 64 k; unit l = (r, kg) = the 8 codes of k-step
+// 2p followed by the 8 codes of k-step 2p+1.
+__global__ __launch_bounds__(256) void pack_kernel_fp8(const uint2* __restrict__ src, uint4* __restrict__ dst,
+                                                       size_t rows, int K) {
+  const size_t npairs = (size_t)(K >> 6), units = rows * (size_t)(K >> 4);
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < units; q += (size_t)gridDim.x * 256) {
+    const size_t blk = q >> 6;
+    const int l = (int)(q & 63), rr = l & 15, kk = l >> 4;
+    const size_t tile = blk / npairs, pr = blk % npairs;
+    const size_t i0 = ((tile * 16 + rr) * (size_t)K + pr * 64 + kk * 8) >> 3;
+    const uint2 a = src[i0], b = src[i0 + 4];
+    dst[q] = uint4{a.x, a.y, b.x, b.y};
+  }
+}
+
+}  // namespace

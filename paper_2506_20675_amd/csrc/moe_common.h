@@ -1,0 +1,149 @@
+// Shared device helpers of the MoE kernels: bf16 / FP8 conversions, 128-bit loads, the activation-fragment
+// layout, the MFMA wrapper, the register software pipeline and the weight addressing.
+// Part of the single translation unit moe_kernels.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cascade_moe.h"
+
+namespace {
+
+constexpr int kMaxTokens = 16;
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 16;
+constexpr int kMaxShared = 8;
+constexpr int kGateCols = 16;  // columns of the per-slot gate table = MFMA N
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // keep NaN a NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// x = hi + lo (+ residual below 2^-17 |x|): both halves are exact bf16 numbers.
+__device__ __forceinline__ void split_bf16(float x, uint16_t& hi, uint16_t& lo) {
+  hi = f32_to_bf16(x);
+  lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit global load; NT = streaming (non-temporal) hint for bytes that are read exactly once.
+template <bool NT>
+__device__ __forceinline__ uint4 ld128(const char* base, uint32_t byte_off) {
+  if constexpr (NT) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
+    return uint4{v.x, v.y, v.z, v.w};
+  } else {
+    return *reinterpret_cast<const uint4*>(base + byte_off);
+  }
+}
+
+// Activation fragments.  The MFMA B operand of k-step s (32 k) wants, in lane (n = l%16, kg = l/16),
+// the 8 values k = 32 s + 8 kg .. +7 of token column n.  Activations are therefore stored in that
+// order — unit q = s*64 + kg*16 + n holds those 8 bf16 (16 bytes) — so a wave fetches the whole
+// fragment of a k-step with ONE contiguous 1 KB load.  Token columns are padded to 16.
+//
+// Two arrangements of the bf16 hi + lo halves of the fp32 activations:
+//   split   (T > 8)   two fragment arrays, hi and lo; column n = token n; two MFMAs per weight tile
+//   packed  (T <= 8)  ONE array: column n < 8 = hi half of token n, column n + 8 = lo half of token n.
+//                     MFMA columns are independent, so one MFMA yields the hi and the lo contribution
+//                     in two columns, which the epilogue adds: half the fragment loads and half the
+//                     MFMAs for every speculation length up to K = 7.
+constexpr int kPackedTokens = 8;
+__device__ __forceinline__ size_t frag_unit(int k8, int n) {  // k8 = k / 8
+  return (size_t)(k8 >> 2) * 64 + (size_t)(k8 & 3) * 16 + n;
+}
+
+// FP8 weights: the 16 bytes a lane loads are its 8 codes of one k-step followed by its 8 codes of the
+// next k-step.  Every E4M3 value is exactly a bf16 number, so the codes are widened in registers (two
+// codes per instruction) and fed to the same bf16 MFMA; the per-row scale is applied to the fp32 sums.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+template <bool HI>
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t v) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v, 1.0f, HI));
+}
+__device__ __forceinline__ void fp8x16_to_bf16(uint4 a, uint4& k0, uint4& k1) {
+  k0 = uint4{fp8x2_to_bf16x2<false>(a.x), fp8x2_to_bf16x2<true>(a.x), fp8x2_to_bf16x2<false>(a.y),
+             fp8x2_to_bf16x2<true>(a.y)};
+  k1 = uint4{fp8x2_to_bf16x2<false>(a.z), fp8x2_to_bf16x2<true>(a.z), fp8x2_to_bf16x2<false>(a.w),
+             fp8x2_to_bf16x2<true>(a.w)};
+}
+
+__device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                  0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// Shared software pipeline of the two expert kernels.
+//   NA  A tiles (16 rows) consumed per step, each with its own wave-uniform base pointer
+//   NB  k-steps (32 k) one 128-bit weight load covers: 1 for bf16, 2 for FP8
+//   P   pipeline depth (steps of loads in flight per wave)
+// A stage holds one 128-bit load per tile plus the hi and lo activation fragments of its NB k-steps.
+// ------------------------------------------------------------------------------------------
+template <int NA, int NB, bool PK>
+struct Stage {
+  uint4 a[NA];
+  uint4 bh[NB];
+  uint4 bl[PK ? 1 : NB];  // unused when the halves are packed into bh
+};
+
+template <int NA, int NB, bool PK, int P, class Load, class Compute>
+__device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
+  Stage<NA, NB, PK> st[P];
+  // The prologue loads are unconditional (a short wave re-reads its last valid step): a load that
+  // is issued on only some paths makes the compiler's wait counters pessimistic inside the loop.
+  const int last = nst > 0 ? nst - 1 : 0;
+#pragma unroll
+  for (int p = 0; p < P; ++p) load(st[p], min(p, last));
+  int s = 0;
+  for (; s + 2 * P <= nst; s += P) {
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      compute(st[p]);
+      load(st[p], s + p + P);
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < P; ++p)
+    if (s + p < nst) {
+      compute(st[p]);
+      if (s + p + P < nst) load(st[p], s + p + P);
+    }
+#pragma unroll
+  for (int p = 0; p < P; ++p)
+    if (s + P + p < nst) compute(st[p]);
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight addressing.  A step of a 16-row tile is 1 KB: 16 rows x 32 k of bf16, or 16 rows x 64 k of FP8.
+//   row-major [rows, K]:  lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg   (bf16 only)
+//   tiled              :  the same 1 KB stored contiguously, block index tile*(steps per row) + s, lane
+//                         l at byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
+// ------------------------------------------------------------------------------------------
+template <bool TILED, bool FP8>
+struct WeightAddr {
+  uint32_t lane_off, step_stride;
+  size_t tile_stride;
+  __device__ __forceinline__ WeightAddr(int K, int r, int kg, int lane) {
+    static_assert(TILED || !FP8, "FP8 weights are consumed in the tiled layout only");
+    if constexpr (TILED) {
+      lane_off = lane * 16;
+      step_stride = 1024;
+      tile_stride = (size_t)(K >> (FP8 ? 6 : 5)) * 1024;
+    } else {
+      lane_off = ((uint32_t)r * K + kg * 8) * 2;
+      step_stride = 64;
+      tile_stride = (size_t)16 * K * 2;
+    }
+  }
+};
+
+}  // namespace

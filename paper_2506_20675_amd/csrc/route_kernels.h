@@ -1,0 +1,310 @@
+// Steps 1 and 2 of the MoE verification path: router (logits, top-k, gates, activation fragments) and the
+// expert-union grouping.  Part of the single translation unit moe_kernels.hip.
+#pragma once
+#include "moe_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Step 2: union of activated experts + per-expert token lists + the tables the expert kernels and
+// the combine read.  One workgroup; thread a = one (token, pick) pair, thread e = one expert.
+// ------------------------------------------------------------------------------------------
+struct GroupArgs {
+  const int32_t* ids;   // [T, top_k], the picks of one token distinct
+  const float* gates;   // [T, top_k] or NULL (then no gate table is built)
+  int T, top_k, E;
+  int32_t *unique, *n_unique, *count, *offset, *assign;     // caller-visible outputs, each optional
+  int32_t *n_unique_ws, *n_unique_extra, *slot_expert;      // tables for the expert kernels, each optional
+  int32_t* tok_slot;                                        // [T, top_k] slot of the union each pick landed in
+  float* slot_gate;                                         // [u_max, 16]
+};
+
+// Every thread of the workgroup must call this (it holds barriers); blockDim.x >= 256.
+// s_ids_in / s_gates_in: the routing in LDS, or NULL to read g.ids / g.gates.
+// A token picks an expert at most once, so expert e's token list is a 16-bit mask: pairs set their
+// bit with an LDS atomic OR (commutative, so the result does not depend on arrival order), counts are
+// popcounts, and lists come out in ascending token order by walking the set bits.
+__device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float* s_gates_in) {
+  __shared__ int s_ids_own[kMaxTokens * kMaxTopK];
+  __shared__ unsigned s_mask[kMaxExperts];
+  __shared__ unsigned char s_pos[kMaxExperts * kMaxTokens];  // which pick i of token t chose expert e
+  __shared__ int s_rank[kMaxExperts];
+  __shared__ float s_row[kMaxExperts * kGateCols];           // gate table by slot, built in LDS
+  __shared__ int s_cnt[4], s_uni[4];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int E = g.E, A = g.T * g.top_k;
+  const bool want_gates = g.slot_gate && (g.gates || s_gates_in);
+  const int* s_ids = s_ids_in ? s_ids_in : s_ids_own;
+  if (!s_ids_in && tid < A) s_ids_own[tid] = g.ids[tid];
+  if (tid < E) s_mask[tid] = 0u;
+  const int max_slots = A < E ? A : E;
+  if (want_gates)
+    for (int i = tid; i < max_slots * kGateCols; i += blockDim.x) s_row[i] = 0.f;
+  __syncthreads();
+  const int my_e = tid < A ? s_ids[tid] : -1;
+  const int my_t = tid / g.top_k;
+  const bool pair_ok = tid < A && (unsigned)my_e < (unsigned)E;
+  if (pair_ok) {
+    atomicOr(&s_mask[my_e], 1u << my_t);
+    s_pos[my_e * kMaxTokens + my_t] = (unsigned char)(tid - my_t * g.top_k);
+  }
+  __syncthreads();
+  const bool act = tid < 256;
+  const int e = tid;
+  unsigned m = (act && e < E) ? s_mask[e] : 0u;
+  const int cnt = __popc(m);
+  const int flag = cnt > 0;
+  // inclusive scan of cnt inside the wave, ballot for the rank among live experts
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  const unsigned long long bal = __ballot(flag);
+  const int rank_in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+  if (act && lane == 63) s_cnt[wave] = incl;
+  if (act && lane == 0) s_uni[wave] = __popcll(bal);
+  __syncthreads();
+  int cbase = 0, ubase = 0, n_unique = 0, total = 0;
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) {
+      cbase += s_cnt[w];
+      ubase += s_uni[w];
+    }
+    n_unique += s_uni[w];
+    total += s_cnt[w];
+  }
+  if (act && e < E) {
+    const int off = cbase + incl - cnt;
+    const int rank = ubase + rank_in_wave;
+    if (g.count) g.count[e] = cnt;
+    if (g.offset) g.offset[e] = off;
+    if (flag) {
+      s_rank[e] = rank;
+      if (g.unique) g.unique[rank] = e;
+      if (g.slot_expert) g.slot_expert[rank] = e;
+      if (g.assign) {
+        int j = 0;
+        while (m) {
+          const int t = __ffs(m) - 1;
+          m &= m - 1u;
+          g.assign[off + j++] = t * g.top_k + s_pos[e * kMaxTokens + t];
+        }
+      }
+    }
+    if (e >= n_unique && g.unique) g.unique[e] = -1;
+  }
+  if (tid == 0) {
+    if (g.offset) g.offset[E] = total;
+    if (g.n_unique) *g.n_unique = n_unique;
+    if (g.n_unique_ws) *g.n_unique_ws = n_unique;
+    if (g.n_unique_extra) *g.n_unique_extra = n_unique;
+  }
+  __syncthreads();
+  if (pair_ok) {
+    const int slot = s_rank[my_e];
+    if (g.tok_slot) g.tok_slot[tid] = slot;
+    if (want_gates) s_row[slot * kGateCols + my_t] = s_gates_in ? s_gates_in[tid] : g.gates[tid];
+  }
+  if (!want_gates) return;
+  __syncthreads();
+  for (int i = tid; i < n_unique * kGateCols; i += blockDim.x) g.slot_gate[i] = s_row[i];
+}
+
+__global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g, nullptr, nullptr); }
+
+// ------------------------------------------------------------------------------------------
+// Step 1: router.
+// ------------------------------------------------------------------------------------------
+struct RouteArgs {
+  const float* hidden;       // [T, d]
+  const uint16_t* router_w;  // [E, d]
+  int d, E, top_k, T, gate_mode;
+  int32_t *ids_ws, *ids_out;  // [T, top_k]; *_out optional
+  float *gates_ws, *gates_out;
+  uint16_t *xf_hi, *xf_lo;    // activation fragments
+};
+
+// activations of token t -> bf16 hi/lo halves in fragment order (the MFMA B operand of the expert kernels)
+__device__ __forceinline__ void split_token(const float* __restrict__ x, int d, int t, int first, int stride,
+                                            uint16_t* __restrict__ xf_hi, uint16_t* __restrict__ xf_lo, bool packed) {
+  for (int k8 = first; k8 < (d >> 3); k8 += stride) {
+    const float4 v0 = *reinterpret_cast<const float4*>(x + k8 * 8);
+    const float4 v1 = *reinterpret_cast<const float4*>(x + k8 * 8 + 4);
+    const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint16_t h0, l0, h1, l1;
+      split_bf16(v[2 * i], h0, l0);
+      split_bf16(v[2 * i + 1], h1, l1);
+      h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    const size_t q = frag_unit(k8, t);
+    reinterpret_cast<uint4*>(xf_hi)[q] = uint4{h[0], h[1], h[2], h[3]};
+    if (packed)
+      reinterpret_cast<uint4*>(xf_hi)[q + kPackedTokens] = uint4{l[0], l[1], l[2], l[3]};
+    else
+      reinterpret_cast<uint4*>(xf_lo)[q] = uint4{l[0], l[1], l[2], l[3]};
+  }
+}
+
+constexpr int kRouteWaves = 16;  // waves per token in route_kernel
+constexpr int kRouteBatch = 8;   // expert rows one work item covers
+
+// One work item of the router of one token: the 512-element chunk `chunk` of d against the expert
+// rows e0 .. e0+7.  The activation loads and the (up to) 8 row loads are issued together — one round
+// trip — and accumulated in fp64: fp32 x bf16 products are exact in double, so the top-k decision does
+// not depend on the order of summation (beyond ~1e-13 relative).  The 64 lanes' partial sums are
+// folded by a reduce-scatter butterfly (each exchange halves the experts a lane still carries: 4 + 2 +
+// 1 exchanges, then 3 plain ones) instead of one 6-step butterfly per expert; lane 8*i then adds the
+// sum of expert e0 + i to s_acc[e0 + i], the wave's own row of partial logits.
+__device__ __forceinline__ void route_item(const float* __restrict__ x, const uint16_t* __restrict__ router_w, int d,
+                                           int E, int lane, int chunk, int e0, double* s_acc) {
+  const int j = chunk * 512 + lane * 8;
+  const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+  const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+  uint4 wv[kRouteBatch];
+#pragma unroll
+  for (int e = 0; e < kRouteBatch; ++e) {
+    const int row = min(e0 + e, E - 1);  // past the last expert: re-read a valid row, result unused
+    wv[e] = *reinterpret_cast<const uint4*>(router_w + (size_t)row * d + j);
+  }
+  const double xd[8] = {(double)x0.x, (double)x0.y, (double)x0.z, (double)x0.w,
+                        (double)x1.x, (double)x1.y, (double)x1.z, (double)x1.w};
+  double v[kRouteBatch];
+#pragma unroll
+  for (int e = 0; e < kRouteBatch; ++e) {
+    double a = 0.0;
+    a = fma(xd[0], (double)bf16_to_f32(wv[e].x & 0xffffu), a);
+    a = fma(xd[1], (double)bf16_to_f32(wv[e].x >> 16), a);
+    a = fma(xd[2], (double)bf16_to_f32(wv[e].y & 0xffffu), a);
+    a = fma(xd[3], (double)bf16_to_f32(wv[e].y >> 16), a);
+    a = fma(xd[4], (double)bf16_to_f32(wv[e].z & 0xffffu), a);
+    a = fma(xd[5], (double)bf16_to_f32(wv[e].z >> 16), a);
+    a = fma(xd[6], (double)bf16_to_f32(wv[e].w & 0xffffu), a);
+    a = fma(xd[7], (double)bf16_to_f32(wv[e].w >> 16), a);
+    v[e] = a;
+  }
+  // reduce-scatter: after the exchange over lane bit 5 a lane carries experts {0..3} or {4..7}, ...
+  const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
+  double u4[4], u2[2], u1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const double send = b5 ? v[i] : v[i + 4];
+    const double keep = b5 ? v[i + 4] : v[i];
+    u4[i] = keep + __shfl_xor(send, 32);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const double send = b4 ? u4[i] : u4[i + 2];
+    const double keep = b4 ? u4[i + 2] : u4[i];
+    u2[i] = keep + __shfl_xor(send, 16);
+  }
+  {
+    const double send = b3 ? u2[0] : u2[1];
+    const double keep = b3 ? u2[1] : u2[0];
+    u1 = keep + __shfl_xor(send, 8);
+  }
+  u1 += __shfl_xor(u1, 4);
+  u1 += __shfl_xor(u1, 2);
+  u1 += __shfl_xor(u1, 1);
+  const int idx = (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0);
+  if ((lane & 7) == 0 && e0 + idx < E) s_acc[e0 + idx] += u1;
+}
+
+// One workgroup (16 waves) per token.  The (chunk of d, batch of 8 experts) work items are dealt
+// round-robin to the waves; partial logits meet in LDS and are summed in wave order.  Top-k by rank
+// counting: thread e counts the logits that beat its own (larger, or equal with a lower index), the
+// expert of rank i < top_k is pick i — no serial arg-max rounds.  Gates = softmax over the picked
+// logits in fp32, summed in pick order.  With a single token in flight (T = 1, no speculation) this
+// workgroup already sees the whole routing, so the expert-union step runs right here; with more
+// tokens it needs the launch of its own that follows (group_kernel).
+__global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, GroupArgs grp) {
+  __shared__ double s_part[kRouteWaves][kMaxExperts];
+  __shared__ double s_logit[kMaxExperts];
+  __shared__ int s_ids[kMaxTopK];
+  __shared__ float s_sel[kMaxTopK];
+  __shared__ float s_gates[kMaxTopK];
+  __shared__ float s_prob[kMaxExperts];
+  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int E = g.E, top_k = g.top_k;
+  const float* x = g.hidden + (size_t)t * g.d;
+  const int n_batches = (E + kRouteBatch - 1) / kRouteBatch;
+  const int n_full = g.d >> 9;  // whole 512-element chunks
+  const int n_items = n_full * n_batches;
+  for (int e = lane; e < E; e += 64) s_part[wave][e] = 0.0;  // the wave's own row: no barrier needed
+  for (int it = wave; it < n_items; it += kRouteWaves)
+    route_item(x, g.router_w, g.d, E, lane, it / n_batches, (it % n_batches) * kRouteBatch, s_part[wave]);
+  if ((g.d & 511) && wave == kRouteWaves - 1) {
+    // ragged tail of d (a multiple of 32 elements): lanes walk it 8 elements at a time
+    for (int e = 0; e < E; ++e) {
+      double a = 0.0;
+      for (int j = (n_full << 9) + lane * 8; j < g.d; j += 512) {
+        const uint4 w = *reinterpret_cast<const uint4*>(g.router_w + (size_t)e * g.d + j);
+        const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+        const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+        a = fma((double)x0.x, (double)bf16_to_f32(w.x & 0xffffu), a);
+        a = fma((double)x0.y, (double)bf16_to_f32(w.x >> 16), a);
+        a = fma((double)x0.z, (double)bf16_to_f32(w.y & 0xffffu), a);
+        a = fma((double)x0.w, (double)bf16_to_f32(w.y >> 16), a);
+        a = fma((double)x1.x, (double)bf16_to_f32(w.z & 0xffffu), a);
+        a = fma((double)x1.y, (double)bf16_to_f32(w.z >> 16), a);
+        a = fma((double)x1.z, (double)bf16_to_f32(w.w & 0xffffu), a);
+        a = fma((double)x1.w, (double)bf16_to_f32(w.w >> 16), a);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+      if (lane == 0) s_part[wave][e] += a;
+    }
+  }
+  split_token(x, g.d, t, tid, 64 * kRouteWaves, g.xf_hi, g.xf_lo, g.T <= kPackedTokens);
+  __syncthreads();
+  if (tid < E) {
+    double l = 0.0;
+#pragma unroll
+    for (int w = 0; w < kRouteWaves; ++w) l += s_part[w][tid];
+    if (l != l) l = -INFINITY;  // a NaN logit is never preferred
+    s_logit[tid] = l;
+  }
+  __syncthreads();
+  if (tid < E) {
+    const double mine = s_logit[tid];
+    int rank = 0;
+    for (int j = 0; j < E; ++j) {
+      const double o = s_logit[j];  // same address in every lane: an LDS broadcast
+      rank += (o > mine || (o == mine && j < tid)) ? 1 : 0;
+    }
+    if (rank < top_k) {
+      s_ids[rank] = tid;
+      s_sel[rank] = (float)mine;
+    }
+  }
+  __syncthreads();
+  const bool all = g.gate_mode == MOE_GATE_SOFTMAX_ALL;
+  if (all) {  // exp(l_e - max) of every expert, for the denominator over all E
+    if (tid < E) s_prob[tid] = expf((float)s_logit[tid] - s_sel[0]);
+    __syncthreads();
+  }
+  if (tid < top_k) {
+    // p_i = exp(l_i - l_0); denominator summed in pick order over the picks, or in expert order over all experts
+    const float l0 = s_sel[0];
+    float sum = 0.f;
+    if (all)
+      for (int e = 0; e < E; ++e) sum += s_prob[e];
+    else
+      for (int i = 0; i < top_k; ++i) sum += expf(s_sel[i] - l0);
+    const float gate = expf(s_sel[tid] - l0) / sum;
+    const int a = t * top_k + tid, id = s_ids[tid];
+    g.ids_ws[a] = id;
+    g.gates_ws[a] = gate;
+    if (g.ids_out) g.ids_out[a] = id;
+    if (g.gates_out) g.gates_out[a] = gate;
+    s_gates[tid] = gate;
+  }
+  if (gridDim.x == 1) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+}
+
+}  // namespace
