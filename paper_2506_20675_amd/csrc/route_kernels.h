@@ -273,7 +273,8 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
   if (tid < E) {
     const double mine = s_logit[tid];
     int rank = 0;
-    for (int j = 0; j < E; ++j) {
+#pragma unroll 8
+    for (int j = 0; j < E; ++j) {  // unrolled: eight independent LDS reads in flight instead of one
       const double o = s_logit[j];  // same address in every lane: an LDS broadcast
       rank += (o > mine || (o == mine && j < tid)) ? 1 : 0;
     }
