@@ -16,7 +16,8 @@
  * Conventions
  *  - C11, no C++ types, no exceptions; every call returns a moe_status (or a plain value).
  *  - "DEVICE" pointers are HIP device pointers owned by the caller; "HOST" pointers are ordinary
- *    host memory.  bf16 tensors are passed as uint16_t bit patterns, row-major, dense.
+ *    host memory.  bf16 tensors are passed as uint16_t bit patterns (FP8 tensors as bytes),
+ *    row-major and dense unless a call says otherwise.
  *  - Device calls only ENQUEUE work on `stream` (a hipStream_t passed as void*, NULL = the default
  *    stream).  They never synchronise, never copy to the host and never allocate; outputs are
  *    valid once the caller has synchronised the stream.  Argument validation is synchronous.
@@ -221,13 +222,14 @@ moe_status moe_decoder_stack(moe_ctx* ctx, const moe_layer_weights* layers, cons
                              const float* x_in, int32_t T, float eps, float* x_out, float* trace_opt,
                              int32_t* n_unique_per_layer_opt, void* stream);
 
-/* Measurement aid: per-kernel timing.  While enabled, every moe_verify_layer / moe_verify_stack
- * layer records HIP events on its stream around each of its four kernels (route, gate/up with the
- * expert-union step, down, combine); this adds event packets between the kernels, so whole-step latency is measured with
- * profiling OFF.
+/* Measurement aid: per-kernel timing.  While enabled, every layer of moe_verify_layer /
+ * moe_verify_stack (and the MoE half of every block of the chained calls, whose slab sum is then
+ * counted with the next block and reads as zero here) records HIP events on its stream around each
+ * of its four stages (route with the expert-union step, gate/up, down, combine); this adds event
+ * packets between the kernels, so whole-step latency is measured with profiling OFF.
  * moe_ctx_profile_read waits for the recorded events, adds the elapsed times into ms_sum[0..3]
- * (HOST, milliseconds, same kernel order), stores the number of layer-steps in
- * *steps (HOST) and forgets the events.  Both calls may allocate/free event objects. */
+ * (HOST, milliseconds, same stage order), stores the number of layer-steps in *steps (HOST) and
+ * forgets the events.  Both calls may allocate/free event objects. */
 moe_status moe_ctx_profile(moe_ctx* ctx, int32_t enable);
 moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);
 
