@@ -8,7 +8,8 @@
 //   route_kernel   one workgroup (16 waves) per token: router logits (fp64 accumulate), top-k by rank
 //                  counting, softmax gates, and the bf16 hi + lo activation fragments for the matrix cores
 //   group_kernel   union of experts, per-expert token lists, slot tables for the expert kernels and the
-//                  combine (for a single token, T = 1, route_kernel does this itself and the launch is skipped)
+//                  combine (for a single token, T = 1, route_kernel does this itself and the launch is skipped;
+//                  with many experts and T > 1 the pair logits_kernel + topk_group_kernel replaces both)
 //   gateup_kernel  for each slot of the union: G = w1 X, U = w3 X, H = gate * silu(G) * U   (2/3 of bytes)
 //   down_kernel    split-K partial sums of w2 H over (slot, k-chunk)                        (1/3 of bytes)
 //   combine_kernel out[t] = sum of the slabs of token t's own picks, in pick order (deterministic, no atomics)
@@ -90,6 +91,7 @@ struct moe_ctx {
   int32_t *ids, *n_unique, *slot_expert, *tok_slot;
   float *gates, *slot_gate, *partial;
   float *xn, *resid[2];  // chained stack: normalised router input and the residual stream (ping-pong), [max_tokens, d]
+  double* logits;        // wide routers: fp64 logits [max_tokens, E] between logits_kernel and topk_group_kernel
   float *hbuf, *qkv;     // decoder stack: stream after the attention half [max_tokens, d]; q|k|v [max_tokens, (H+2Hkv) dh]
   uint16_t *af_hi, *af_lo;  // decoder stack: fragments of the attention output, H*dh*16 elements each
   bool profiling;
@@ -101,6 +103,7 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
+constexpr int kWideRouterExperts = 32;  // from this many experts on, T > 1 routes through logits_kernel + topk_group_kernel
 
 // Launch plan of the two expert kernels for one (T, weight layout).
 //   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
@@ -174,6 +177,13 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
                c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
                c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
+  if (T > 1 && s.n_experts >= kWideRouterExperts) {
+    // many experts, several tokens: logits over (token, 16 experts) workgroups, then one workgroup for top-k + union
+    const dim3 grid(T, (s.n_experts + kLogitExperts - 1) / kLogitExperts);
+    hipLaunchKernelGGL(logits_kernel, grid, dim3(64 * kLogitWaves), 0, st, ra, c->logits);
+    hipLaunchKernelGGL(topk_group_kernel, dim3(1), dim3(1024), 0, st, ra, ga, (const double*)c->logits);
+    return;
+  }
   hipLaunchKernelGGL(route_kernel, dim3(T), dim3(64 * kRouteWaves), 0, st, ra, ga);
   if (T > 1) hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, st, ga);  // T = 1: done inside route_kernel
 }
@@ -368,6 +378,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   const size_t nq = (size_t)s.n_heads * s.head_dim, nqkv = nq + 2 * (size_t)s.n_kv_heads * s.head_dim;
   const size_t o_hb = carve((size_t)s.max_tokens * s.d * 4), o_qkv = carve((size_t)s.max_tokens * nqkv * 4 + 16);
   const size_t o_ah = carve(nq * kGateCols * 2 + 16), o_al = carve(nq * kGateCols * 2 + 16);
+  const size_t o_lg = carve((size_t)s.max_tokens * s.n_experts * 8);
   c->ws_bytes = off;
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
@@ -392,6 +403,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->qkv = reinterpret_cast<float*>(c->ws + o_qkv);
   c->af_hi = reinterpret_cast<uint16_t*>(c->ws + o_ah);
   c->af_lo = reinterpret_cast<uint16_t*>(c->ws + o_al);
+  c->logits = reinterpret_cast<double*>(c->ws + o_lg);
   if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
     delete c;

@@ -162,7 +162,7 @@ constexpr int kRouteBatch = 8;   // expert rows one work item covers
 // 1 exchanges, then 3 plain ones) instead of one 6-step butterfly per expert; lane 8*i then adds the
 // sum of expert e0 + i to s_acc[e0 + i], the wave's own row of partial logits.
 __device__ __forceinline__ void route_item(const float* __restrict__ x, const uint16_t* __restrict__ router_w, int d,
-                                           int E, int lane, int chunk, int e0, double* s_acc) {
+                                           int E, int lane, int chunk, int e0, double* s_acc, int acc_base = 0) {
   const int j = chunk * 512 + lane * 8;
   const float4 x0 = *reinterpret_cast<const float4*>(x + j);
   const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
@@ -212,7 +212,32 @@ __device__ __forceinline__ void route_item(const float* __restrict__ x, const ui
   u1 += __shfl_xor(u1, 2);
   u1 += __shfl_xor(u1, 1);
   const int idx = (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0);
-  if ((lane & 7) == 0 && e0 + idx < E) s_acc[e0 + idx] += u1;
+  if ((lane & 7) == 0 && e0 + idx < E) s_acc[e0 + idx - acc_base] += u1;  // s_acc[0] belongs to expert acc_base
+}
+
+// Ragged tail of d (a multiple of 32 elements past the last whole 512-element chunk) for experts e_lo .. e_hi-1:
+// the wave's lanes walk it 8 elements at a time; one 6-step butterfly per expert.
+__device__ __forceinline__ void route_tail(const float* __restrict__ x, const uint16_t* __restrict__ router_w, int d,
+                                           int lane, int e_lo, int e_hi, double* s_acc) {
+  for (int e = e_lo; e < e_hi; ++e) {
+    double a = 0.0;
+    for (int j = ((d >> 9) << 9) + lane * 8; j < d; j += 512) {
+      const uint4 w = *reinterpret_cast<const uint4*>(router_w + (size_t)e * d + j);
+      const float4 x0 = *reinterpret_cast<const float4*>(x + j);
+      const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
+      a = fma((double)x0.x, (double)bf16_to_f32(w.x & 0xffffu), a);
+      a = fma((double)x0.y, (double)bf16_to_f32(w.x >> 16), a);
+      a = fma((double)x0.z, (double)bf16_to_f32(w.y & 0xffffu), a);
+      a = fma((double)x0.w, (double)bf16_to_f32(w.y >> 16), a);
+      a = fma((double)x1.x, (double)bf16_to_f32(w.z & 0xffffu), a);
+      a = fma((double)x1.y, (double)bf16_to_f32(w.z >> 16), a);
+      a = fma((double)x1.z, (double)bf16_to_f32(w.w & 0xffffu), a);
+      a = fma((double)x1.w, (double)bf16_to_f32(w.w >> 16), a);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+    if (lane == 0) s_acc[e - e_lo] += a;
+  }
 }
 
 // One workgroup (16 waves) per token.  The (chunk of d, batch of 8 experts) work items are dealt
@@ -238,28 +263,7 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
   for (int e = lane; e < E; e += 64) s_part[wave][e] = 0.0;  // the wave's own row: no barrier needed
   for (int it = wave; it < n_items; it += kRouteWaves)
     route_item(x, g.router_w, g.d, E, lane, it / n_batches, (it % n_batches) * kRouteBatch, s_part[wave]);
-  if ((g.d & 511) && wave == kRouteWaves - 1) {
-    // ragged tail of d (a multiple of 32 elements): lanes walk it 8 elements at a time
-    for (int e = 0; e < E; ++e) {
-      double a = 0.0;
-      for (int j = (n_full << 9) + lane * 8; j < g.d; j += 512) {
-        const uint4 w = *reinterpret_cast<const uint4*>(g.router_w + (size_t)e * g.d + j);
-        const float4 x0 = *reinterpret_cast<const float4*>(x + j);
-        const float4 x1 = *reinterpret_cast<const float4*>(x + j + 4);
-        a = fma((double)x0.x, (double)bf16_to_f32(w.x & 0xffffu), a);
-        a = fma((double)x0.y, (double)bf16_to_f32(w.x >> 16), a);
-        a = fma((double)x0.z, (double)bf16_to_f32(w.y & 0xffffu), a);
-        a = fma((double)x0.w, (double)bf16_to_f32(w.y >> 16), a);
-        a = fma((double)x1.x, (double)bf16_to_f32(w.z & 0xffffu), a);
-        a = fma((double)x1.y, (double)bf16_to_f32(w.z >> 16), a);
-        a = fma((double)x1.z, (double)bf16_to_f32(w.w & 0xffffu), a);
-        a = fma((double)x1.w, (double)bf16_to_f32(w.w >> 16), a);
-      }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
-      if (lane == 0) s_part[wave][e] += a;
-    }
-  }
+  if ((g.d & 511) && wave == kRouteWaves - 1) route_tail(x, g.router_w, g.d, lane, 0, E, s_part[wave]);
   split_token(x, g.d, t, tid, 64 * kRouteWaves, g.xf_hi, g.xf_lo, g.T <= kPackedTokens);
   __syncthreads();
   if (tid < E) {
@@ -306,6 +310,83 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
     s_gates[tid] = gate;
   }
   if (gridDim.x == 1) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+}
+
+// ------------------------------------------------------------------------------------------
+// Wide routers (T > 1 and many experts).  One workgroup per token cannot do E * d fp64 multiply-adds on the
+// router weights fast enough (one compute unit: ~10 us at E = 64, d = 2048), and with several tokens in flight the
+// grouping needs a launch of its own anyway.  So the work is cut the other way:
+//   logits_kernel      grid (T, E / 16): one workgroup per (token, 16 experts) -> fp64 logits in HBM, and the
+//                      workgroups of the first expert block write the activation fragments;
+//   topk_group_kernel  one workgroup: top-k by rank counting and gates for all T tokens, then the expert-union step.
+// Same arithmetic, same orders of summation per logit as route_kernel up to the split of d over 8 instead of 16 waves.
+// ------------------------------------------------------------------------------------------
+constexpr int kLogitWaves = 8;
+constexpr int kLogitExperts = 16;
+
+__global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, double* __restrict__ logits) {
+  __shared__ double s_part[kLogitWaves][kLogitExperts];
+  const int t = blockIdx.x, e_lo = blockIdx.y * kLogitExperts, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nE = min(kLogitExperts, g.E - e_lo);
+  const float* x = g.hidden + (size_t)t * g.d;
+  const int n_batches = (nE + kRouteBatch - 1) / kRouteBatch;
+  const int n_items = (g.d >> 9) * n_batches;
+  if (lane < kLogitExperts) s_part[wave][lane] = 0.0;
+  for (int it = wave; it < n_items; it += kLogitWaves)
+    route_item(x, g.router_w, g.d, g.E, lane, it / n_batches, e_lo + (it % n_batches) * kRouteBatch, s_part[wave], e_lo);
+  if ((g.d & 511) && wave == kLogitWaves - 1) route_tail(x, g.router_w, g.d, lane, e_lo, e_lo + nE, s_part[wave]);
+  if (blockIdx.y == 0) split_token(x, g.d, t, tid, 64 * kLogitWaves, g.xf_hi, g.xf_lo, g.T <= kPackedTokens);
+  __syncthreads();
+  if (tid < nE) {
+    double l = 0.0;
+#pragma unroll
+    for (int w = 0; w < kLogitWaves; ++w) l += s_part[w][tid];
+    if (l != l) l = -INFINITY;  // a NaN logit is never preferred
+    logits[(size_t)t * g.E + e_lo + tid] = l;
+  }
+}
+
+__global__ __launch_bounds__(1024) void topk_group_kernel(RouteArgs g, GroupArgs grp, const double* __restrict__ logits) {
+  __shared__ double s_logit[kMaxTokens * kMaxExperts];
+  __shared__ int s_ids[kMaxTokens * kMaxTopK];
+  __shared__ float s_sel[kMaxTokens * kMaxTopK];
+  __shared__ float s_gates[kMaxTokens * kMaxTopK];
+  const int tid = threadIdx.x, E = g.E, top_k = g.top_k, T = g.T;
+  for (int i = tid; i < T * E; i += 1024) s_logit[i] = logits[i];
+  __syncthreads();
+  for (int i = tid; i < T * E; i += 1024) {  // pair (token, expert): the expert's rank among the token's logits
+    const int t = i / E, e = i - t * E;
+    const double* row = s_logit + t * E;
+    const double mine = row[e];
+    int rank = 0;
+#pragma unroll 8
+    for (int j = 0; j < E; ++j) {
+      const double o = row[j];
+      rank += (o > mine || (o == mine && j < e)) ? 1 : 0;
+    }
+    if (rank < top_k) {
+      s_ids[t * top_k + rank] = e;
+      s_sel[t * top_k + rank] = (float)mine;
+    }
+  }
+  __syncthreads();
+  if (tid < T * top_k) {  // pair (token, pick): its gate, by the same sums in the same order as route_kernel
+    const int t = tid / top_k;
+    const float l0 = s_sel[t * top_k];
+    float sum = 0.f;
+    if (g.gate_mode == MOE_GATE_SOFTMAX_ALL)
+      for (int e = 0; e < E; ++e) sum += expf((float)s_logit[t * E + e] - l0);
+    else
+      for (int i = 0; i < top_k; ++i) sum += expf(s_sel[t * top_k + i] - l0);
+    const float gate = expf(s_sel[tid] - l0) / sum;
+    const int id = s_ids[tid];
+    g.ids_ws[tid] = id;
+    g.gates_ws[tid] = gate;
+    if (g.ids_out) g.ids_out[tid] = id;
+    if (g.gates_out) g.gates_out[tid] = gate;
+    s_gates[tid] = gate;
+  }
+  group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
 }
 
 }  // namespace
