@@ -103,7 +103,7 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
-constexpr int kWideRouterExperts = 32;  // from this many experts on, T > 1 routes through logits_kernel + topk_group_kernel
+constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
 // Launch plan of the two expert kernels for one (T, weight layout).
 //   gu_R, dn_R  weight tiles (16 rows) per wave; the pipeline depth is tied to it (fewer tiles ->
@@ -177,8 +177,9 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
                c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
                c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
-  if (T > 1 && s.n_experts >= kWideRouterExperts) {
-    // many experts, several tokens: logits over (token, 16 experts) workgroups, then one workgroup for top-k + union
+  if (s.n_experts >= kWideRouterExperts) {
+    // many experts: logits over (token, 16 experts) workgroups, then one workgroup for top-k + union (measured
+    // faster than the one-workgroup-per-token router even for a single token, where it costs a launch more)
     const dim3 grid(T, (s.n_experts + kLogitExperts - 1) / kLogitExperts);
     hipLaunchKernelGGL(logits_kernel, grid, dim3(64 * kLogitWaves), 0, st, ra, c->logits);
     hipLaunchKernelGGL(topk_group_kernel, dim3(1), dim3(1024), 0, st, ra, ga, (const double*)c->logits);

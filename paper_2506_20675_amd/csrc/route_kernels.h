@@ -313,9 +313,8 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
 }
 
 // ------------------------------------------------------------------------------------------
-// Wide routers (T > 1 and many experts).  One workgroup per token cannot do E * d fp64 multiply-adds on the
-// router weights fast enough (one compute unit: ~10 us at E = 64, d = 2048), and with several tokens in flight the
-// grouping needs a launch of its own anyway.  So the work is cut the other way:
+// Wide routers (many experts).  One workgroup per token cannot do E * d fp64 multiply-adds on the router weights
+// fast enough (one compute unit: ~10 us at E = 64, d = 2048).  So the work is cut the other way:
 //   logits_kernel      grid (T, E / 16): one workgroup per (token, 16 experts) -> fp64 logits in HBM, and the
 //                      workgroups of the first expert block write the activation fragments;
 //   topk_group_kernel  one workgroup: top-k by rank counting and gates for all T tokens, then the expert-union step.
