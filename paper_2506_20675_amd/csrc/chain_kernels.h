@@ -9,10 +9,12 @@ namespace {
 // Chained stack: one workgroup per token finishes block l-1 and prepares block l in one pass over d:
 //   x_l = x_{l-1} + (slabs of the token's picks, as in combine_kernel)      -> resid_out
 //   n   = x_l / sqrt(mean(x_l^2) + eps) * gamma_l                           -> xn_out (the router's input)
-// partial == NULL: no MoE term (first block: x_0 is the caller's input).  gamma == NULL: no
+// partial == NULL and moe_out == NULL: no MoE term (first block: x_0 is the caller's input); moe_out: the term is
+// already summed.  gamma == NULL: no
 // normalisation (after the last block only the residual stream is wanted).
 // ------------------------------------------------------------------------------------------
 struct ChainArgs {
+  const float* moe_out;    // [T, d]: the MoE term already summed (fused down projection), or NULL
   const float* partial;
   const int32_t* tok_slot;
   const float* resid_in;   // [T, d]
@@ -48,6 +50,7 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) {
         const float4 p = *reinterpret_cast<const float4*>(g.partial + o + ((size_t)u * g.KS + k) * slab);
         m.x += p.x, m.y += p.y, m.z += p.z, m.w += p.w;
       }
+      if (g.moe_out) m = *reinterpret_cast<const float4*>(g.moe_out + o);
       const float4 x = *reinterpret_cast<const float4*>(g.resid_in + o);
       v[q] = float4{x.x + m.x, x.y + m.y, x.z + m.z, x.w + m.w};
       if (g.resid_out) *reinterpret_cast<float4*>(g.resid_out + o) = v[q];

@@ -290,6 +290,115 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Steps 4 + 5 in one launch, for small unions of SMALL experts (a few tens of MB in the whole step), where the
+// step is bound by launch latencies and not by HBM: one workgroup of 16 waves per 16-row tile of d walks ALL live slots.  The waves take (slot, k-chunk)
+// items round-robin; because the gate is already folded into H and the columns of unrouted tokens are masked to
+// zero, every item simply adds into the wave's one accumulator tile, so the sum over a token's experts — the
+// combine — happens in registers, the 16 waves meet in LDS in a fixed order, and out[t] is written directly:
+// no slabs, no combine launch.  (On large experts the split-K kernel above streams better: it shares each H
+// fragment among 4 row tiles.)   grid = d / 16.
+// ------------------------------------------------------------------------------------------
+struct DownFusedArgs {
+  const void *w2, *sw2;
+  const float *s2, *ss2;
+  const uint16_t *hf_hi, *hf_lo;
+  const int32_t* n_unique;
+  const int32_t* slot_expert;
+  const float* slot_gate;
+  float* out;  // [T, d]
+  int d, ffn, T, n_shared, u_max, C;  // C = k-chunks per slot
+};
+
+constexpr int kFusedWaves = 16;
+
+template <int P, bool FP8, bool PK>
+__global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedArgs g) {
+  constexpr int NB = FP8 ? 2 : 1;
+  __shared__ float4 red[kFusedWaves * 64];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int tile = blockIdx.x, col = PK ? (r & (kPackedTokens - 1)) : r;
+  const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
+  const int nu = *g.n_unique, n_items = (nu + g.n_shared) * g.C;
+  const int nsteps = g.ffn >> (FP8 ? 6 : 5), chunk = (nsteps + g.C - 1) / g.C;
+  const WeightAddr<true, FP8> wa(g.ffn, r, kg, lane);
+  const uint32_t b_off = lane * 16;
+  f32x4 total = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int item = wave; item < n_items; item += kFusedWaves) {
+    const int sl = item / g.C, c = item - sl * g.C;
+    const char* W2;
+    const float* S2 = nullptr;
+    int hslot;
+    bool live;
+    if (sl < nu) {
+      const int e = g.slot_expert[sl];
+      live = g.slot_gate[sl * kGateCols + col] != 0.f;
+      W2 = reinterpret_cast<const char*>(g.w2) + e * per;
+      if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
+      hslot = sl;
+    } else {
+      const int sh = sl - nu;
+      live = col < g.T;
+      W2 = reinterpret_cast<const char*>(g.sw2) + sh * per;
+      if constexpr (FP8) S2 = g.ss2 + (size_t)sh * g.d;
+      hslot = g.u_max + sh;
+    }
+    const int nst = max(0, min(chunk, nsteps - c * chunk));
+    const int s_beg = min(c * chunk, nsteps - 1);
+    const char* base = W2 + (size_t)tile * wa.tile_stride + (size_t)s_beg * wa.step_stride;
+    const char* HH =
+        reinterpret_cast<const char*>(g.hf_hi) + ((size_t)hslot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+    const char* HL =
+        reinterpret_cast<const char*>(g.hf_lo) + ((size_t)hslot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    pipeline<1, NB, PK, P>(
+        nst,
+        [&](Stage<1, NB, PK>& st, int s) {
+          st.a[0] = ld128<true>(base, wa.lane_off + (uint32_t)s * wa.step_stride);
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            st.bh[b] = uint4{0u, 0u, 0u, 0u};
+            if constexpr (!PK) st.bl[b] = uint4{0u, 0u, 0u, 0u};
+            if (live) {
+              st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+              if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+            }
+          }
+        },
+        [&](const Stage<1, NB, PK>& st) {
+          if constexpr (FP8) {
+            uint4 k0, k1;
+            fp8x16_to_bf16(st.a[0], k0, k1);
+            acc = mfma_bf16(k0, st.bh[0], acc);
+            if constexpr (!PK) acc = mfma_bf16(k0, st.bl[0], acc);
+            acc = mfma_bf16(k1, st.bh[1], acc);
+            if constexpr (!PK) acc = mfma_bf16(k1, st.bl[1], acc);
+          } else {
+            acc = mfma_bf16(st.a[0], st.bh[0], acc);
+            if constexpr (!PK) acc = mfma_bf16(st.a[0], st.bl[0], acc);
+          }
+        });
+    if constexpr (FP8) {  // every slot has its own row scales: scale the item's sum before it joins the others
+      const float4 c2 = *reinterpret_cast<const float4*>(S2 + tile * 16 + kg * 4);
+      total[0] += acc[0] * c2.x, total[1] += acc[1] * c2.y, total[2] += acc[2] * c2.z, total[3] += acc[3] * c2.w;
+    } else {
+      total[0] += acc[0], total[1] += acc[1], total[2] += acc[2], total[3] += acc[3];
+    }
+  }
+  red[wave * 64 + lane] = float4{total[0], total[1], total[2], total[3]};
+  __syncthreads();
+  if (wave != 0) return;
+  float4 y = red[lane];
+  for (int w = 1; w < kFusedWaves; ++w) {
+    const float4 y2 = red[w * 64 + lane];
+    y.x += y2.x, y.y += y2.y, y.z += y2.z, y.w += y2.w;
+  }
+  if constexpr (PK)
+    y.x += __shfl_xor(y.x, 8), y.y += __shfl_xor(y.y, 8), y.z += __shfl_xor(y.z, 8), y.w += __shfl_xor(y.w, 8);
+  if (r < g.T && (!PK || r < kPackedTokens))
+    *reinterpret_cast<float4*>(g.out + (size_t)r * g.d + (size_t)tile * 16 + kg * 4) = y;
+}
+
+// ------------------------------------------------------------------------------------------
 // Step 5: out[t] = sum over the token's own picks i = 0 .. top_k-1 (the slot each landed in comes from
 // the grouping step), then the shared experts; k-chunks ascending inside each.  A fixed order — the
 // order of the defining sum — so reruns are bit-identical and no floating-point atomics are needed.

@@ -85,6 +85,7 @@ struct moe_ctx {
   int u_max;              // largest possible union: min(E, max_tokens * top_k)
   int ks_alloc;           // split-K slabs the partial buffer is sized for
   int plan_override[3];   // MOE_PLAN=guR,dnR,dnKS (tuning), zeros = automatic
+  bool no_fused_down;     // MOE_NO_FUSED_DOWN set (tuning): always use the split-K down projection
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
@@ -103,6 +104,7 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
+constexpr size_t kFusedDownBytes = (size_t)36 << 20;  // most down-projection bytes per step for the fused down + combine launch
 constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
 // Launch plan of the two expert kernels for one (T, weight layout).
@@ -112,6 +114,7 @@ constexpr int kWideRouterExperts = 32;  // from this many experts on, routing go
 // Chosen from measurements on Mixtral-shaped layers (see plan_for).
 struct Plan {
   int gu_R, dn_R, dn_KS;
+  int dn_fused_C;  // > 0: small experts, down projection and combine in one launch with this many k-chunks per slot
 };
 
 int ks_cap_for(const moe_shape& s, bool fp8) {
@@ -145,6 +148,17 @@ Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
       p.dn_KS = ks;
       break;
     }
+  }
+  // small unions of small experts (up to 36 MB of down-projection weights expected in the step): the step is
+  // latency-bound and one launch less is worth more than the better streaming of the split-K kernel (measured:
+  // 5-8 % on an OLMoE-like layer at K = 0, break-even near 40 MB, a loss beyond).  Items = live slots x C, dealt
+  // to 16 waves; every item keeps >= 8 steps.
+  p.dn_fused_C = 0;
+  const int nsteps = s.ffn / (fp8 ? 64 : 32);
+  if (tiled && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes && !c->no_fused_down) {
+    int C = 1;
+    while (slots * C < 2 * kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
+    p.dn_fused_C = C;
   }
   if (c->plan_override[0] > 0) {
     p.gu_R = c->plan_override[0];
@@ -256,6 +270,24 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     }
   }
   mark(c, st);
+  if (p.dn_fused_C > 0) {
+    // down projection and combine in one launch; with no `out` (chained stack) the summed term goes to the slab
+    // buffer as a plain [T, d] array and *ks_used = 0 tells the caller so
+    DownFusedArgs fa{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
+                     c->slot_gate, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C};
+    const dim3 grid(s.d / 16), block(64 * kFusedWaves);
+    if (fp8) {
+      if (pk) hipLaunchKernelGGL((down_fused_kernel<4, true, true>), grid, block, 0, st, fa);
+      else hipLaunchKernelGGL((down_fused_kernel<4, true, false>), grid, block, 0, st, fa);
+    } else {
+      if (pk) hipLaunchKernelGGL((down_fused_kernel<4, false, true>), grid, block, 0, st, fa);
+      else hipLaunchKernelGGL((down_fused_kernel<4, false, false>), grid, block, 0, st, fa);
+    }
+    mark(c, st);
+    if (ks_used) *ks_used = 0;
+    mark(c, st);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+  }
   DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
               c->slot_gate, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
@@ -342,6 +374,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
   c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
+  c->no_fused_down = getenv("MOE_NO_FUSED_DOWN") != nullptr;
   if (const char* env = getenv("MOE_PLAN")) {  // tuning override: "guR,dnR,dnKS"
     int a = 0, b = 0, k = 0;
     if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
@@ -502,7 +535,8 @@ moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const 
   for (int l = 0; l <= L; ++l) {
     // finish block l-1 (if any) and, unless this is the end, normalise for block l
     ChainArgs a{};
-    a.partial = l > 0 ? c->partial : nullptr;
+    a.partial = l > 0 && ks > 0 ? c->partial : nullptr;
+    a.moe_out = l > 0 && ks == 0 ? c->partial : nullptr;  // ks == 0: the fused down projection already summed the term
     a.tok_slot = c->tok_slot;
     a.resid_in = cur;
     float* dst = l == L ? x_out : (trace_opt ? trace_opt + (size_t)l * per : (l > 0 ? c->resid[l & 1] : nullptr));
@@ -574,7 +608,8 @@ moe_status moe_decoder_stack(moe_ctx* c, const moe_layer_weights* layers, const 
   for (int l = 0; l <= L; ++l) {
     // x_l = (stream after the previous attention half) + (previous MoE term); normalise for this block's attention
     ChainArgs a = base;
-    a.partial = l > 0 ? c->partial : nullptr;
+    a.partial = l > 0 && ks > 0 ? c->partial : nullptr;
+    a.moe_out = l > 0 && ks == 0 ? c->partial : nullptr;  // ks == 0: the fused down projection already summed the term
     a.KS = ks;
     a.resid_in = cur;
     float* dst = l == L ? x_out : (trace_opt ? trace_opt + (size_t)l * per : (l > 0 ? c->resid[l & 1] : nullptr));
