@@ -2,6 +2,7 @@
 // per-head core of the attention stub.  Part of the single translation unit moe_kernels.hip.
 #pragma once
 #include "moe_common.h"
+#include "route_kernels.h"
 
 namespace {
 
@@ -28,7 +29,7 @@ struct ChainArgs {
 constexpr int kChainThreads = 1024;
 constexpr int kChainVecs = 4;  // float4 per thread: d <= 4 * 4 * 1024
 
-__global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) {
+__device__ __forceinline__ void chain_body(const ChainArgs& g) {
   __shared__ float s_ss[kChainThreads / 64];
   const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int per_tok = g.d >> 2;
@@ -92,6 +93,20 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) {
       }
     }
   }
+}
+
+__global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs g) { chain_body(g); }
+
+// The same pass followed, in the same launch, by the router of the block it has just normalised for: both are one
+// workgroup of 1024 threads per token, and the router reads exactly what this workgroup has written (c.xn_out ==
+// r.hidden), so a workgroup barrier is all that lies between them.  Saves one launch per block in the chained stacks.
+// Requires c.gamma != NULL.
+static_assert(kChainThreads == 64 * kRouteWaves, "chain_route_kernel runs both bodies on one workgroup shape");
+__global__ __launch_bounds__(kChainThreads) void chain_route_kernel(ChainArgs c, RouteArgs r, GroupArgs grp) {
+  chain_body(c);
+  __threadfence_block();
+  __syncthreads();
+  route_body(r, grp);
 }
 
 // ------------------------------------------------------------------------------------------

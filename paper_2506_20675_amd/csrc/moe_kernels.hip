@@ -184,13 +184,18 @@ void mark(moe_ctx* c, hipStream_t st) {
 }
 
 // Steps 1 and 2.  ids / gates / unique / n_unique / n_unique_extra: optional DEVICE outputs.
+// pre != NULL (chained stacks): the slab sum + residual + RMSNorm pass that produces `hidden` runs first — inside
+// the router's launch when the router is the one-workgroup-per-token kernel.
 void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* router_w, int T, int32_t* ids,
-                            float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st) {
+                            float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
+                            const ChainArgs* pre = nullptr) {
   const moe_shape& s = c->s;
   RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, s.gate_mode, c->ids, ids, c->gates, gates,
                c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
                c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
+  if (pre && s.n_experts >= kWideRouterExperts)
+    hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre);
   if (s.n_experts >= kWideRouterExperts) {
     // many experts: logits over (token, 16 experts) workgroups, then one workgroup for top-k + union (measured
     // faster than the one-workgroup-per-token router even for a single token, where it costs a launch more)
@@ -199,7 +204,10 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
     hipLaunchKernelGGL(topk_group_kernel, dim3(1), dim3(1024), 0, st, ra, ga, (const double*)c->logits);
     return;
   }
-  hipLaunchKernelGGL(route_kernel, dim3(T), dim3(64 * kRouteWaves), 0, st, ra, ga);
+  if (pre)
+    hipLaunchKernelGGL(chain_route_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre, ra, ga);
+  else
+    hipLaunchKernelGGL(route_kernel, dim3(T), dim3(64 * kRouteWaves), 0, st, ra, ga);
   if (T > 1) hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, st, ga);  // T = 1: done inside route_kernel
 }
 
@@ -236,13 +244,13 @@ void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipS
 // split-K factor they were written with.
 moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
                         float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
-                        int* ks_used = nullptr) {
+                        int* ks_used = nullptr, const ChainArgs* pre = nullptr) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
   if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;  // FP8 is streamed in the tiled layout only
   const Plan p = plan_for(c, T, tiled, fp8);
   mark(c, st);
-  launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st);
+  launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st, pre);
   mark(c, st);
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
@@ -545,11 +553,14 @@ moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const 
     a.xn_out = c->xn;
     a.d = s.d, a.T = T, a.top_k = s.top_k, a.u_max = c->u_max, a.n_shared = s.n_shared, a.max_tokens = s.max_tokens;
     a.KS = ks, a.eps = eps;
-    if (l > 0 || dst || a.gamma) hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, a);
     if (dst) cur = dst;
-    if (l == L) break;
+    if (l == L) {  // the last MoE term and nothing to normalise for
+      hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, a);
+      break;
+    }
+    // this pass runs at the head of block l's router launch (or as a launch of its own in front of a wide router)
     if (moe_status rc = launch_layer(c, layers + l, c->xn, T, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks))
+                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks, &a))
       return rc;
   }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
@@ -632,10 +643,9 @@ moe_status moe_decoder_stack(moe_ctx* c, const moe_layer_weights* layers, const 
     m.resid_in = c->hbuf;
     m.gamma = attn[l].gamma_moe;
     m.xn_out = c->xn;
-    hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, m);
     cur = c->hbuf;
     if (moe_status rc = launch_layer(c, layers + l, c->xn, T, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks))
+                                     n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks, &m))
       return rc;
   }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;

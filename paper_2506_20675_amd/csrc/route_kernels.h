@@ -247,7 +247,7 @@ __device__ __forceinline__ void route_tail(const float* __restrict__ x, const ui
 // logits in fp32, summed in pick order.  With a single token in flight (T = 1, no speculation) this
 // workgroup already sees the whole routing, so the expert-union step runs right here; with more
 // tokens it needs the launch of its own that follows (group_kernel).
-__global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, GroupArgs grp) {
+__device__ __forceinline__ void route_body(const RouteArgs& g, const GroupArgs& grp) {
   __shared__ double s_part[kRouteWaves][kMaxExperts];
   __shared__ double s_logit[kMaxExperts];
   __shared__ int s_ids[kMaxTopK];
@@ -311,6 +311,8 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
   }
   if (gridDim.x == 1) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
 }
+
+__global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, GroupArgs grp) { route_body(g, grp); }
 
 // ------------------------------------------------------------------------------------------
 // Wide routers (many experts).  One workgroup per token cannot do E * d fp64 multiply-adds on the router weights
