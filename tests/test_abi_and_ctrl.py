@@ -116,3 +116,21 @@ def test_c_controller_rejects_bad_observations():
         binding.CascadeController(k_start=9)
     with pytest.raises(ValueError):
         binding.CascadeController(t_trial=0)
+
+
+def test_header_is_plain_c11_and_structs_match_the_binding(tmp_path):
+    """The boundary is a C ABI: the header must compile as C11 on its own, and the ctypes mirrors of its structs must
+    have the sizes the C compiler gives them."""
+    import ctypes
+    import os
+    import subprocess
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "cascade_moe.h"\n'
+                   'int main(void) { printf("%zu %zu %zu %zu\\n", sizeof(moe_shape), sizeof(moe_layer_weights), '
+                   'sizeof(moe_attn_weights), sizeof(cascade_params)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c11", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe)], check=True)
+    sizes = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert sizes == [ctypes.sizeof(binding.MoeShape), ctypes.sizeof(binding.MoeLayerWeights),
+                     ctypes.sizeof(binding.MoeAttnWeights), ctypes.sizeof(binding.CascadeParams)]
