@@ -821,3 +821,27 @@ def test_decoder_stack_teacher_forced_and_free_running():
     assert err.value.status == -1
     plain.close()
     ctx.close()
+
+
+def test_stack_driver_chained_and_decoder_modes_run_under_the_controller():
+    """The decode loop in its two chained forms on a small stack: every iteration gets a K from the C controller, a
+    positive verification time and 1 .. K+1 tokens; the recorded trace replays on the policy oracle."""
+    import torch
+    from oracle import cascade_oracle as co
+    from paper_2506_20675_amd import stack_driver
+    cfg = synth.TINY
+    H, Hkv, dh = synth.attn_geometry(cfg)
+    L = 3
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, synth.K_MAX + 1, 0, H, Hkv, dh)
+    stack = stack_driver.build_stack(cfg, L, ctx, "tiled")
+    pool = stack_driver.HiddenPool(cfg, L, 0.5, n_pool=2)
+    gammas = [_dev(synth.norm_gamma_host(cfg, l)) for l in range(L)]
+    attn = [_attn_dev(ctx, synth.attn_weights_host(cfg, l)) for l in range(L)]
+    for kw in (dict(gammas=gammas), dict(attn=attn)):
+        summary, recs = stack_driver.run(cfg, layers=L, iters=60, ctx=ctx, stack=stack, pool=pool, **kw)
+        assert summary["chained"] and summary["attention_stub"] == ("attn" in kw)
+        ref = co.Controller()
+        for r in recs:
+            assert ref.next_k() == r["K"] and r["t_verify_ms"] > 0 and 1 <= r["tokens"] <= r["K"] + 1
+            ref.observe(r["K"], r["tokens"], r["t_verify_ms"] * 1e-3)
+    ctx.close()
