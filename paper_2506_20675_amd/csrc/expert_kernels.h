@@ -15,7 +15,8 @@ struct GateupArgs {
   const uint16_t *xf_hi, *xf_lo;        // activation fragments, d*16 elements each
   const int32_t* n_unique;              // [1]        size of the union                   } written by the
   const int32_t* slot_expert;           // [u_max]    expert of slot u (ascending)        } grouping step
-  const float* slot_gate;               // [u_max+n_shared, 16] gate of token column n, 0 = not routed
+  const int32_t* slot_mask;             // [u_max]    bit t set: token t is routed to slot u
+  const float* slot_gate;               // [u_max+n_shared, 16] gate of token column n
   uint16_t *hf_hi, *hf_lo;              // [u_max + n_shared] fragments of gate*silu(G)*U, ffn*16 elements each
   int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
 };
@@ -29,12 +30,15 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   const float *S1 = nullptr, *S3 = nullptr;  // FP8: scale rows of this expert
   const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
   float gate;
+  bool routed;  // token column r's token goes through this expert (its gate may still be 0 after underflow)
+  const int col = PK ? (r & (kPackedTokens - 1)) : r;
   int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
   if (slot < g.routed_slots) {
-    // three independent loads (one round trip); the tables are in bounds for every slot of the grid
+    // independent loads (one round trip); the tables are in bounds for every slot of the grid
     const int nu = *g.n_unique;
     const int e = g.slot_expert[slot];
-    gate = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)];
+    gate = g.slot_gate[slot * kGateCols + col];
+    routed = (g.slot_mask[slot] >> col) & 1;
     if (slot >= nu) return;  // beyond the union of this step
     W1 = reinterpret_cast<const char*>(g.w1) + e * per;
     W3 = reinterpret_cast<const char*>(g.w3) + e * per;
@@ -44,6 +48,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
     }
   } else {
     gate = 1.f;  // shared expert: every token, gate 1
+    routed = true;
     const int sh = slot - g.routed_slots;
     W1 = reinterpret_cast<const char*>(g.sw1) + sh * per;
     W3 = reinterpret_cast<const char*>(g.sw3) + sh * per;
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       G.x *= c1.x, G.y *= c1.y, G.z *= c1.z, G.w *= c1.w;
       U.x *= c3.x, U.y *= c3.y, U.z *= c3.z, U.w *= c3.w;
     }
-    if (r < g.T && (!PK || r < kPackedTokens) && gate != 0.f) {
+    if (r < g.T && (!PK || r < kPackedTokens) && routed) {
       // lane holds rows 4*kg .. 4*kg+3 of the tile for token column r: four consecutive k of the
       // down projection, i.e. one half of a 16-byte fragment unit
       uint16_t hi[4], lo[4];
@@ -171,7 +176,7 @@ struct DownArgs {
   const uint16_t *hf_hi, *hf_lo;  // [u_max + n_shared] fragments, ffn*16 elements each
   const int32_t* n_unique;
   const int32_t* slot_expert;
-  const float* slot_gate;
+  const int32_t* slot_mask;
   float* partial;                 // [(u_max + n_shared)*KS, max_tokens, d]
   int d, ffn, T, routed_slots, u_max, max_tokens, KS;
 };
@@ -190,8 +195,8 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   if (slot < g.routed_slots) {
     const int nu = *g.n_unique;  // three independent loads, one round trip
     const int e = g.slot_expert[slot];
-    // 0 also for the padded columns r >= T; packed: column n + 8 belongs to token n
-    live = g.slot_gate[slot * kGateCols + (PK ? (r & (kPackedTokens - 1)) : r)] != 0.f;
+    // clear also for the padded columns r >= T; packed: column n + 8 belongs to token n
+    live = (g.slot_mask[slot] >> (PK ? (r & (kPackedTokens - 1)) : r)) & 1;
     if (slot >= nu) return;
     W2 = reinterpret_cast<const char*>(g.w2) + e * per;
     if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
@@ -304,7 +309,7 @@ struct DownFusedArgs {
   const uint16_t *hf_hi, *hf_lo;
   const int32_t* n_unique;
   const int32_t* slot_expert;
-  const float* slot_gate;
+  const int32_t* slot_mask;
   float* out;  // [T, d]
   int d, ffn, T, n_shared, u_max, C;  // C = k-chunks per slot
 };
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
     bool live;
     if (sl < nu) {
       const int e = g.slot_expert[sl];
-      live = g.slot_gate[sl * kGateCols + col] != 0.f;
+      live = (g.slot_mask[sl] >> col) & 1;
       W2 = reinterpret_cast<const char*>(g.w2) + e * per;
       if constexpr (FP8) S2 = g.s2 + (size_t)e * g.d;
       hslot = sl;

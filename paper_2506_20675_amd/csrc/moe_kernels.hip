@@ -89,7 +89,7 @@ struct moe_ctx {
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
-  int32_t *ids, *n_unique, *slot_expert, *tok_slot;
+  int32_t *ids, *n_unique, *slot_expert, *tok_slot, *slot_mask;
   float *gates, *slot_gate, *partial;
   float *xn, *resid[2];  // chained stack: normalised router input and the residual stream (ping-pong), [max_tokens, d]
   double* logits;        // wide routers: fp64 logits [max_tokens, E] between logits_kernel and topk_group_kernel
@@ -193,7 +193,7 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
   RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, s.gate_mode, c->ids, ids, c->gates, gates,
                c->xf_hi, c->xf_lo};
   GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
-               c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_gate};
+               c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_mask, c->slot_gate};
   if (pre && s.n_experts >= kWideRouterExperts)
     hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre);
   if (s.n_experts >= kWideRouterExperts) {
@@ -254,7 +254,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   mark(c, st);
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
-                c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_gate,
+                c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_mask, c->slot_gate,
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
   const bool pk = T <= kPackedTokens;  // must match what route_kernel wrote
   if (fp8) {
@@ -282,7 +282,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     // down projection and combine in one launch; with no `out` (chained stack) the summed term goes to the slab
     // buffer as a plain [T, d] array and *ks_used = 0 tells the caller so
     DownFusedArgs fa{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
-                     c->slot_gate, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C};
+                     c->slot_mask, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C};
     const dim3 grid(s.d / 16), block(64 * kFusedWaves);
     if (fp8) {
       if (pk) hipLaunchKernelGGL((down_fused_kernel<4, true, true>), grid, block, 0, st, fa);
@@ -297,7 +297,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
   }
   DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
-              c->slot_gate, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
+              c->slot_mask, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
     case 4: launch_down<4, 4>(c, da, tiled, fp8, st); break;
     case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
@@ -414,6 +414,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
   const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
   const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
+  const size_t o_sm = carve((size_t)c->u_max * 4);
   const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
   const size_t o_xn = carve((size_t)s.max_tokens * s.d * 4);
   const size_t o_r0 = carve((size_t)s.max_tokens * s.d * 4), o_r1 = carve((size_t)s.max_tokens * s.d * 4);
@@ -437,6 +438,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->slot_expert = reinterpret_cast<int32_t*>(c->ws + o_se);
   c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
   c->tok_slot = reinterpret_cast<int32_t*>(c->ws + o_ts);
+  c->slot_mask = reinterpret_cast<int32_t*>(c->ws + o_sm);
   c->partial = reinterpret_cast<float*>(c->ws + o_part);
   c->xn = reinterpret_cast<float*>(c->ws + o_xn);
   c->resid[0] = reinterpret_cast<float*>(c->ws + o_r0);
@@ -489,7 +491,7 @@ moe_status moe_group(moe_ctx* c, const int32_t* ids, int32_t T, int32_t* unique_
   if (!c || !ids || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c)) return st;
   GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, unique_experts, n_unique, expert_count, expert_offset,
-               assign, nullptr, nullptr, nullptr, nullptr, nullptr};
+               assign, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ga);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }

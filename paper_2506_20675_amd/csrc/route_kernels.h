@@ -16,7 +16,8 @@ struct GroupArgs {
   int32_t *unique, *n_unique, *count, *offset, *assign;     // caller-visible outputs, each optional
   int32_t *n_unique_ws, *n_unique_extra, *slot_expert;      // tables for the expert kernels, each optional
   int32_t* tok_slot;                                        // [T, top_k] slot of the union each pick landed in
-  float* slot_gate;                                         // [u_max, 16]
+  int32_t* slot_mask;                                       // [u_max] bit t set: token t is routed to the slot
+  float* slot_gate;                                         // [u_max, 16] its gate there (may be 0: see slot_mask)
 };
 
 // Every thread of the workgroup must call this (it holds barriers); blockDim.x >= 256.
@@ -84,6 +85,7 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
       s_rank[e] = rank;
       if (g.unique) g.unique[rank] = e;
       if (g.slot_expert) g.slot_expert[rank] = e;
+      if (g.slot_mask) g.slot_mask[rank] = (int32_t)m;  // routed-ness is kept apart from the gate: a gate can underflow to 0
       if (g.assign) {
         int j = 0;
         while (m) {

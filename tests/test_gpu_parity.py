@@ -845,3 +845,29 @@ def test_stack_driver_chained_and_decoder_modes_run_under_the_controller():
             assert ref.next_k() == r["K"] and r["t_verify_ms"] > 0 and 1 <= r["tokens"] <= r["K"] + 1
             ref.observe(r["K"], r["tokens"], r["t_verify_ms"] * 1e-3)
     ctx.close()
+
+
+def test_gate_that_underflows_to_zero_still_counts_as_routed(monkeypatch):
+    """Hidden states far from unit scale make the router's logit gaps so large that the weaker picks' gates underflow
+    to exactly 0.  Such a pick is still a pick: its expert is in the union, and it contributes 0 * FFN = 0 — not
+    whatever an unwritten buffer holds.  Checked on the fused and on the split-K down path."""
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 9)
+    x = (synth.hidden_host(cfg, 9, 0, 5, 0.5) * np.float32(300.0)).astype(np.float32)
+    ref64, rids, rgates = orc.layer(x, W, cfg.top_k, 0, "f64")
+    assert (rgates[:, 1] == 0.0).any(), "the case is meant to have underflowed gates"
+    Wd = _weights_dev(W)
+    for no_fused in (False, True):
+        if no_fused:
+            monkeypatch.setenv("MOE_NO_FUSED_DOWN", "1")
+        ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+        for tiled in (False, True):
+            for rep in range(2):      # twice: the second run meets the first one's leftovers in the workspace
+                out, ids, gates, uniq, nu = _run_layer(ctx, Wd, x if rep == 0 else x[::-1].copy(), tiled)
+            want = ref64[::-1]
+            np.testing.assert_array_equal(ids, rids[::-1])
+            assert nu == orc.union(rids, cfg.n_experts)["n_unique"]
+            assert np.isfinite(out).all()
+            err = out.astype(np.float64) - want
+            assert np.sqrt((err ** 2).sum() / (want ** 2).sum()) <= 5e-5
+        ctx.close()
