@@ -204,7 +204,7 @@ def main():
         "metric": "unique-expert GB/s (MoE verify step, sum of unique-expert weight bytes / time); latency/layer vs K in by_K",
         "value": round(float(value), 1), "unit": "GB/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": round(wall / K_steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "fp8_e4m3" if fp8 else "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",   # MFMA operand type (FP8 codes are widened to bf16)
         "config": {"workload": f"{cfg.name} MoE layer d={cfg.d} E={cfg.n_experts} top{cfg.top_k} ffn={cfg.ffn} "
                                f"shared={cfg.n_shared}, {'FP8 E4M3 + per-row scale' if fp8 else 'bf16'} weights, T=K+1 with K "
                                + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
