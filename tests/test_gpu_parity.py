@@ -308,6 +308,43 @@ def test_stack_matches_per_layer_oracle():
     ctx.close()
 
 
+def test_stack_full_size_sampled_layers_match_the_oracle():
+    """The 32-layer Mixtral-shaped stack as the stack driver runs it (90 GB of device-generated weights, tiled,
+    one moe_verify_stack call per T); the oracle regenerates the weights of layers 0, 15 and 31 from the seed and
+    checks those layers' whole outputs and union sizes at T = 1, 4 and 9."""
+    import torch
+    from paper_2506_20675_amd import stack_driver
+    cfg, L, sample = synth.MIXTRAL, 32, (0, 15, 31)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 100 * 2**30:
+        pytest.skip("needs 100 GB of free device memory")
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    stack = stack_driver.build_stack(cfg, L, ctx, layout="tiled")
+    x9 = np.stack([synth.hidden_host(cfg, l, 700, 9, 0.5) for l in range(L)])   # rows are nested in T
+    outs = {}
+    for T in (1, 4, 9):
+        out = torch.full((L, T, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+        nu = torch.full((L,), -7, dtype=torch.int32, device="cuda")
+        ctx.moe_verify_stack(stack, _dev(np.ascontiguousarray(x9[:, :T])), out, nu)
+        torch.cuda.synchronize()
+        outs[T] = (out.cpu().numpy(), nu.cpu().numpy())
+        assert np.isfinite(outs[T][0]).all()
+    del stack
+    ctx.close()
+    torch.cuda.empty_cache()
+    for l in sample:
+        W = synth.layer_weights_host(cfg, l)
+        for T in (1, 4, 9):
+            x = np.ascontiguousarray(x9[l, :T])
+            ref32, rids, _ = orc.layer(x, W, cfg.top_k, 0, "f32")
+            ref64, _, _ = orc.layer(x, W, cfg.top_k, 0, "f64")
+            _check_out(outs[T][0][l], ref32, ref64)
+            assert int(outs[T][1][l]) == orc.union(rids, cfg.n_experts)["n_unique"]
+    # every layer's union is possible for its T, not only the sampled ones
+    for T in (1, 4, 9):
+        assert ((outs[T][1] >= cfg.top_k) & (outs[T][1] <= min(cfg.n_experts, T * cfg.top_k))).all()
+
+
 def test_argument_errors_are_reported_not_launched():
     import torch
     ctx = binding.MoeContext(64, 64, 4, 2, 0, 4)
