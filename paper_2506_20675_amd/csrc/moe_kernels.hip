@@ -269,7 +269,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
     const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
     if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 6, true, true, false, true>), grid, dim3(64), 0, st, ga);
-    else hipLaunchKernelGGL((gateup_kernel<1, 1, 8, true, true, false, false>), grid, dim3(64), 0, st, ga);
+    else hipLaunchKernelGGL((gateup_kernel<1, 1, 6, true, true, false, false>), grid, dim3(64), 0, st, ga);
   } else {
     switch (p.gu_R) {
       case 4: launch_gateup<4, 2>(c, ga, st); break;
