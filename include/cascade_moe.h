@@ -239,6 +239,30 @@ moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);
  * published HBM peak. */
 moe_status moe_stream_read_probe(const void* src, int64_t bytes, float* sink, void* stream);
 
+/* The launch plan moe_verify_layer would use for T tokens in flight on a layer of this shape, layout
+ * (MOE_LAYOUT_*) and weight type (MOE_WEIGHT_*).  Pure host arithmetic (no device, no context): the plan
+ * depends only on its arguments, because the union of experts the T tokens form (Section 2.4) is known on
+ * the device only and the grids are sized for the largest union they could form.
+ *   routed_slots     expert slots the grids cover besides the shared experts: min(n_experts, T*top_k)
+ *   expected_slots   live slots expected under uniform routing, shared experts included (balls into bins)
+ *   wide_router      1: logits over (token, 16 experts) workgroups + one top-k/grouping workgroup; 0: one workgroup
+ *                    per token (+ a grouping launch when T > 1)
+ *   packed_fragments 1: T <= 8, the bf16 hi and lo halves of the activations share one MFMA operand
+ *   gu_tiles         16-row tile pairs of w1/w3 per wavefront in the gate/up kernel
+ *   dn_tiles         16-row tiles of w2 per wavefront in the down kernel
+ *   dn_split_k       k-chunks of the down projection across workgroups (slabs per slot)
+ *   dn_fused_chunks  > 0: down projection and combine run as one launch with this many k-chunks per slot
+ *                    (small unions of small experts); dn_tiles / dn_split_k are then unused
+ *   launches         kernel launches of one moe_verify_layer call
+ * Errors: MOE_ERR_INVALID_ARG for NULL pointers, T outside 1..max_tokens or unknown layout / dtype;
+ * MOE_ERR_UNSUPPORTED_SHAPE as moe_ctx_create, and for FP8 when d or ffn is not a multiple of 64;
+ * MOE_ERR_UNIMPLEMENTED for row-major FP8. */
+typedef struct {
+  int32_t routed_slots, wide_router, packed_fragments, gu_tiles, dn_tiles, dn_split_k, dn_fused_chunks, launches;
+  double expected_slots;
+} moe_plan_info;
+moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int32_t dtype, moe_plan_info* out);
+
 /* ----------------------------------------------------------------------------------------
  * Host side — pure C, no device.
  * -------------------------------------------------------------------------------------- */

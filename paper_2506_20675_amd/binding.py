@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
            "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
-           "moe_stream_read_probe",
+           "moe_stream_read_probe", "moe_plan_query",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
            "cascade_next_k", "cascade_observe", "cascade_get_state")
@@ -45,6 +45,12 @@ class MoeLayerWeights(ctypes.Structure):
 
 class MoeAttnWeights(ctypes.Structure):
     _fields_ = [(n, c_void_p) for n in ("wqkv", "wo", "gamma_attn", "gamma_moe")]
+
+
+class MoePlanInfo(ctypes.Structure):
+    _fields_ = ([(n, c_int32) for n in ("routed_slots", "wide_router", "packed_fragments", "gu_tiles", "dn_tiles",
+                                        "dn_split_k", "dn_fused_chunks", "launches")]
+                + [("expected_slots", ctypes.c_double)])
 
 
 MOE_LAYOUT_ROW_MAJOR, MOE_LAYOUT_TILED = 0, 1
@@ -110,6 +116,8 @@ def lib():
     L.moe_ctx_profile.argtypes = [c_void_p, c_int32]
     L.moe_ctx_profile_read.restype = ctypes.c_int
     L.moe_ctx_profile_read.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64)]
+    L.moe_plan_query.restype = ctypes.c_int
+    L.moe_plan_query.argtypes = [ctypes.POINTER(MoeShape), c_int32, c_int32, c_int32, ctypes.POINTER(MoePlanInfo)]
     L.moe_stream_read_probe.restype = ctypes.c_int
     L.moe_stream_read_probe.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.cascade_utility.restype = c_double
@@ -385,6 +393,15 @@ class AttnWeights:
     def __init__(self, wqkv_tiled, wo_tiled, gamma_attn, gamma_moe):
         self.tensors = (wqkv_tiled, wo_tiled, gamma_attn, gamma_moe)
         self.c = MoeAttnWeights(*[t.data_ptr() for t in self.tensors])
+
+
+def moe_plan_query(d, ffn, n_experts, top_k, n_shared=0, max_tokens=9, T=1, layout=MOE_LAYOUT_TILED,
+                   dtype=MOE_WEIGHT_BF16, gate_mode=0, n_heads=0, n_kv_heads=0, head_dim=0) -> dict:
+    """Launch plan of one layer-step (host arithmetic only; needs no GPU)."""
+    shape = MoeShape(d, ffn, n_experts, top_k, n_shared, max_tokens, gate_mode, n_heads, n_kv_heads, head_dim)
+    info = MoePlanInfo()
+    _check(lib().moe_plan_query(ctypes.byref(shape), T, layout, dtype, ctypes.byref(info)), "moe_plan_query")
+    return {n: getattr(info, n) for n, _ in MoePlanInfo._fields_}
 
 
 def moe_stream_read_probe(src, sink, stream=None):

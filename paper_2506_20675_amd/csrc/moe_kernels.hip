@@ -124,12 +124,16 @@ int ks_cap_for(const moe_shape& s, bool fp8) {
   return cap;
 }
 
-Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
-  const moe_shape& s = c->s;
-  // expected number of live expert slots for T tokens under uniform routing (balls into bins)
+// expected number of live expert slots for T tokens under uniform routing (balls into bins), shared experts included
+double expected_slots(const moe_shape& s, int T) {
   double miss = 1.0;
   for (int t = 0; t < T; ++t) miss *= 1.0 - (double)s.top_k / s.n_experts;
-  const double slots = s.n_experts * (1.0 - miss) + s.n_shared;
+  return s.n_experts * (1.0 - miss) + s.n_shared;
+}
+
+// plan_override: three ints (guR, dnR, dnKS), zeros = automatic
+Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, int T, bool tiled, bool fp8) {
+  const double slots = expected_slots(s, T);
   Plan p;
   p.gu_R = tiled ? 1 : ((s.ffn / 16 / 2) * kWaves * slots >= 1536 ? 2 : 1);
   const int cap = ks_cap_for(s, fp8);
@@ -155,17 +159,52 @@ Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
   // to 16 waves; every item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
-  if (tiled && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes && !c->no_fused_down) {
+  if (tiled && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes && !no_fused_down) {
     int C = 1;
     while (slots * C < 2 * kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
     p.dn_fused_C = C;
   }
-  if (c->plan_override[0] > 0) {
-    p.gu_R = c->plan_override[0];
-    p.dn_R = c->plan_override[1];
-    p.dn_KS = c->plan_override[2] < cap ? c->plan_override[2] : cap;
+  if (plan_override[0] > 0) {
+    p.gu_R = plan_override[0];
+    p.dn_R = plan_override[1];
+    p.dn_KS = plan_override[2] < cap ? plan_override[2] : cap;
   }
   return p;
+}
+Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
+  return plan_for(c->s, c->plan_override, c->no_fused_down, T, tiled, fp8);
+}
+
+// tuning overrides from the environment: MOE_PLAN="guR,dnR,dnKS", MOE_NO_FUSED_DOWN
+void plan_env(int* plan_override, bool* no_fused_down) {
+  plan_override[0] = plan_override[1] = plan_override[2] = 0;
+  *no_fused_down = getenv("MOE_NO_FUSED_DOWN") != nullptr;
+  if (const char* env = getenv("MOE_PLAN")) {
+    int a = 0, b = 0, k = 0;
+    if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
+        k >= 1 && k <= kMaxKS) {
+      plan_override[0] = a;
+      plan_override[1] = b;
+      plan_override[2] = k;
+    }
+  }
+}
+
+moe_status validate_shape(const moe_shape& s) {
+  if (s.d < 32 || s.ffn < 32 || s.n_experts < 1 || s.top_k < 1 || s.n_shared < 0 || s.max_tokens < 1)
+    return MOE_ERR_INVALID_ARG;
+  if (s.top_k > s.n_experts) return MOE_ERR_INVALID_ARG;
+  if (s.gate_mode != MOE_GATE_RENORM_TOPK && s.gate_mode != MOE_GATE_SOFTMAX_ALL) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads < 0 || s.n_kv_heads < 0 || s.head_dim < 0) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads == 0 && (s.n_kv_heads != 0 || s.head_dim != 0)) return MOE_ERR_INVALID_ARG;
+  if (s.n_heads > 0) {
+    if (s.n_kv_heads < 1 || s.n_heads % s.n_kv_heads) return MOE_ERR_INVALID_ARG;
+    if (s.head_dim < 32 || s.head_dim > 128 || s.head_dim % 32 || s.n_heads > 1024) return MOE_ERR_UNSUPPORTED_SHAPE;
+  }
+  if (s.d % 32 || s.ffn % 32 || s.n_experts > kMaxExperts || s.top_k > kMaxTopK || s.n_shared > kMaxShared ||
+      s.max_tokens > kMaxTokens || (int64_t)s.d * s.ffn > (int64_t)1 << 30)
+    return MOE_ERR_UNSUPPORTED_SHAPE;
+  return MOE_OK;
 }
 
 moe_status check_stream_device(const moe_ctx* c) {
@@ -360,19 +399,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (out) *out = nullptr;
   if (!shape || !out) return MOE_ERR_INVALID_ARG;
   const moe_shape s = *shape;
-  if (s.d < 32 || s.ffn < 32 || s.n_experts < 1 || s.top_k < 1 || s.n_shared < 0 || s.max_tokens < 1)
-    return MOE_ERR_INVALID_ARG;
-  if (s.top_k > s.n_experts) return MOE_ERR_INVALID_ARG;
-  if (s.gate_mode != MOE_GATE_RENORM_TOPK && s.gate_mode != MOE_GATE_SOFTMAX_ALL) return MOE_ERR_INVALID_ARG;
-  if (s.n_heads < 0 || s.n_kv_heads < 0 || s.head_dim < 0) return MOE_ERR_INVALID_ARG;
-  if (s.n_heads == 0 && (s.n_kv_heads != 0 || s.head_dim != 0)) return MOE_ERR_INVALID_ARG;
-  if (s.n_heads > 0) {
-    if (s.n_kv_heads < 1 || s.n_heads % s.n_kv_heads) return MOE_ERR_INVALID_ARG;
-    if (s.head_dim < 32 || s.head_dim > 128 || s.head_dim % 32 || s.n_heads > 1024) return MOE_ERR_UNSUPPORTED_SHAPE;
-  }
-  if (s.d % 32 || s.ffn % 32 || s.n_experts > kMaxExperts || s.top_k > kMaxTopK || s.n_shared > kMaxShared ||
-      s.max_tokens > kMaxTokens || (int64_t)s.d * s.ffn > (int64_t)1 << 30)
-    return MOE_ERR_UNSUPPORTED_SHAPE;
+  if (moe_status st = validate_shape(s)) return st;
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
   moe_ctx* c = new (std::nothrow) moe_ctx();
@@ -381,17 +408,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->device = dev;
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
-  c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
-  c->no_fused_down = getenv("MOE_NO_FUSED_DOWN") != nullptr;
-  if (const char* env = getenv("MOE_PLAN")) {  // tuning override: "guR,dnR,dnKS"
-    int a = 0, b = 0, k = 0;
-    if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
-        k >= 1 && k <= kMaxKS) {
-      c->plan_override[0] = a;
-      c->plan_override[1] = b;
-      c->plan_override[2] = k;
-    }
-  }
+  plan_env(c->plan_override, &c->no_fused_down);
   // the slab buffer is sized for the largest split-K factor any T can ask for
   c->ks_alloc = 1;
   for (int T = 1; T <= s.max_tokens; ++T)
@@ -476,6 +493,33 @@ moe_status moe_ctx_destroy(moe_ctx* c) {
 }
 
 int64_t moe_ctx_workspace_bytes(const moe_ctx* c) { return c ? (int64_t)c->ws_bytes : 0; }
+
+moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int32_t dtype, moe_plan_info* out) {
+  if (!shape || !out) return MOE_ERR_INVALID_ARG;
+  const moe_shape s = *shape;
+  if (moe_status st = validate_shape(s)) return st;
+  if (T < 1 || T > s.max_tokens) return MOE_ERR_INVALID_ARG;
+  if (layout != MOE_LAYOUT_ROW_MAJOR && layout != MOE_LAYOUT_TILED) return MOE_ERR_INVALID_ARG;
+  if (dtype != MOE_WEIGHT_BF16 && dtype != MOE_WEIGHT_FP8_E4M3) return MOE_ERR_INVALID_ARG;
+  const bool tiled = layout == MOE_LAYOUT_TILED, fp8 = dtype == MOE_WEIGHT_FP8_E4M3;
+  if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;
+  if (fp8 && (s.d % 64 || s.ffn % 64)) return MOE_ERR_UNSUPPORTED_SHAPE;
+  int override[3];
+  bool no_fused;
+  plan_env(override, &no_fused);
+  const Plan p = plan_for(s, override, no_fused, T, tiled, fp8);
+  out->routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;
+  out->expected_slots = expected_slots(s, T);
+  out->wide_router = s.n_experts >= kWideRouterExperts;
+  out->packed_fragments = T <= kPackedTokens;
+  out->gu_tiles = fp8 ? 2 : (tiled ? 1 : p.gu_R);  // tiled gate/up kernels have fixed shapes (see launch_layer)
+  out->dn_tiles = p.dn_R;
+  out->dn_split_k = p.dn_KS;
+  out->dn_fused_chunks = p.dn_fused_C;
+  const int route_launches = out->wide_router ? 2 : (T > 1 ? 2 : 1);
+  out->launches = route_launches + 1 + (p.dn_fused_C > 0 ? 1 : 2);
+  return MOE_OK;
+}
 
 moe_status moe_route(moe_ctx* c, const float* hidden, const uint16_t* router_w, int32_t T, int32_t* ids, float* gates,
                      int32_t* unique_experts, int32_t* n_unique, void* stream) {

@@ -127,10 +127,58 @@ def test_header_is_plain_c11_and_structs_match_the_binding(tmp_path):
     inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
     src = tmp_path / "sizes.c"
     src.write_text('#include <stdio.h>\n#include "cascade_moe.h"\n'
-                   'int main(void) { printf("%zu %zu %zu %zu\\n", sizeof(moe_shape), sizeof(moe_layer_weights), '
-                   'sizeof(moe_attn_weights), sizeof(cascade_params)); return 0; }\n')
+                   'int main(void) { printf("%zu %zu %zu %zu %zu\\n", sizeof(moe_shape), sizeof(moe_layer_weights), '
+                   'sizeof(moe_attn_weights), sizeof(cascade_params), sizeof(moe_plan_info)); return 0; }\n')
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-std=c11", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe)], check=True)
     sizes = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert sizes == [ctypes.sizeof(binding.MoeShape), ctypes.sizeof(binding.MoeLayerWeights),
-                     ctypes.sizeof(binding.MoeAttnWeights), ctypes.sizeof(binding.CascadeParams)]
+                     ctypes.sizeof(binding.MoeAttnWeights), ctypes.sizeof(binding.CascadeParams),
+                     ctypes.sizeof(binding.MoePlanInfo)]
+
+
+def test_launch_plan_is_host_arithmetic_with_sane_invariants():
+    """moe_plan_query needs no device.  For every benchmark shape, weight type and T: the split-K factor is a power of
+    two that leaves every wave at least 4 k-steps, the workspace rule (slabs per slot <= 16) holds, tile counts are
+    from the instantiated set, the fused down + combine launch is chosen only while the expected down-projection
+    bytes stay under its 36 MB limit, and the launch count follows from the choices."""
+    from paper_2506_20675_amd import synth
+    seen_fused = seen_split = False
+    for cfg in (synth.TINY, synth.MIXTRAL, synth.OLMOE, synth.DEEPSEEK, synth.PHI35, synth.QWEN15):
+        for dtype in (binding.MOE_WEIGHT_BF16, binding.MOE_WEIGHT_FP8_E4M3):
+            for layout in (binding.MOE_LAYOUT_TILED, binding.MOE_LAYOUT_ROW_MAJOR):
+                if dtype == binding.MOE_WEIGHT_FP8_E4M3 and layout == binding.MOE_LAYOUT_ROW_MAJOR:
+                    with pytest.raises(binding.MoeError):
+                        binding.moe_plan_query(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 16, 1, layout, dtype)
+                    continue
+                prev_slots = 0.0
+                for T in range(1, 17):
+                    p = binding.moe_plan_query(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 16, T, layout, dtype)
+                    assert p["routed_slots"] == min(cfg.n_experts, T * cfg.top_k)
+                    assert cfg.top_k + cfg.n_shared <= p["expected_slots"] + 1e-9 <= p["routed_slots"] + cfg.n_shared + 1e-9
+                    assert p["expected_slots"] > prev_slots            # more tokens in flight, larger union (Section 2.4)
+                    prev_slots = p["expected_slots"]
+                    assert p["wide_router"] == (cfg.n_experts >= 32) and p["packed_fragments"] == (T <= 8)
+                    assert p["gu_tiles"] in (1, 2, 4) and p["dn_tiles"] in (1, 2, 4)
+                    ks, nsteps = p["dn_split_k"], cfg.ffn // (64 if dtype else 32)
+                    assert 1 <= ks <= 16 and ks & (ks - 1) == 0
+                    assert ks == 1 or nsteps // (4 * ks) >= 4
+                    bytes_dn = p["expected_slots"] * cfg.d * cfg.ffn * (1 if dtype else 2)
+                    if p["dn_fused_chunks"] > 0:
+                        seen_fused = True
+                        assert layout == binding.MOE_LAYOUT_TILED and bytes_dn <= 36 * 2**20
+                        assert nsteps // p["dn_fused_chunks"] >= 8 or p["dn_fused_chunks"] == 1   # >= 8 k-steps per item
+                    else:
+                        seen_split = True
+                        assert layout == binding.MOE_LAYOUT_ROW_MAJOR or bytes_dn > 36 * 2**20
+                    router = 2 if (p["wide_router"] or T > 1) else 1
+                    assert p["launches"] == router + 1 + (1 if p["dn_fused_chunks"] > 0 else 2)
+    assert seen_fused and seen_split
+    # the Mixtral-shaped layer without speculation: four launches, four slabs per slot
+    p = binding.moe_plan_query(4096, 14336, 8, 2, 0, 9, 1)
+    assert (p["launches"], p["dn_split_k"], p["dn_tiles"], p["dn_fused_chunks"]) == (4, 4, 4, 0)
+    for bad in (dict(T=0), dict(T=10), dict(layout=7), dict(dtype=5)):
+        with pytest.raises(binding.MoeError):
+            binding.moe_plan_query(4096, 14336, 8, 2, 0, 9, **{"T": 1, **bad})
+    with pytest.raises(binding.MoeError):
+        binding.moe_plan_query(4096, 14336 + 32, 8, 2, 0, 9, 1, dtype=binding.MOE_WEIGHT_FP8_E4M3)  # FP8 needs ffn % 64
