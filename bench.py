@@ -189,16 +189,33 @@ def main():
         Wh = synth.layer_weights_fp8_host(cfg, 0) if fp8 else synth.layer_weights_host(cfg, 0)
         sample_T = tuple(range(1, T_MAX + 1)) + (T_MAX,)
         cbytes, csec = 0, 0.0
+        max_err, err2, ref2, ids_equal = 0.0, 0.0, 0.0, True
         for n, T in enumerate(sample_T):
             x = synth.hidden_host(cfg, 0, 10_000 + n, T, args.rho)
             c0 = time.perf_counter()
-            _, rids, _ = (orc.layer_fp8 if fp8 else orc.layer)(x, Wh, cfg.top_k, cfg.n_shared, "f32", cfg.gate_mode)
+            ref, rids, _ = (orc.layer_fp8 if fp8 else orc.layer)(x, Wh, cfg.top_k, cfg.n_shared, "f32", cfg.gate_mode)
             csec += time.perf_counter() - c0
             cbytes += (orc.union(rids, cfg.n_experts)["n_unique"] + cfg.n_shared) * expert_bytes
+            # the same step through the library, in the launch configuration that was timed above
+            ids_d = torch.full((T, cfg.top_k), -1, dtype=torch.int32, device="cuda")
+            ctx.moe_verify_layer(lw[0], torch.from_numpy(x).cuda(), outs[0][:T], ids=ids_d)
+            torch.cuda.synchronize()
+            err = outs[0][:T].cpu().numpy().astype(np.float64) - ref
+            max_err = max(max_err, float(np.abs(err).max()))
+            err2 += float((err ** 2).sum())
+            ref2 += float((ref.astype(np.float64) ** 2).sum())
+            ids_equal = ids_equal and bool((ids_d.cpu().numpy() == rids).all())
+        rel_rms = (err2 / ref2) ** 0.5
         cpu = {"value": round(cbytes / csec / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"fp32 oracle, layer 0, rho={args.rho}, one layer-step each at T in {list(sample_T)}; "
                          f"{csec:.1f} s of CPU time; host has {os.cpu_count()} logical cores",
-               "ms_per_step": round(csec / len(sample_T) * 1e3, 1)}
+               "ms_per_step": round(csec / len(sample_T) * 1e3, 1),
+               "parity": {"steps": len(sample_T), "ids_equal": ids_equal, "max_abs_err": float(f"{max_err:.3e}"),
+                          "rel_rms": float(f"{rel_rms:.3e}")}}
+        if not (ids_equal and max_err <= 2e-2 and rel_rms <= 1e-2):
+            print("bench.py: the library's output left the parity bar against the oracle: " + json.dumps(cpu["parity"]),
+                  file=sys.stderr)
+            sys.exit(1)
 
     res = {
         "metric": "unique-expert GB/s (MoE verify step, sum of unique-expert weight bytes / time); latency/layer vs K in by_K",
