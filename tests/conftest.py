@@ -12,6 +12,14 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
 
 
+def pytest_sessionstart(session):
+    """The tests load the libraries that are built; only when none is there (a fresh clone) they are built first."""
+    from paper_2506_20675_amd import binding, synth
+    if not (os.path.exists(binding.LIB_PATH) and os.path.exists(synth.synth_lib_path())):
+        import __graft_entry__
+        __graft_entry__.build()
+
+
 def _has_gpu() -> bool:
     try:
         import torch
