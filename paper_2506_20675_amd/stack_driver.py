@@ -142,6 +142,65 @@ def run(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, layout="tiled", seed_f
     return summary, recs
 
 
+def run_concurrent(cfg=synth.MIXTRAL, layers=32, iters=600, rho=0.5, requests=2, static_k=None, ctx=None, stack=None,
+                   pool=None, layout="tiled", weights="bf16"):
+    """R requests decoded together, each with its own controller and its own acceptance trace (seed field r):
+    every iteration verifies the in-flight tokens of all requests in ONE pass over the stack, T = sum(K_r + 1) <= 16,
+    so a request that speculates also lengthens the others' iteration — every controller sees the joint t_verify
+    (paper: Section 5.1, one speculation manager per request; Section 6, per-request K).
+    static_k = None: controllers; an int: that K for every request.  Returns (summary, records)."""
+    import torch
+    t_cap = 16
+    k_max = t_cap // requests - 1
+    if requests < 1 or k_max < 1:
+        raise ValueError("1 <= requests <= 8")
+    own = ctx is None
+    if own:
+        ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, t_cap, cfg.gate_mode)
+    if stack is None:
+        stack = build_stack(cfg, layers, ctx, layout, weights=weights)
+    if pool is None:
+        pool = HiddenPool(cfg, layers, rho, t_max=t_cap)
+    ctrls = None
+    if static_k is None:
+        ctrls = [binding.CascadeController(k_max=k_max, k_start=min(3, k_max)) for _ in range(requests)]
+    elif not 0 <= static_k <= k_max:
+        raise ValueError(f"static K must be in 0..{k_max} for {requests} requests")
+    regimes = [synth.regime_sequence(iters, r) for r in range(requests)]
+    uni = [synth.acceptance_uniforms(iters, r) for r in range(requests)]
+    out = torch.empty((layers, t_cap, cfg.d), dtype=torch.float32, device="cuda")
+    nu = torch.zeros((layers,), dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ctx.moe_verify_stack(stack, pool.get(0, t_cap), out, nu)   # warm-up: every layer once at the largest T
+    torch.cuda.synchronize()
+    recs = []
+    for i in range(iters):
+        ks = [c.next_k() for c in ctrls] if ctrls else [static_k] * requests
+        T = sum(k + 1 for k in ks)
+        o = out[:, :T].contiguous() if T != t_cap else out
+        e0.record()
+        ctx.moe_verify_stack(stack, pool.get(i, T), o, nu)
+        e1.record()
+        e1.synchronize()
+        t_verify = e0.elapsed_time(e1) * 1e-3
+        toks = [synth.tokens_emitted(uni[r][i], regimes[r][i], ks[r]) for r in range(requests)]
+        if ctrls:
+            for r in range(requests):
+                ctrls[r].observe(ks[r], toks[r], t_verify)
+        recs.append({"iter": i, "K": ks, "T": T, "tokens": toks, "t_verify_ms": t_verify * 1e3})
+    tok = sum(sum(r["tokens"]) for r in recs)
+    tv = sum(r["t_verify_ms"] for r in recs)
+    summary = {"policy": "cascade" if static_k is None else f"static K={static_k}", "requests": requests, "k_max": k_max,
+               "layers": layers, "iters": iters, "rho": rho, "tokens": tok, "t_verify_total_ms": round(tv, 3),
+               "ms_per_token": round(tv / tok, 4), "tokens_per_s": round(tok / (tv * 1e-3), 1),
+               "mean_T": round(float(np.mean([r["T"] for r in recs])), 3),
+               "mean_K_per_request": [round(float(np.mean([r["K"][q] for r in recs])), 3) for q in range(requests)],
+               "tokens_per_request": [sum(r["tokens"][q] for r in recs) for q in range(requests)]}
+    if own:
+        ctx.close()
+    return summary, recs
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="mixtral-8x7b-shaped")
@@ -156,8 +215,28 @@ def main(argv=None):
                     help="full decoder blocks: attention stub + MoE, each feeding the next (moe_decoder_stack)")
     ap.add_argument("--chained", action="store_true",
                     help="pre-norm residual blocks feeding each other (moe_chained_stack) instead of independent inputs")
+    ap.add_argument("--requests", type=int, default=1,
+                    help="decode this many requests together, one controller each (independent-input stack only)")
     a = ap.parse_args(argv)
     cfg = synth.CONFIGS[a.config]
+    if a.requests > 1:
+        if a.chained or a.decoder:
+            ap.error("--requests runs the independent-input stack")
+        ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 16, cfg.gate_mode)
+        stack = build_stack(cfg, a.layers, ctx, a.layout, weights=a.weights)
+        pool = HiddenPool(cfg, a.layers, a.rho, t_max=16)
+        res = {"cascade": run_concurrent(cfg, a.layers, a.iters, a.rho, a.requests, None, ctx, stack, pool)[0]}
+        for k in [int(v) for v in a.static.split(",") if v != ""]:
+            res[f"static_{k}"] = run_concurrent(cfg, a.layers, a.iters, a.rho, a.requests, k, ctx, stack, pool)[0]
+        base = res.get("static_0")
+        if base:
+            for v in res.values():
+                v["speedup_vs_no_spec"] = round(base["ms_per_token"] / v["ms_per_token"], 4)
+        for v in res.values():
+            v["weights"] = a.weights
+        print(json.dumps(res))
+        ctx.close()
+        return 0
     H, Hkv, dh = synth.attn_geometry(cfg) if a.decoder else (0, 0, 0)
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, synth.K_MAX + 1, cfg.gate_mode,
                              H, Hkv, dh)

@@ -884,6 +884,29 @@ def test_stack_driver_chained_and_decoder_modes_run_under_the_controller():
     ctx.close()
 
 
+def test_concurrent_requests_share_one_pass_and_keep_their_own_controllers():
+    """Two and four requests decoded together on a small stack: the in-flight tokens of all requests go through one
+    pass (T = sum(K_r + 1) <= 16), and every request's K sequence replays on the policy oracle fed with that request's
+    own tokens and the joint iteration time."""
+    from oracle import cascade_oracle as co
+    from paper_2506_20675_amd import stack_driver
+    cfg = synth.TINY
+    for R in (2, 4):
+        summary, recs = stack_driver.run_concurrent(cfg, layers=3, iters=120, rho=0.5, requests=R, layout="row")
+        k_max = 16 // R - 1
+        assert summary["k_max"] == k_max and summary["tokens"] >= 120 * R
+        assert all(r["T"] == sum(k + 1 for k in r["K"]) <= 16 and max(r["K"]) <= k_max for r in recs)
+        for q in range(R):
+            ref = co.Controller(co.Params(k_max=k_max, k_start=min(3, k_max)))
+            for r in recs:
+                assert ref.next_k() == r["K"][q]
+                assert 1 <= r["tokens"][q] <= r["K"][q] + 1
+                ref.observe(r["K"][q], r["tokens"][q], r["t_verify_ms"] * 1e-3)
+        assert [r["K"] for r in recs[:4]] == [[0] * R] * 4          # every request starts with its baseline window
+    s0, _ = stack_driver.run_concurrent(cfg, layers=3, iters=20, rho=0.5, requests=2, static_k=2, layout="row")
+    assert s0["mean_T"] == 6.0 and s0["mean_K_per_request"] == [2.0, 2.0]
+
+
 def test_gate_that_underflows_to_zero_still_counts_as_routed(monkeypatch):
     """Hidden states far from unit scale make the router's logit gaps so large that the weaker picks' gates underflow
     to exactly 0.  Such a pick is still a pick: its expert is in the union, and it contributes 0 * FFN = 0 — not
