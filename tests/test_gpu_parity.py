@@ -931,3 +931,68 @@ def test_gate_that_underflows_to_zero_still_counts_as_routed(monkeypatch):
             err = out.astype(np.float64) - want
             assert np.sqrt((err ** 2).sum() / (want ** 2).sum()) <= 5e-5
         ctx.close()
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_valid_configurations_match_the_oracle(block):
+    """48 seeded random draws over everything a caller may legally combine: d and ffn at the granularity of the
+    weight type, 1 .. 256 experts (narrow and wide routers, top_k up to 16), 0 .. 8 shared experts, 1 .. 16 tokens,
+    both gate rules, bf16 in both layouts or FP8, token correlation 0 / 0.5 / 1.  Each is run twice on one context
+    (the second run meets the first one's workspace) and compared with the fp64 oracle: ids, gates, union, output.
+    (The same generator passed 1200 draws when this test was written.)"""
+    import torch
+    codes = synth.code_table_e4m3()
+    for seed in range(12 * block, 12 * block + 12):
+        rng = np.random.default_rng(seed)
+        fp8 = bool(rng.integers(0, 2))
+        q = 64 if fp8 else 32
+        d, ffn = int(rng.integers(1, 9)) * q, int(rng.integers(1, 13)) * q
+        E = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 32, 33, 60, 64, 100, 256]))
+        k = int(rng.integers(1, min(E, 16) + 1))
+        if rng.random() < 0.5:
+            k = min(k, 4)
+        ns, T, gm = int(rng.choice([0, 0, 1, 2, 8])), int(rng.integers(1, 17)), int(rng.integers(0, 2))
+        tiled = True if fp8 else bool(rng.integers(0, 2))
+        rho = float(rng.choice([0.0, 0.5, 1.0]))
+        case = f"seed={seed} fp8={fp8} d={d} ffn={ffn} E={E} k={k} ns={ns} T={T} gate_mode={gm} tiled={tiled} rho={rho}"
+        bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+        qm = lambda shape: codes[rng.integers(0, len(codes), shape)]
+        sc = lambda shape: (rng.uniform(0.5, 1.5, shape) * 2e-3).astype(np.float32)
+        W = dict(router_w=bf(rng.normal(0, 0.3, (E, d))))
+        if fp8:
+            W.update(q1=qm((E, ffn, d)), q3=qm((E, ffn, d)), q2=qm((E, d, ffn)), s1=sc((E, ffn)), s3=sc((E, ffn)), s2=sc((E, d)))
+            if ns:
+                W.update(sq1=qm((ns, ffn, d)), sq3=qm((ns, ffn, d)), sq2=qm((ns, d, ffn)),
+                         ss1=sc((ns, ffn)), ss3=sc((ns, ffn)), ss2=sc((ns, d)))
+        else:
+            W.update(w1=bf(rng.normal(0, 0.1, (E, ffn, d))), w3=bf(rng.normal(0, 0.1, (E, ffn, d))),
+                     w2=bf(rng.normal(0, 0.1, (E, d, ffn))))
+            if ns:
+                W.update(sw1=bf(rng.normal(0, 0.1, (ns, ffn, d))), sw3=bf(rng.normal(0, 0.1, (ns, ffn, d))),
+                         sw2=bf(rng.normal(0, 0.1, (ns, d, ffn))))
+        x = (np.sqrt(rho) * rng.normal(size=(1, d)) + np.sqrt(1 - rho) * rng.normal(size=(T, d))).astype(np.float32)
+        ref64, rids, rgates = (orc.layer_fp8 if fp8 else orc.layer)(x, W, k, ns, "f64", gm)
+        _, _, logits = orc.route(x, W["router_w"], k, "f64")
+        srt = np.sort(logits, axis=1)[:, ::-1][:, :min(k + 1, E)]
+        assert srt.shape[1] < 2 or np.abs(np.diff(srt, axis=1)).min() > 1e-9, case + ": routing near-tie, change the seed"
+        ctx = binding.MoeContext(d, ffn, E, k, ns, max_tokens=16, gate_mode=gm)
+        lw = ctx.weights({n: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for n, v in W.items()})
+        if tiled:
+            lw = ctx.moe_pack_weights(lw)
+        out = torch.full((T, d), float("nan"), dtype=torch.float32, device="cuda")
+        ids = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+        gates = torch.zeros((T, k), dtype=torch.float32, device="cuda")
+        uniq = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+        nu = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            ctx.moe_verify_layer(lw, _dev(x), out, ids, gates, uniq, nu)
+        torch.cuda.synchronize()
+        o, u = out.cpu().numpy(), orc.union(rids, E)
+        assert np.isfinite(o).all(), case
+        np.testing.assert_array_equal(ids.cpu().numpy(), rids, err_msg=case)
+        assert int(nu.item()) == u["n_unique"], case
+        np.testing.assert_array_equal(uniq.cpu().numpy(), u["unique"], err_msg=case)
+        assert np.abs(gates.cpu().numpy() - rgates).max() <= 1e-5, case
+        err = o.astype(np.float64) - ref64
+        assert np.sqrt((err ** 2).sum()) <= 5e-5 * np.sqrt((ref64 ** 2).sum()), case
+        ctx.close()
