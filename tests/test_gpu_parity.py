@@ -1102,3 +1102,49 @@ def test_one_context_many_calls_leftovers_never_matter():
             checked += 1
         assert checked >= 35
         ctx.close()
+
+
+def test_measurement_aids_profile_and_stream_probe():
+    """The two measurement aids the benchmark relies on.  Per-kernel profiling: the outputs stay bit-identical with the
+    events in the stream, the number of profiled layer-steps is what was run, every stage that has a launch shows
+    time, and a read empties the record.  Read-stream probe: every 32-bit word of the buffer reaches the sink exactly
+    once (the sink's XOR fold equals the host's), also for sizes that leave waves without work or with a ragged tail."""
+    import torch
+    cfg = synth.TINY
+    W = synth.layer_weights_host(cfg, 12)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    lw = ctx.moe_pack_weights(ctx.weights(_weights_dev(W)))
+    xs = [_dev(synth.hidden_host(cfg, 12, it, T, 0.5)) for it, T in enumerate((1, 4, 9))]
+    plain = []
+    for x in xs:
+        o = torch.zeros((x.shape[0], cfg.d), dtype=torch.float32, device="cuda")
+        ctx.moe_verify_layer(lw, x, o)
+        plain.append(o)
+    torch.cuda.synchronize()
+    ctx.moe_ctx_profile(True)
+    for rep in range(2):
+        for x, want in zip(xs, plain):
+            o = torch.zeros_like(want)
+            ctx.moe_verify_layer(lw, x, o)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(o.cpu().numpy(), want.cpu().numpy())
+    ms, steps = ctx.moe_ctx_profile_read()
+    assert steps == 6 and set(ms) == {"route", "gateup", "down", "combine"}
+    assert ms["route"] > 0 and ms["gateup"] > 0 and ms["down"] > 0 and ms["combine"] >= 0
+    assert sum(ms.values()) < 50.0                                   # six tiny layer-steps: far below 50 ms
+    assert ctx.moe_ctx_profile_read()[1] == 0                        # the read forgot the events
+    ctx.moe_ctx_profile(False)
+    o = torch.zeros_like(plain[0])
+    ctx.moe_verify_layer(lw, xs[0], o)
+    torch.cuda.synchronize()
+    assert ctx.moe_ctx_profile_read()[1] == 0                        # nothing is recorded when switched off
+    ctx.close()
+    rng = np.random.default_rng(5)
+    for n_words in (4, 4 * 64, 4 * 64 * 4096 + 4 * 7, 3_000_000 * 4):
+        host = rng.integers(0, 2**32, n_words, dtype=np.uint32)
+        src = torch.from_numpy(host.view(np.int32)).cuda()
+        sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+        binding.moe_stream_read_probe(src, sink)
+        torch.cuda.synchronize()
+        fold = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        assert fold == np.bitwise_xor.reduce(host), n_words
