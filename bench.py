@@ -46,6 +46,11 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    fp8 = args.weights == "fp8"
+    if fp8 and args.layout != "tiled":
+        print("bench.py: FP8 weights are streamed in the tiled layout only", file=sys.stderr)
+        sys.exit(2)
+
     import torch
     from paper_2506_20675_amd import binding, synth
 
@@ -55,10 +60,6 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
-    fp8 = args.weights == "fp8"
-    if fp8 and args.layout != "tiled":
-        print("bench.py: FP8 weights are streamed in the tiled layout only", file=sys.stderr)
-        sys.exit(2)
     expert_bytes = cfg.expert_bytes_fp8 if fp8 else cfg.expert_bytes
     L, K_steps, W_steps = args.layers, args.steps, args.warmup
     T_MAX = 9
