@@ -170,18 +170,22 @@ def main():
     roofline["down_kernel_GBps"] = round(dn_bytes / (kms["down"] / max(n_prof, 1) * 1e-3) / 1e9, 1)
 
     # ---- the box's plain read-stream rate, as a second denominator ---------------------------
+    # one launch over 8 GB (so that the ~8 us a launch costs whatever it does are below 1 %), data that has not
+    # been read before; best of three passes
     sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
-    probe = [lw[l].tensors[i] for l in range(min(L, 4)) for i in (1, 2)]
-    for t in probe[:2]:
-        binding.moe_stream_read_probe(t, sink)
+    probe = torch.empty(2 << 30, dtype=torch.int32, device="cuda")
+    probe.random_()
+    binding.moe_stream_read_probe(lw[0].tensors[1], sink)          # warm the kernel itself on other data
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for t in probe:
-        binding.moe_stream_read_probe(t, sink)
-    e1.record()
-    torch.cuda.synchronize()
-    stream_gbs = sum(t.numel() * t.element_size() for t in probe) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    stream_gbs = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.moe_stream_read_probe(probe, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        stream_gbs = max(stream_gbs, probe.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del probe
 
     # ---- CPU oracle beside it (bounded sample, single thread) ---------------------------------
     cpu = None
