@@ -234,7 +234,8 @@ moe_status moe_ctx_profile(moe_ctx* ctx, int32_t enable);
 moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);
 
 /* Measurement aid: read `bytes` (multiple of 16) of DEVICE memory at `src` once with contiguous
- * non-temporal 128-bit loads (each wavefront streams its own chunk) and fold them into `sink` (DEVICE,
+ * non-temporal 128-bit loads (each wavefront streams its own chunk, the wavefronts starting at staggered
+ * offsets of their chunks and wrapping around) and fold them into `sink` (DEVICE,
  * >= 4096 words).  Used only to report the box's achievable read-stream bandwidth next to the
  * published HBM peak. */
 moe_status moe_stream_read_probe(const void* src, int64_t bytes, float* sink, void* stream);
