@@ -24,6 +24,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+TRAFFIC_TAG = {"mixtral-8x7b-shaped": "mixtral", "olmoe-like": "olmoe", "deepseek-v2-lite-like": "deepseek"}
+BY_K_STEPS = 20        # layer-steps per K in the latency-vs-K table (a sample of its own, independent of --steps)
 
 
 def main():
@@ -40,6 +42,8 @@ def main():
                     help="expert weight storage: tiled = re-ordered once at load time by moe_pack_weights")
     ap.add_argument("--weights", choices=("bf16", "fp8"), default="bf16",
                     help="expert weight type: bf16 (the headline workload) or fp8 = E4M3 codes + per-row scales")
+    ap.add_argument("--tune", default="", help="tuning aid: gu_tiles,dn_tiles,dn_split_k,fused_down for moe_ctx_tune "
+                                                 "(0,0,0,-1 = the automatic plan)")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build is single-GPU (no sharding, no collectives); --gpus {args.gpus} is not supported",
@@ -66,6 +70,8 @@ def main():
 
     # ---- resident inputs -------------------------------------------------------------------
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, T_MAX, cfg.gate_mode)
+    if args.tune:
+        ctx.moe_ctx_tune(*[int(v) for v in args.tune.split(",")])
     lw = []
     for l in range(L):
         # row-major, as the oracle sees them
@@ -104,45 +110,53 @@ def main():
     wall = time.perf_counter() - t0
 
     nu_h = nu.cpu().numpy()[W_steps:]
-    ks = np.array([k_of(W_steps + j) for j in range(K_steps)])
     ubytes = (nu_h.astype(np.int64) + cfg.n_shared) * expert_bytes
     value = ubytes.sum() / wall / 1e9
 
-    # ---- latency per layer vs K: the timed steps again, grouped by K, one event pair per group ----
-    # (an event between every two steps would put an extra packet into each kernel chain)
+    # ---- latency per layer vs K: a sample of its own, BY_K_STEPS steps per K whatever --steps is -----------
+    # One event pair around each group of BY_K_STEPS steps (an event between every two steps would put an extra
+    # packet into each kernel chain, and a pair around two or three steps would not amortise its own latency).
+    k_list = [args.fixed_k] if args.fixed_k >= 0 else list(range(T_MAX))
+    sample = {k: [(j % L, 50_000 + 100 * k + j) for j in range(BY_K_STEPS)] for k in k_list}
+    s_hid = {k: [torch.from_numpy(synth.hidden_host(cfg, l, it, k + 1, args.rho)).cuda() for l, it in sample[k]]
+             for k in k_list}
+    s_nu = torch.zeros((len(k_list), BY_K_STEPS), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+
+    def sample_step(ki, k, j):
+        ctx.moe_verify_layer(lw[sample[k][j][0]], s_hid[k][j], outs[j & 1][:k + 1], n_unique=s_nu[ki, j:j + 1])
+
     by_k = {}
-    for k in sorted(set(ks.tolist())):
-        idx = [W_steps + j for j in range(K_steps) if ks[j] == k]
+    for ki, k in enumerate(k_list):
         reps = []
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for i in idx:
-                step(i)
+            for j in range(BY_K_STEPS):
+                sample_step(ki, k, j)
             e1.record()
             torch.cuda.synchronize()
-            reps.append(e0.elapsed_time(e1) / len(idx))
+            reps.append(e0.elapsed_time(e1) / BY_K_STEPS)
         lat_ms = float(np.median(reps))
-        m = ks == k
-        gbs = float(ubytes[m].mean()) / (lat_ms * 1e-3) / 1e9
-        by_k[str(k)] = {"latency_us": round(lat_ms * 1e3, 1), "mean_unique": round(float(nu_h[m].mean()), 2),
-                        "unique_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
-    # spread of single steps: one event pair per step (each pair puts extra packets into the chain, so these
-    # run ~3 us above the grouped figure; they are reported for the p10/p90 spread only)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
-    for j in range(K_steps):
-        evs[j][0].record()
-        step(W_steps + j)
-        evs[j][1].record()
-    torch.cuda.synchronize()
-    single = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
-    for k in by_k:
-        v = single[ks == int(k)]
-        by_k[k]["single_step_us_p10_p50_p90"] = [round(float(np.percentile(v, q)), 1) for q in (10, 50, 90)]
+        # spread of single steps: one event pair per step (each pair puts extra packets into the chain, so these
+        # run a few us above the grouped figure; they are reported for the p10/p90 spread only)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(BY_K_STEPS)]
+        for j in range(BY_K_STEPS):
+            evs[j][0].record()
+            sample_step(ki, k, j)
+            evs[j][1].record()
+        torch.cuda.synchronize()
+        single = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+        nu_k = s_nu[ki].cpu().numpy().astype(np.int64)
+        gbs = float(((nu_k + cfg.n_shared) * expert_bytes).mean()) / (lat_ms * 1e-3) / 1e9
+        by_k[str(k)] = {"latency_us": round(lat_ms * 1e3, 1), "mean_unique": round(float(nu_k.mean()), 2),
+                        "unique_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                        "single_step_us_p10_p50_p90": [round(float(np.percentile(single, q)), 1) for q in (10, 50, 90)]}
     k0 = by_k.get("0", {}).get("latency_us")
     if k0:
         for k in by_k:
             by_k[k]["t_verify_over_t0"] = round(by_k[k]["latency_us"] / k0, 3)
+    del s_hid
 
     # ---- roofline of the dominant kernel: same steps again with per-kernel events ------------
     ctx.moe_ctx_profile(True)
@@ -158,14 +172,21 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_us": round(gu_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(gu_bytes_per_launch),
                 "kernel_us_per_step": {k: round(v / max(n_prof, 1) * 1e3, 2) for k, v in kms.items()}}
-    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same default
-    # workload (summary committed under profiles/); reported only when the run matches that workload
-    traffic_file = os.path.join(ROOT, "profiles", f"gateup_kernel_mixtral{'_fp8' if fp8 else ''}_hbm_traffic.txt")
-    if (cfg is synth.MIXTRAL and args.layout == "tiled" and args.rho == 0.5 and args.fixed_k < 0 and L == 8
-            and K_steps == 180 and os.path.exists(traffic_file)):
-        for line in open(traffic_file):
+    # HBM bytes per launch: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE cannot run inside this process, so the figure is
+    # DERIVED from the committed counter run on this workload (profiles/): its measured traffic / algorithmic ratio
+    # of the gate/up kernel times this run's algorithmic bytes per launch
+    traffic_file = os.path.join("profiles", f"gateup_kernel_{TRAFFIC_TAG.get(cfg.name, cfg.name)}{'_fp8' if fp8 else ''}_hbm_traffic.txt")
+    if args.layout == "tiled" and os.path.exists(os.path.join(ROOT, traffic_file)):
+        t_b = a_b = None
+        for line in open(os.path.join(ROOT, traffic_file)):
             if line.startswith("traffic_bytes_per_launch gateup_kernel"):
-                roofline["traffic"] = int(line.split()[-1])
+                t_b = int(line.split()[-1])
+            elif line.startswith("algorithmic bytes per launch"):
+                a_b = int(line.split("=")[-1])
+        if t_b and a_b:
+            roofline["traffic"] = int(round(t_b / a_b * gu_bytes_per_launch))
+            roofline["traffic_source"] = (f"derived: traffic/algorithmic = {t_b / a_b:.4f} measured with rocprofv3 --pmc "
+                                          f"FETCH_SIZE, WRITE_SIZE ({traffic_file}) x this run's algorithmic bytes per launch")
     dn_bytes = float((nu_h.astype(np.int64) + cfg.n_shared).mean()) * expert_bytes / 3
     roofline["down_kernel_GBps"] = round(dn_bytes / (kms["down"] / max(n_prof, 1) * 1e-3) / 1e9, 1)
 

@@ -25,6 +25,11 @@
  *    ctx per stream, and do not overlap calls on the same ctx from different streams.
  *  - The library never falls back to the CPU: without a usable GPU every device call fails with
  *    MOE_ERR_HIP.
+ *  - The library reads no environment variable.  Two families of calls are aids and not part of the
+ *    path, and are the only exceptions to the rules above: moe_ctx_tune changes the launch plan of one
+ *    context (tuning and tests; the plan moe_plan_query reports is the automatic one), and while
+ *    moe_ctx_profile is switched on every layer-step creates HIP event objects (host-side allocations)
+ *    and records them between its kernels, which moe_ctx_profile_read waits for and frees.
  */
 #ifndef CASCADE_MOE_H
 #define CASCADE_MOE_H
@@ -80,6 +85,16 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out);
 moe_status moe_ctx_destroy(moe_ctx* ctx);
 /* Bytes of device workspace held by the context. */
 int64_t moe_ctx_workspace_bytes(const moe_ctx* ctx);
+
+/* Tuning aid: override parts of the launch plan of THIS context for all later calls (what moe_plan_query
+ * describes; the kernels and their results per element are the same, only the split of the work changes).
+ *   gu_tiles, dn_tiles  0 = automatic, or 1, 2, 4 (gu_tiles is honoured for row-major weights only: the
+ *                       tiled gate/up kernels have one fixed shape per weight type)
+ *   dn_split_k          0 = automatic, or a power of two <= 16; clamped to what the shape allows and to the
+ *                       largest split the workspace was sized for at creation
+ *   fused_down          -1 = automatic, 0 = never fuse the down projection with the combine
+ * Host only, no device work.  MOE_ERR_INVALID_ARG for any other value. */
+moe_status moe_ctx_tune(moe_ctx* ctx, int32_t gu_tiles, int32_t dn_tiles, int32_t dn_split_k, int32_t fused_down);
 
 /* Step 1 — router logits, top-k, gates, and the union of activated experts (Section 2.1: a small
  * gating network selects a few experts per token; Section 1 / 2.2: the in-flight tokens together

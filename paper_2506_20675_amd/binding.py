@@ -18,7 +18,7 @@ MOE_OK = 0
 STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAPE", -3: "MOE_ERR_WORKSPACE",
                 -4: "MOE_ERR_HIP", -5: "MOE_ERR_UNIMPLEMENTED"}
 
-EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes",
+EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes", "moe_ctx_tune",
            "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
            "moe_stream_read_probe", "moe_plan_query",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
@@ -92,6 +92,8 @@ def lib():
     L.moe_ctx_destroy.argtypes = [c_void_p]
     L.moe_ctx_workspace_bytes.restype = c_int64
     L.moe_ctx_workspace_bytes.argtypes = [c_void_p]
+    L.moe_ctx_tune.restype = ctypes.c_int
+    L.moe_ctx_tune.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32]
     L.moe_route.restype = ctypes.c_int
     L.moe_route.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.moe_group.restype = ctypes.c_int
@@ -213,6 +215,7 @@ class LayerWeights:
                     raise ValueError(f"{name} required for FP8 weights")
                 _want(t, torch.float32, shp, name)
         self.dtype = dtype
+        self.geometry = (d, f, E, ns)        # the tensors were checked against these sizes
         self.c = MoeLayerWeights(*[None if t is None else t.data_ptr() for t in self.tensors], layout, dtype,
                                  *[None if t is None else t.data_ptr() for t in self.scales])
 
@@ -237,6 +240,15 @@ class MoeContext:
         except Exception:
             pass
 
+    def _same_geometry(self, *layers) -> None:
+        """The library sees raw pointers: weights validated for another geometry would be read out of bounds."""
+        s = self.shape
+        mine = (s.d, s.ffn, s.n_experts, s.n_shared)
+        for lw in layers:
+            if lw.geometry != mine:
+                raise ValueError(f"layer weights were built for (d, ffn, E, n_shared) = {lw.geometry}, "
+                                 f"this context is {mine}")
+
     @property
     def workspace_bytes(self) -> int:
         return int(lib().moe_ctx_workspace_bytes(self._h))
@@ -250,6 +262,9 @@ class MoeContext:
                                 scales=(W["s1"], W["s3"], W["s2"], W.get("ss1"), W.get("ss3"), W.get("ss2")))
         return LayerWeights(self.shape, W["router_w"], W["w1"], W["w3"], W["w2"], W.get("sw1"), W.get("sw3"),
                             W.get("sw2"))
+
+    def moe_ctx_tune(self, gu_tiles=0, dn_tiles=0, dn_split_k=0, fused_down=-1) -> None:
+        _check(lib().moe_ctx_tune(self._h, gu_tiles, dn_tiles, dn_split_k, fused_down), "moe_ctx_tune")
 
     KERNELS = ("route", "gateup", "down", "combine")
 
@@ -266,6 +281,7 @@ class MoeContext:
     def moe_pack_weights(self, src: LayerWeights, stream=None, in_place_of=None) -> LayerWeights:
         """Re-layout src (row-major) into freshly allocated tiled buffers; returns the tiled LayerWeights."""
         import torch
+        self._same_geometry(src)
         bufs = [None if t is None else torch.empty_like(t) for t in src.tensors]
         bufs[0] = src.tensors[0]            # router is shared, it stays row-major
         dst = LayerWeights(self.shape, *bufs, layout=0, dtype=src.dtype, scales=src.scales)
@@ -311,6 +327,7 @@ class MoeContext:
         _want(gates, torch.float32, (T, s.top_k), "gates")
         _want(unique_experts, torch.int32, (s.n_experts,), "unique_experts")
         _want(n_unique, torch.int32, (1,), "n_unique")
+        self._same_geometry(weights)
         _check(lib().moe_verify_layer(self._h, byref(weights.c), _ptr(hidden), T, _ptr(out), _ptr(ids), _ptr(gates),
                                       _ptr(unique_experts), _ptr(n_unique), _stream_ptr(stream)), "moe_verify_layer")
 
@@ -323,6 +340,7 @@ class MoeContext:
         _want(hidden, torch.float32, (L, T, s.d), "hidden")
         _want(out, torch.float32, (L, T, s.d), "out")
         _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
+        self._same_geometry(*layers)
         arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
         _check(lib().moe_verify_stack(self._h, arr, L, _ptr(hidden), T, _ptr(out), _ptr(n_unique_per_layer),
                                       _stream_ptr(stream)), "moe_verify_stack")
@@ -342,6 +360,7 @@ class MoeContext:
         _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
         for g in gammas:
             _want_bf16(g, (s.d,), "gamma")
+        self._same_geometry(*layers)
         arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
         garr = (c_void_p * L)(*[g.data_ptr() for g in gammas])
         _check(lib().moe_chained_stack(self._h, arr, garr, L, _ptr(x_in), T, ctypes.c_float(eps), _ptr(x_out),
@@ -381,6 +400,7 @@ class MoeContext:
         _want(x_out, torch.float32, (T, s.d), "x_out")
         _want(trace, torch.float32, (L, T, s.d), "trace")
         _want(n_unique_per_layer, torch.int32, (L,), "n_unique_per_layer")
+        self._same_geometry(*layers)
         arr = (MoeLayerWeights * L)(*[lw.c for lw in layers])
         aarr = (MoeAttnWeights * L)(*[a.c for a in attn])
         _check(lib().moe_decoder_stack(self._h, arr, aarr, L, _ptr(x_in), T, ctypes.c_float(eps), _ptr(x_out),

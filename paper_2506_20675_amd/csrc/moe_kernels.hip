@@ -89,8 +89,8 @@ struct moe_ctx {
   int device;
   int u_max;              // largest possible union: min(E, max_tokens * top_k)
   int ks_alloc;           // split-K slabs the partial buffer is sized for
-  int plan_override[3];   // MOE_PLAN=guR,dnR,dnKS (tuning), zeros = automatic
-  bool no_fused_down;     // MOE_NO_FUSED_DOWN set (tuning): always use the split-K down projection
+  int plan_override[3];   // moe_ctx_tune: gate/up tiles, down tiles, split-K factor; zero = automatic
+  bool no_fused_down;     // moe_ctx_tune: always use the split-K down projection
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
@@ -136,7 +136,7 @@ double expected_slots(const moe_shape& s, int T) {
   return s.n_experts * (1.0 - miss) + s.n_shared;
 }
 
-// plan_override: three ints (guR, dnR, dnKS), zeros = automatic
+// plan_override: three ints (gate/up tiles, down tiles, split-K factor), each zero = automatic (moe_ctx_tune)
 Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, int T, bool tiled, bool fp8) {
   const double slots = expected_slots(s, T);
   Plan p;
@@ -169,30 +169,13 @@ Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, 
     while (slots * C < 2 * kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
     p.dn_fused_C = C;
   }
-  if (plan_override[0] > 0) {
-    p.gu_R = plan_override[0];
-    p.dn_R = plan_override[1];
-    p.dn_KS = plan_override[2] < cap ? plan_override[2] : cap;
-  }
+  if (plan_override[0] > 0) p.gu_R = plan_override[0];
+  if (plan_override[1] > 0) p.dn_R = plan_override[1];
+  if (plan_override[2] > 0) p.dn_KS = plan_override[2] < cap ? plan_override[2] : cap;
   return p;
 }
 Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
   return plan_for(c->s, c->plan_override, c->no_fused_down, T, tiled, fp8);
-}
-
-// tuning overrides from the environment: MOE_PLAN="guR,dnR,dnKS", MOE_NO_FUSED_DOWN
-void plan_env(int* plan_override, bool* no_fused_down) {
-  plan_override[0] = plan_override[1] = plan_override[2] = 0;
-  *no_fused_down = getenv("MOE_NO_FUSED_DOWN") != nullptr;
-  if (const char* env = getenv("MOE_PLAN")) {
-    int a = 0, b = 0, k = 0;
-    if (sscanf(env, "%d,%d,%d", &a, &b, &k) == 3 && (a == 1 || a == 2 || a == 4) && (b == 1 || b == 2 || b == 4) &&
-        k >= 1 && k <= kMaxKS) {
-      plan_override[0] = a;
-      plan_override[1] = b;
-      plan_override[2] = k;
-    }
-  }
 }
 
 moe_status validate_shape(const moe_shape& s) {
@@ -212,10 +195,20 @@ moe_status validate_shape(const moe_shape& s) {
   return MOE_OK;
 }
 
-moe_status check_stream_device(const moe_ctx* c) {
+// The context's workspace lives on one device: the current device must be that one, and so must the stream's
+// (the NULL stream belongs to the current device; a stream HIP cannot place is taken as the caller's word).
+moe_status check_stream_device(const moe_ctx* c, void* stream) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-  return dev == c->device ? MOE_OK : MOE_ERR_INVALID_ARG;
+  if (dev != c->device) return MOE_ERR_INVALID_ARG;
+  if (stream) {
+    hipDevice_t sdev = -1;
+    if (hipStreamGetDevice((hipStream_t)stream, &sdev) != hipSuccess)
+      (void)hipGetLastError();
+    else if ((int)sdev != c->device)
+      return MOE_ERR_INVALID_ARG;
+  }
+  return MOE_OK;
 }
 
 // profiling mode only: drop an event into the stream between kernels
@@ -413,7 +406,8 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   c->device = dev;
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
-  plan_env(c->plan_override, &c->no_fused_down);
+  c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
+  c->no_fused_down = false;
   // the slab buffer is sized for the largest split-K factor any T can ask for
   c->ks_alloc = 1;
   for (int T = 1; T <= s.max_tokens; ++T)
@@ -499,6 +493,19 @@ moe_status moe_ctx_destroy(moe_ctx* c) {
 
 int64_t moe_ctx_workspace_bytes(const moe_ctx* c) { return c ? (int64_t)c->ws_bytes : 0; }
 
+moe_status moe_ctx_tune(moe_ctx* c, int32_t gu_tiles, int32_t dn_tiles, int32_t dn_split_k, int32_t fused_down) {
+  auto tiles_ok = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
+  if (!c || !tiles_ok(gu_tiles) || !tiles_ok(dn_tiles) || dn_split_k < 0 || dn_split_k > kMaxKS) return MOE_ERR_INVALID_ARG;
+  if (dn_split_k & (dn_split_k - 1)) return MOE_ERR_INVALID_ARG;  // powers of two only
+  if (fused_down != -1 && fused_down != 0) return MOE_ERR_INVALID_ARG;
+  c->plan_override[0] = gu_tiles;
+  c->plan_override[1] = dn_tiles;
+  // the slab buffer was sized at creation for the automatic plan: a larger split does not fit
+  c->plan_override[2] = dn_split_k < c->ks_alloc ? dn_split_k : c->ks_alloc;
+  c->no_fused_down = fused_down == 0;
+  return MOE_OK;
+}
+
 moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int32_t dtype, moe_plan_info* out) {
   if (!shape || !out) return MOE_ERR_INVALID_ARG;
   const moe_shape s = *shape;
@@ -509,10 +516,8 @@ moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int
   const bool tiled = layout == MOE_LAYOUT_TILED, fp8 = dtype == MOE_WEIGHT_FP8_E4M3;
   if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;
   if (fp8 && (s.d % 64 || s.ffn % 64)) return MOE_ERR_UNSUPPORTED_SHAPE;
-  int override[3];
-  bool no_fused;
-  plan_env(override, &no_fused);
-  const Plan p = plan_for(s, override, no_fused, T, tiled, fp8);
+  const int automatic[3] = {0, 0, 0};
+  const Plan p = plan_for(s, automatic, false, T, tiled, fp8);
   out->routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;
   out->expected_slots = expected_slots(s, T);
   out->wide_router = s.n_experts >= kWideRouterExperts;
@@ -530,7 +535,7 @@ moe_status moe_route(moe_ctx* c, const float* hidden, const uint16_t* router_w, 
                      int32_t* unique_experts, int32_t* n_unique, void* stream) {
   if (!c || !hidden || !router_w || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (!aligned16(hidden) || !aligned16(router_w)) return MOE_ERR_INVALID_ARG;
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   launch_route_and_group(c, hidden, router_w, T, ids, gates, unique_experts, n_unique, nullptr, (hipStream_t)stream);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -538,7 +543,7 @@ moe_status moe_route(moe_ctx* c, const float* hidden, const uint16_t* router_w, 
 moe_status moe_group(moe_ctx* c, const int32_t* ids, int32_t T, int32_t* unique_experts, int32_t* n_unique,
                      int32_t* expert_count, int32_t* expert_offset, int32_t* assign, void* stream) {
   if (!c || !ids || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   GroupArgs ga{ids, nullptr, T, c->s.top_k, c->s.n_experts, unique_experts, n_unique, expert_count, expert_offset,
                assign, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   hipLaunchKernelGGL(group_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, ga);
@@ -550,7 +555,7 @@ moe_status moe_verify_layer(moe_ctx* c, const moe_layer_weights* w, const float*
                             void* stream) {
   if (!c || !hidden || !out || T < 1 || T > c->s.max_tokens || !weights_ok(c, w)) return MOE_ERR_INVALID_ARG;
   if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   return launch_layer(c, w, hidden, T, out, ids_opt, gates_opt, unique_opt, n_unique_opt, nullptr, st);
 }
@@ -563,7 +568,7 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
     if (!weights_ok(c, layers + l)) return MOE_ERR_INVALID_ARG;
     if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
   }
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   const size_t per = (size_t)T * c->s.d;
   for (int l = 0; l < L; ++l) {
@@ -585,7 +590,7 @@ moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const 
     if (!weights_ok(c, layers + l) || !gammas[l] || !aligned16(gammas[l])) return MOE_ERR_INVALID_ARG;
     if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
   }
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   const moe_shape& s = c->s;
   const size_t per = (size_t)T * s.d;
@@ -623,7 +628,7 @@ moe_status moe_pack_matrix(moe_ctx* c, const void* src, void* dst, int64_t rows,
   if (dtype != MOE_WEIGHT_BF16 && dtype != MOE_WEIGHT_FP8_E4M3) return MOE_ERR_INVALID_ARG;
   const bool fp8 = dtype == MOE_WEIGHT_FP8_E4M3;
   if (K % (fp8 ? 64 : 32) || rows * (int64_t)K > (int64_t)1 << 34) return MOE_ERR_INVALID_ARG;
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   const size_t units = (size_t)rows * (size_t)(K / (fp8 ? 16 : 8));
   const unsigned blocks = (unsigned)((units + 255) / 256 < 65536 ? (units + 255) / 256 : 65536);
   if (fp8)
@@ -652,7 +657,7 @@ moe_status moe_decoder_stack(moe_ctx* c, const moe_layer_weights* layers, const 
     if (!aligned16(a.wqkv) || !aligned16(a.wo) || !aligned16(a.gamma_attn) || !aligned16(a.gamma_moe))
       return MOE_ERR_INVALID_ARG;
   }
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   const size_t per = (size_t)T * s.d;
   const int nq = s.n_heads * s.head_dim, nqkv = nq + 2 * s.n_kv_heads * s.head_dim;
@@ -710,7 +715,7 @@ moe_status moe_pack_weights(moe_ctx* c, const moe_layer_weights* src, moe_layer_
   chk.w1_scale = src->w1_scale, chk.w3_scale = src->w3_scale, chk.w2_scale = src->w2_scale;
   chk.sw1_scale = src->sw1_scale, chk.sw3_scale = src->sw3_scale, chk.sw2_scale = src->sw2_scale;
   if (!weights_ok(c, &chk)) return MOE_ERR_INVALID_ARG;
-  if (moe_status st = check_stream_device(c)) return st;
+  if (moe_status st = check_stream_device(c, stream)) return st;
   const moe_shape& s = c->s;
   hipStream_t st = (hipStream_t)stream;
   const bool fp8 = src->dtype == MOE_WEIGHT_FP8_E4M3;

@@ -1,0 +1,125 @@
+"""GPU parity, part 2: FP8 (E4M3 codes + per-output-channel scale) expert weights.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import moe_oracle as orc
+from paper_2506_20675_amd import binding, synth
+from gpu_common import (_check_layer, _check_out, _dev, _run_layer, _tiled, _weights_dev)
+
+
+from gpu_common import _check_layer_fp8, _run_layer_fp8
+
+
+def test_device_fp8_code_fill_is_bit_identical_to_host():
+    import torch
+    key = synth.stream_key(2, 5, synth.T_Q["q1"])
+    for n, start in ((4096, 0), (1001, 4), (7, 0), (3, 8), (1 << 20, 1 << 22), (65537 * 4 + 2, 12)):
+        t = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        synth.fill_codes_e4m3_device(t, key, start)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(t.cpu().numpy(), synth.codes_e4m3(key, n, start, force_numpy=True))
+
+
+def test_pack_fp8_layout_is_as_documented():
+    """Block (i, p) of a tiled FP8 matrix is rows 16i..16i+15 x columns 64p..64p+63; unit l = r + 16 g holds row
+    16i + r, columns 64p + 8g .. + 7 followed by columns 64p + 32 + 8g .. + 7."""
+    import torch
+    d, ffn, E, ns = 128, 192, 3, 1
+    rng = np.random.default_rng(8)
+    W = {n: rng.integers(0, 256, size=shp, dtype=np.uint8) for n, shp in
+         (("q1", (E, ffn, d)), ("q3", (E, ffn, d)), ("q2", (E, d, ffn)), ("sq1", (ns, ffn, d)), ("sq3", (ns, ffn, d)),
+          ("sq2", (ns, d, ffn)))}
+    W["router_w"] = rng.integers(0, 65536, size=(E, d), dtype=np.uint16)
+    for n, shp in (("s1", (E, ffn)), ("s3", (E, ffn)), ("s2", (E, d)), ("ss1", (ns, ffn)), ("ss3", (ns, ffn)), ("ss2", (ns, d))):
+        W[n] = rng.uniform(0.5, 2, shp).astype(np.float32)
+    ctx = binding.MoeContext(d, ffn, E, 2, ns, 4)
+    Wd = _weights_dev(W)
+    src = ctx.weights(Wd)
+    packed = ctx.moe_pack_weights(src)
+    torch.cuda.synchronize()
+    assert packed.c.layout == 1 and packed.c.dtype == 1
+    assert packed.c.w2_scale == src.c.w2_scale and packed.c.sw1_scale == src.c.sw1_scale     # scales are not re-ordered
+    for idx, name, rows, K in ((1, "q1", E * ffn, d), (2, "q3", E * ffn, d), (3, "q2", E * d, ffn), (6, "sq2", ns * d, ffn)):
+        got = packed.tensors[idx].cpu().numpy().reshape(-1)
+        s = W[name].reshape(rows, K)
+        want = s.reshape(rows // 16, 16, K // 64, 2, 4, 8).transpose(0, 2, 4, 1, 3, 5).reshape(-1)   # [i][p][g][r][half][8]
+        np.testing.assert_array_equal(got, want)
+    ctx.close()
+
+
+@pytest.mark.parametrize("T", [1, 3, 9])
+def test_fp8_layer_parity_tiny(T):
+    cfg = synth.TINY
+    W = synth.layer_weights_fp8_host(cfg, 0)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    _check_layer_fp8(ctx, W, _weights_dev(W), synth.hidden_host(cfg, 0, 40 + T, T, 0.5), cfg.top_k, 0)
+    ctx.close()
+
+
+@pytest.mark.parametrize("shape", [
+    # d, ffn, E, top_k, n_shared, T : odd numbers of 64-wide steps, ragged tile counts, shared experts, T = 16
+    (192, 320, 5, 3, 1, 7), (64, 64, 1, 1, 0, 1), (128, 192, 4, 4, 2, 16), (1088, 576, 6, 2, 1, 4),
+])
+def test_fp8_layer_parity_all_codes_and_wide_scales(shape):
+    """Codes drawn uniformly from all 254 finite E4M3 codes (subnormals and the largest values as likely as any
+    other) with row scales spread over two orders of magnitude: a wrong value for any code class or a scale
+    applied at the wrong row shows up here."""
+    d, ffn, E, k, ns, T = shape
+    rng = np.random.default_rng(sum(shape))
+    finite = np.array([c for c in range(256) if c not in (0x7F, 0xFF)], dtype=np.uint8)
+    W = dict(router_w=synth.f32_to_bf16_bits(rng.normal(0, 0.3, (E, d)).astype(np.float32)))
+    amp = 1e-4               # keeps the outputs O(1) so the absolute bar of the benchmark applies as stated
+    for q, s, shp in (("q1", "s1", (E, ffn, d)), ("q3", "s3", (E, ffn, d)), ("q2", "s2", (E, d, ffn))) + \
+            ((("sq1", "ss1", (ns, ffn, d)), ("sq3", "ss3", (ns, ffn, d)), ("sq2", "ss2", (ns, d, ffn))) if ns else ()):
+        W[q] = rng.choice(finite, shp)
+        W[s] = (amp * 10.0 ** rng.uniform(-1, 1, shp[:2])).astype(np.float32)
+    x = rng.normal(size=(T, d)).astype(np.float32)
+    ctx = binding.MoeContext(d, ffn, E, k, ns, max_tokens=max(9, T))
+    _check_layer_fp8(ctx, W, _weights_dev(W), x, k, ns)
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg", [synth.OLMOE, synth.DEEPSEEK], ids=lambda c: c.name)
+def test_fp8_layer_parity_fine_grained_full_size(cfg):
+    W = synth.layer_weights_fp8_host(cfg, 1)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, cfg.n_shared, 9)
+    Wd = _weights_dev(W)
+    for it, (T, rho) in enumerate(((1, 0.5), (9, 0.9))):
+        x = synth.hidden_host(cfg, 1, 400 + it, T, rho)
+        _check_layer_fp8(ctx, W, Wd, x, cfg.top_k, cfg.n_shared)
+    ctx.close()
+
+
+def test_fp8_argument_errors():
+    import torch
+    cfg = synth.TINY
+    W = synth.layer_weights_fp8_host(cfg, 3)
+    Wd = _weights_dev(W)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 4)
+    x = torch.zeros((2, cfg.d), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, cfg.d), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.MoeError) as e:
+        ctx.moe_verify_layer(ctx.weights(Wd), x, out)          # row-major FP8 is not streamed: pack first
+    assert e.value.status == -5                                  # MOE_ERR_UNIMPLEMENTED
+    lw = ctx.weights(Wd)
+    lw.c.w3_scale = None                                         # a missing scale vector is an argument error
+    with pytest.raises(binding.MoeError) as e:
+        ctx.moe_pack_weights(lw)
+    assert e.value.status == -1
+    ctx.close()
+    ctx = binding.MoeContext(96, 160, 4, 2, 0, 4)              # d, ffn not multiples of 64
+    Wbad = dict(router_w=torch.zeros((4, 96), dtype=torch.int16, device="cuda"),
+                q1=torch.zeros((4, 160, 96), dtype=torch.uint8, device="cuda"),
+                q3=torch.zeros((4, 160, 96), dtype=torch.uint8, device="cuda"),
+                q2=torch.zeros((4, 96, 160), dtype=torch.uint8, device="cuda"),
+                s1=torch.ones((4, 160), device="cuda"), s3=torch.ones((4, 160), device="cuda"),
+                s2=torch.ones((4, 96), device="cuda"))
+    with pytest.raises(binding.MoeError) as e:
+        ctx.moe_pack_weights(ctx.weights(Wbad))
+    assert e.value.status == -1
+    ctx.close()
+
+
