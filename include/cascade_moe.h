@@ -190,6 +190,23 @@ moe_status moe_verify_layer(moe_ctx* ctx, const moe_layer_weights* w, const floa
                             int32_t* ids_opt, float* gates_opt, int32_t* unique_opt, int32_t* n_unique_opt,
                             void* stream);
 
+/* moe_verify_layer for callers that cannot allocate device memory and cannot hold a moe_ctx that did: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and
+ * launch plan, same results as moe_verify_layer on a fresh context of `shape`, but the workspace is a fixed
+ * 32 MiB array inside the library's device code (every GPU the library runs on holds it until the process ends),
+ * and the call itself allocates nothing: no hipMalloc / hipFree, no event objects, no allocating library routine.
+ *   - The geometry's workspace (what moe_ctx_workspace_bytes reports for a context of `shape`; 12 MiB for the
+ *     Mixtral-8x7B-shaped layer at max_tokens 9, under 23 MiB for every Table 1 shape at max_tokens 16) must fit
+ *     the array; a geometry that needs more returns MOE_ERR_WORKSPACE and launches nothing.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents; each call first clears
+ *     the part a layer-step reads before writing (a small fill kernel on `stream`).  Calls that overlap on one GPU
+ *     — from different streams or threads — race: serialise them.  The array's device address is looked up on the
+ *     first call on each device, which must therefore not happen inside a stream capture.
+ * shape: HOST; every other argument as for moe_verify_layer.  moe_ctx_tune / moe_ctx_profile do not apply. */
+moe_status moe_verify_layer_noalloc(const moe_shape* shape, const moe_layer_weights* w, const float* hidden, int32_t T,
+                                    float* out, int32_t* ids_opt, float* gates_opt, int32_t* unique_opt,
+                                    int32_t* n_unique_opt, void* stream);
+
 /* L layers back to back on one stream without host synchronisation: layer l reads hidden[l] and
  * writes out[l] (independent per-layer inputs; the method's cost model needs no chaining).
  * layers: HOST array of L structs (copied during the call).  hidden, out: DEVICE [L,T,d].

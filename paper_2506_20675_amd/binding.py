@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
                 -4: "MOE_ERR_HIP", -5: "MOE_ERR_UNIMPLEMENTED"}
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes", "moe_ctx_tune",
-           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
+           "moe_route", "moe_group", "moe_verify_layer", "moe_verify_layer_noalloc", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
            "moe_stream_read_probe", "moe_plan_query",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
@@ -101,6 +101,9 @@ def lib():
     L.moe_verify_layer.restype = ctypes.c_int
     L.moe_verify_layer.argtypes = [c_void_p, POINTER(MoeLayerWeights), c_void_p, c_int32, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.moe_verify_layer_noalloc.restype = ctypes.c_int
+    L.moe_verify_layer_noalloc.argtypes = [POINTER(MoeShape), POINTER(MoeLayerWeights), c_void_p, c_int32, c_void_p,
+                                           c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.moe_chained_stack.restype = ctypes.c_int
     L.moe_chained_stack.argtypes = [c_void_p, POINTER(MoeLayerWeights), POINTER(c_void_p), c_int32, c_void_p, c_int32,
                                     ctypes.c_float, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -422,6 +425,25 @@ def moe_plan_query(d, ffn, n_experts, top_k, n_shared=0, max_tokens=9, T=1, layo
     info = MoePlanInfo()
     _check(lib().moe_plan_query(ctypes.byref(shape), T, layout, dtype, ctypes.byref(info)), "moe_plan_query")
     return {n: getattr(info, n) for n, _ in MoePlanInfo._fields_}
+
+
+def moe_verify_layer_noalloc(shape: MoeShape, weights: LayerWeights, hidden, out, ids=None, gates=None,
+                             unique_experts=None, n_unique=None, stream=None):
+    """moe_verify_layer on the library's fixed workspace: no context, no allocation inside the call."""
+    import torch
+    s = shape
+    T = hidden.shape[0]
+    _want(hidden, torch.float32, (T, s.d), "hidden")
+    _want(out, torch.float32, (T, s.d), "out")
+    _want(ids, torch.int32, (T, s.top_k), "ids")
+    _want(gates, torch.float32, (T, s.top_k), "gates")
+    _want(unique_experts, torch.int32, (s.n_experts,), "unique_experts")
+    _want(n_unique, torch.int32, (1,), "n_unique")
+    if weights.geometry != (s.d, s.ffn, s.n_experts, s.n_shared):
+        raise ValueError(f"layer weights were built for (d, ffn, E, n_shared) = {weights.geometry}")
+    _check(lib().moe_verify_layer_noalloc(byref(s), byref(weights.c), _ptr(hidden), T, _ptr(out), _ptr(ids), _ptr(gates),
+                                          _ptr(unique_experts), _ptr(n_unique), _stream_ptr(stream)),
+           "moe_verify_layer_noalloc")
 
 
 def moe_stream_read_probe(src, sink, stream=None):

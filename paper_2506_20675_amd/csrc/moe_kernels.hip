@@ -79,6 +79,26 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ------------------------------------------------------------------------------------------
+// Workspace of moe_verify_layer_noalloc: device memory that exists from the moment the code object is loaded, so
+// that entry point never has to allocate.  Every GPU the library runs on holds its own copy of this array until
+// the process ends.  In host code the NAME of the array is only a handle for hipGetSymbolAddress; the device
+// address it yields (kept per device in g_noalloc) is what kernels, fills and copies are given.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Prepares the leading n16 16-byte units of the workspace (router-input fragments and slot tables): zeros, except
+// the units [ones_beg, ones_end) — the constant gate rows of the shared experts — which get 1.0.  A kernel and not
+// a memset, so that a caller may record it in a HIP graph like the rest of the call.
+__global__ __launch_bounds__(256) void scratch_init_kernel(uint4* __restrict__ p, size_t n16, size_t ones_beg,
+                                                           size_t ones_end) {
+  const uint32_t one = 0x3f800000u;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+    p[i] = (i >= ones_beg && i < ones_end) ? uint4{one, one, one, one} : uint4{0u, 0u, 0u, 0u};
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
@@ -176,6 +196,77 @@ Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, 
 }
 Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
   return plan_for(c->s, c->plan_override, c->no_fused_down, T, tiled, fp8);
+}
+
+// Geometry-dependent host fields of a context (automatic plan; slab buffer sized for the largest split-K factor
+// any T can ask for).
+void ctx_set_shape(moe_ctx* c, const moe_shape& s, int dev) {
+  c->s = s;
+  c->device = dev;
+  c->profiling = false;
+  c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
+  c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
+  c->no_fused_down = false;
+  c->ks_alloc = 1;
+  for (int T = 1; T <= s.max_tokens; ++T)
+    for (bool tiled : {false, true})
+      for (bool fp8 : {false, true}) {
+        const int ks = plan_for(c, T, tiled, fp8).dn_KS;
+        if (ks > c->ks_alloc) c->ks_alloc = ks;
+      }
+}
+
+// Carves the workspace of a context out of `base` (256-byte aligned pieces) and returns its size; base == NULL
+// only measures.  The pieces whose CONTENT a layer-step relies on before writing them come first — the
+// activation fragments of the router input (their padded token columns are read by the matrix cores) and the
+// per-slot tables (the shared experts' gate rows are constant 1) — and *init_bytes gets their total size.
+size_t ctx_layout(moe_ctx* c, char* base, size_t* init_bytes = nullptr) {
+  const moe_shape& s = c->s;
+  const size_t A = (size_t)s.max_tokens * s.top_k;
+  size_t off = 0;
+  auto carve = [&](size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  const size_t n_slots = (size_t)c->u_max + s.n_shared;
+  const size_t o_xh = carve((size_t)s.d * kGateCols * 2), o_xl = carve((size_t)s.d * kGateCols * 2);
+  const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
+  const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
+  const size_t o_sm = carve((size_t)c->u_max * 4);
+  if (init_bytes) *init_bytes = off;
+  const size_t o_hh = carve(n_slots * s.ffn * kGateCols * 2);
+  const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
+  const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
+  const size_t o_xn = carve((size_t)s.max_tokens * s.d * 4);
+  const size_t o_r0 = carve((size_t)s.max_tokens * s.d * 4), o_r1 = carve((size_t)s.max_tokens * s.d * 4);
+  const size_t nq = (size_t)s.n_heads * s.head_dim, nqkv = nq + 2 * (size_t)s.n_kv_heads * s.head_dim;
+  const size_t o_hb = carve((size_t)s.max_tokens * s.d * 4), o_qkv = carve((size_t)s.max_tokens * nqkv * 4 + 16);
+  const size_t o_ah = carve(nq * kGateCols * 2 + 16), o_al = carve(nq * kGateCols * 2 + 16);
+  const size_t o_lg = carve((size_t)s.max_tokens * s.n_experts * 8);
+  if (!base) return off;
+  c->ws = base;
+  c->xf_hi = reinterpret_cast<uint16_t*>(base + o_xh);
+  c->xf_lo = reinterpret_cast<uint16_t*>(base + o_xl);
+  c->hf_hi = reinterpret_cast<uint16_t*>(base + o_hh);
+  c->hf_lo = reinterpret_cast<uint16_t*>(base + o_hl);
+  c->ids = reinterpret_cast<int32_t*>(base + o_ids);
+  c->gates = reinterpret_cast<float*>(base + o_gates);
+  c->n_unique = reinterpret_cast<int32_t*>(base + o_nu);
+  c->slot_expert = reinterpret_cast<int32_t*>(base + o_se);
+  c->slot_gate = reinterpret_cast<float*>(base + o_sg);
+  c->tok_slot = reinterpret_cast<int32_t*>(base + o_ts);
+  c->slot_mask = reinterpret_cast<int32_t*>(base + o_sm);
+  c->partial = reinterpret_cast<float*>(base + o_part);
+  c->xn = reinterpret_cast<float*>(base + o_xn);
+  c->resid[0] = reinterpret_cast<float*>(base + o_r0);
+  c->resid[1] = reinterpret_cast<float*>(base + o_r1);
+  c->hbuf = reinterpret_cast<float*>(base + o_hb);
+  c->qkv = reinterpret_cast<float*>(base + o_qkv);
+  c->af_hi = reinterpret_cast<uint16_t*>(base + o_ah);
+  c->af_lo = reinterpret_cast<uint16_t*>(base + o_al);
+  c->logits = reinterpret_cast<double*>(base + o_lg);
+  return off;
 }
 
 moe_status validate_shape(const moe_shape& s) {
@@ -375,6 +466,19 @@ bool weights_ok(const moe_ctx* c, const moe_layer_weights* w) {
   return true;
 }
 
+// Per-device state of moe_verify_layer_noalloc: the device address of `scratch` on that device and a context that
+// lives in host memory of this library and is laid out over it.
+constexpr int kMaxDevices = 64;
+struct NoAllocSlot {
+  char* base = nullptr;     // device address of the scratch array on this device (hipGetSymbolAddress)
+  bool have_shape = false;  // ctx below is set up for `shape`
+  moe_shape shape;
+  size_t init_bytes = 0;
+  moe_ctx ctx;
+};
+NoAllocSlot g_noalloc[kMaxDevices];
+
+
 }  // namespace
 
 extern "C" {
@@ -384,7 +488,7 @@ const char* moe_strerror(moe_status s) {
     case MOE_OK: return "ok";
     case MOE_ERR_INVALID_ARG: return "invalid argument";
     case MOE_ERR_UNSUPPORTED_SHAPE: return "unsupported layer shape";
-    case MOE_ERR_WORKSPACE: return "device workspace allocation failed";
+    case MOE_ERR_WORKSPACE: return "device workspace could not be allocated, or the geometry needs more than the fixed workspace";
     case MOE_ERR_HIP: return "HIP runtime error";
     case MOE_ERR_UNIMPLEMENTED: return "not implemented";
   }
@@ -402,68 +506,14 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
   moe_ctx* c = new (std::nothrow) moe_ctx();
   if (!c) return MOE_ERR_WORKSPACE;
-  c->s = s;
-  c->device = dev;
-  c->profiling = false;
-  c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
-  c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
-  c->no_fused_down = false;
-  // the slab buffer is sized for the largest split-K factor any T can ask for
-  c->ks_alloc = 1;
-  for (int T = 1; T <= s.max_tokens; ++T)
-    for (bool tiled : {false, true})
-      for (bool fp8 : {false, true}) {
-        const int ks = plan_for(c, T, tiled, fp8).dn_KS;
-        if (ks > c->ks_alloc) c->ks_alloc = ks;
-      }
-
-  const size_t A = (size_t)s.max_tokens * s.top_k;
-  size_t off = 0;
-  auto carve = [&](size_t bytes) {
-    const size_t o = off;
-    off = align_up(off + bytes, 256);
-    return o;
-  };
-  const size_t o_xh = carve((size_t)s.d * kGateCols * 2), o_xl = carve((size_t)s.d * kGateCols * 2);
-  const size_t n_slots = (size_t)c->u_max + s.n_shared;
-  const size_t o_hh = carve(n_slots * s.ffn * kGateCols * 2);
-  const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
-  const size_t o_ids = carve(A * 4), o_gates = carve(A * 4), o_nu = carve(4);
-  const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
-  const size_t o_sm = carve((size_t)c->u_max * 4);
-  const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
-  const size_t o_xn = carve((size_t)s.max_tokens * s.d * 4);
-  const size_t o_r0 = carve((size_t)s.max_tokens * s.d * 4), o_r1 = carve((size_t)s.max_tokens * s.d * 4);
-  const size_t nq = (size_t)s.n_heads * s.head_dim, nqkv = nq + 2 * (size_t)s.n_kv_heads * s.head_dim;
-  const size_t o_hb = carve((size_t)s.max_tokens * s.d * 4), o_qkv = carve((size_t)s.max_tokens * nqkv * 4 + 16);
-  const size_t o_ah = carve(nq * kGateCols * 2 + 16), o_al = carve(nq * kGateCols * 2 + 16);
-  const size_t o_lg = carve((size_t)s.max_tokens * s.n_experts * 8);
-  c->ws_bytes = off;
+  ctx_set_shape(c, s, dev);
+  c->ws_bytes = ctx_layout(c, nullptr);
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
     return MOE_ERR_WORKSPACE;
   }
-  c->xf_hi = reinterpret_cast<uint16_t*>(c->ws + o_xh);
-  c->xf_lo = reinterpret_cast<uint16_t*>(c->ws + o_xl);
-  c->hf_hi = reinterpret_cast<uint16_t*>(c->ws + o_hh);
-  c->hf_lo = reinterpret_cast<uint16_t*>(c->ws + o_hl);
-  c->ids = reinterpret_cast<int32_t*>(c->ws + o_ids);
-  c->gates = reinterpret_cast<float*>(c->ws + o_gates);
-  c->n_unique = reinterpret_cast<int32_t*>(c->ws + o_nu);
-  c->slot_expert = reinterpret_cast<int32_t*>(c->ws + o_se);
-  c->slot_gate = reinterpret_cast<float*>(c->ws + o_sg);
-  c->tok_slot = reinterpret_cast<int32_t*>(c->ws + o_ts);
-  c->slot_mask = reinterpret_cast<int32_t*>(c->ws + o_sm);
-  c->partial = reinterpret_cast<float*>(c->ws + o_part);
-  c->xn = reinterpret_cast<float*>(c->ws + o_xn);
-  c->resid[0] = reinterpret_cast<float*>(c->ws + o_r0);
-  c->resid[1] = reinterpret_cast<float*>(c->ws + o_r1);
-  c->hbuf = reinterpret_cast<float*>(c->ws + o_hb);
-  c->qkv = reinterpret_cast<float*>(c->ws + o_qkv);
-  c->af_hi = reinterpret_cast<uint16_t*>(c->ws + o_ah);
-  c->af_lo = reinterpret_cast<uint16_t*>(c->ws + o_al);
-  c->logits = reinterpret_cast<double*>(c->ws + o_lg);
+  (void)ctx_layout(c, c->ws);
   if (hipMemset(c->ws, 0, c->ws_bytes) != hipSuccess) {  // padded token columns of the fragments are finite zeros
     (void)hipFree(c->ws);
     delete c;
@@ -557,6 +607,50 @@ moe_status moe_verify_layer(moe_ctx* c, const moe_layer_weights* w, const float*
   if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
   if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
+  return launch_layer(c, w, hidden, T, out, ids_opt, gates_opt, unique_opt, n_unique_opt, nullptr, st);
+}
+
+moe_status moe_verify_layer_noalloc(const moe_shape* shape, const moe_layer_weights* w, const float* hidden, int32_t T,
+                                    float* out, int32_t* ids_opt, float* gates_opt, int32_t* unique_opt,
+                                    int32_t* n_unique_opt, void* stream) {
+  if (!shape || !hidden || !out) return MOE_ERR_INVALID_ARG;
+  const moe_shape s = *shape;
+  if (moe_status st = validate_shape(s)) return st;
+  if (T < 1 || T > s.max_tokens) return MOE_ERR_INVALID_ARG;
+  if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED_SHAPE;
+  NoAllocSlot& slot = g_noalloc[dev];
+  if (!slot.base) {
+    // once per device, with that device current: every GPU has its own copy of the array at its own address
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return MOE_ERR_HIP;
+    }
+    slot.base = static_cast<char*>(ptr);
+  }
+  if (!slot.have_shape || memcmp(&slot.shape, &s, sizeof(s)) != 0) {
+    slot.have_shape = false;
+    ctx_set_shape(&slot.ctx, s, dev);
+    const size_t need = ctx_layout(&slot.ctx, nullptr, &slot.init_bytes);
+    if (need > kScratchBytes) return MOE_ERR_WORKSPACE;  // this geometry needs more than the fixed workspace
+    slot.ctx.ws_bytes = ctx_layout(&slot.ctx, slot.base);
+    slot.shape = s;
+    slot.have_shape = true;
+  }
+  moe_ctx* c = &slot.ctx;
+  if (!weights_ok(c, w)) return MOE_ERR_INVALID_ARG;
+  if (moe_status st = check_stream_device(c, stream)) return st;
+  hipStream_t st = (hipStream_t)stream;
+  // the array keeps whatever the last call on this GPU left in it (possibly laid out for another geometry)
+  const size_t n16 = slot.init_bytes / 16;
+  const size_t ones_beg = (size_t)(reinterpret_cast<char*>(c->slot_gate + (size_t)c->u_max * kGateCols) - slot.base) / 16;
+  const size_t ones_end = ones_beg + (size_t)s.n_shared * kGateCols * sizeof(float) / 16;
+  const unsigned blocks = (unsigned)((n16 + 255) / 256 < 1024 ? (n16 + 255) / 256 : 1024);
+  hipLaunchKernelGGL(scratch_init_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(slot.base), n16,
+                     ones_beg, ones_end);
   return launch_layer(c, w, hidden, T, out, ids_opt, gates_opt, unique_opt, n_unique_opt, nullptr, st);
 }
 
