@@ -37,19 +37,42 @@ def _check_no_scratch(stderr: str) -> None:
                 raise RuntimeError(f"kernel {name} uses {size} bytes/lane of scratch (register spill)")
 
 
+def _check_mfma_readers(tmp: str) -> None:
+    """Refuse a build whose generated code reads a matrix-core result sooner than the hardware delivers it on some
+    path (see mfma_hazard_check.py): the device assembly the compiler left in `tmp` is scanned."""
+    from . import mfma_hazard_check
+    asm = [f for f in os.listdir(tmp) if f.endswith(".s") and "gfx950" in f]
+    if len(asm) != 1:
+        raise RuntimeError(f"expected one gfx950 assembly file in {tmp}, found {asm}")
+    bad = mfma_hazard_check.check(open(os.path.join(tmp, asm[0])).read())
+    if bad:
+        lines = [f"  {k}: v_mfma #{i} read after {slots} issue slots by `{what}`" for k, i, what, slots in bad[:10]]
+        raise RuntimeError(f"{len(bad)} too-early reader(s) of a matrix-core result in the generated code:\n" + "\n".join(lines))
+
+
 def build_all(verbose: bool = False) -> None:
-    obj_k = os.path.join(HERE, "moe_kernels.o")
+    import shutil
+    import tempfile
     obj_c = os.path.join(HERE, "cascade_ctrl.o")
-    r = _run([HIPCC] + HIP_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-I", INCLUDE, "-c",
-                                   os.path.join(CSRC, "moe_kernels.hip"), "-o", obj_k])
-    _check_no_scratch(r.stderr)
+    tmp = tempfile.mkdtemp(prefix="moe_build_")
+    try:
+        obj_k = os.path.join(tmp, "moe_kernels.o")
+        r = _run([HIPCC] + HIP_FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-save-temps=obj", "-I", INCLUDE, "-c",
+                                       os.path.join(CSRC, "moe_kernels.hip"), "-o", obj_k])
+        _check_no_scratch(r.stderr)
+        _check_mfma_readers(tmp)
+        _build_rest(obj_k, obj_c, verbose)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+
+
+def _build_rest(obj_k: str, obj_c: str, verbose: bool) -> None:
     # host policy code: plain C++ with contraction off so decisions replay identically everywhere
     _run(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-I", INCLUDE, "-c",
           os.path.join(CSRC, "cascade_ctrl.cpp"), "-o", obj_c])
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", obj_k, obj_c, "-o", LIB])
     _run([HIPCC] + HIP_FLAGS + ["-shared", os.path.join(CSRC, "synth_fill.hip"), "-o", SYNTH_LIB])
-    for o in (obj_k, obj_c):
-        os.remove(o)
+    os.remove(obj_c)
     if verbose:
         print("built", LIB, SYNTH_LIB)
 

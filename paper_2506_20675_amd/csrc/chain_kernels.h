@@ -31,7 +31,7 @@ constexpr int kChainVecs = 4;  // float4 per thread: d <= 4 * 4 * 1024
 
 __device__ __forceinline__ void chain_body(const ChainArgs& g) {
   __shared__ float s_ss[kChainThreads / 64];
-  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int t = blockIdx.x, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int per_tok = g.d >> 2;
   const size_t slab = (size_t)g.max_tokens * g.d;
   const int n = g.partial ? (g.top_k + g.n_shared) * g.KS : 0;
@@ -126,7 +126,7 @@ template <bool PK>
 __global__ __launch_bounds__(256) void linear_kernel(LinearArgs g) {
   constexpr int W = 4, P = 6;
   __shared__ float4 red[W * 64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int nsteps = g.K >> 5, chunk = (nsteps + W - 1) / W;
   const int nst = max(0, min(chunk, nsteps - wave * chunk));
   const int s_beg = min(wave * chunk, nsteps - 1);

@@ -25,7 +25,7 @@ template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
 __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * 2 * R * 64 : 1];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const char *W1, *W3;
   const float *S1 = nullptr, *S3 = nullptr;  // FP8: scale rows of this expert
   const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
@@ -185,7 +185,7 @@ template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
 __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * R * 64 : 1];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int ks = blockIdx.z;
   int slot = blockIdx.y;
   const char* W2;
@@ -232,33 +232,39 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       [&](Stage<R, NB, PK>& st, int s) {
 #pragma unroll
         for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+        // The fragment loads are unconditional although H of a token that was not routed here was never written
+        // (the address is inside the workspace, the value is whatever an earlier call left): a load under a
+        // per-lane condition makes the compiler count on the smaller number of loads in flight and halves the
+        // effective prefetch depth.  The unrouted columns are masked to zero where they are consumed.
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-          st.bh[b] = uint4{0u, 0u, 0u, 0u};
-          if constexpr (!PK) st.bl[b] = uint4{0u, 0u, 0u, 0u};
-          if (live) {  // H of a token that was not routed here was never written: do not read it
-            st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
-            if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
-          }
+          st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+          if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
         }
       },
       [&](const Stage<R, NB, PK>& st) {
+        uint4 bh[NB], bl[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          bh[b] = live ? st.bh[b] : uint4{0u, 0u, 0u, 0u};
+          if constexpr (!PK) bl[b] = live ? st.bl[b] : uint4{0u, 0u, 0u, 0u};
+        }
         if constexpr (FP8) {
 #pragma unroll
           for (int j = 0; j < R; ++j) {
             uint4 k0, k1;
             fp8x16_to_bf16(st.a[j], k0, k1);
-            acc[j] = mfma_bf16(k0, st.bh[0], acc[j]);
-            if constexpr (!PK) acc[j] = mfma_bf16(k0, st.bl[0], acc[j]);
-            acc[j] = mfma_bf16(k1, st.bh[1], acc[j]);
-            if constexpr (!PK) acc[j] = mfma_bf16(k1, st.bl[1], acc[j]);
+            acc[j] = mfma_bf16(k0, bh[0], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k0, bl[0], acc[j]);
+            acc[j] = mfma_bf16(k1, bh[1], acc[j]);
+            if constexpr (!PK) acc[j] = mfma_bf16(k1, bl[1], acc[j]);
           }
         } else {
 #pragma unroll
-          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bh[0], acc[j]);
+          for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], bh[0], acc[j]);
           if constexpr (!PK) {
 #pragma unroll
-            for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], st.bl[0], acc[j]);
+            for (int j = 0; j < R; ++j) acc[j] = mfma_bf16(st.a[j], bl[0], acc[j]);
           }
         }
       });
@@ -320,7 +326,7 @@ template <int P, bool FP8, bool PK>
 __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[kFusedWaves * 64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kg = lane >> 4;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
   const int tile = blockIdx.x, col = PK ? (r & (kPackedTokens - 1)) : r;
   const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
   const int nu = *g.n_unique, n_items = (nu + g.n_shared) * g.C;
@@ -360,26 +366,28 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
         [&](Stage<1, NB, PK>& st, int s) {
           st.a[0] = ld128<true>(base, wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
-          for (int b = 0; b < NB; ++b) {
-            st.bh[b] = uint4{0u, 0u, 0u, 0u};
-            if constexpr (!PK) st.bl[b] = uint4{0u, 0u, 0u, 0u};
-            if (live) {
-              st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
-              if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
-            }
+          for (int b = 0; b < NB; ++b) {  // unconditional loads, masked where consumed (as in down_kernel)
+            st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+            if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
           }
         },
         [&](const Stage<1, NB, PK>& st) {
+          uint4 bh[NB], bl[NB];
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            bh[b] = live ? st.bh[b] : uint4{0u, 0u, 0u, 0u};
+            if constexpr (!PK) bl[b] = live ? st.bl[b] : uint4{0u, 0u, 0u, 0u};
+          }
           if constexpr (FP8) {
             uint4 k0, k1;
             fp8x16_to_bf16(st.a[0], k0, k1);
-            acc = mfma_bf16(k0, st.bh[0], acc);
-            if constexpr (!PK) acc = mfma_bf16(k0, st.bl[0], acc);
-            acc = mfma_bf16(k1, st.bh[1], acc);
-            if constexpr (!PK) acc = mfma_bf16(k1, st.bl[1], acc);
+            acc = mfma_bf16(k0, bh[0], acc);
+            if constexpr (!PK) acc = mfma_bf16(k0, bl[0], acc);
+            acc = mfma_bf16(k1, bh[1], acc);
+            if constexpr (!PK) acc = mfma_bf16(k1, bl[1], acc);
           } else {
-            acc = mfma_bf16(st.a[0], st.bh[0], acc);
-            if constexpr (!PK) acc = mfma_bf16(st.a[0], st.bl[0], acc);
+            acc = mfma_bf16(st.a[0], bh[0], acc);
+            if constexpr (!PK) acc = mfma_bf16(st.a[0], bl[0], acc);
           }
         });
     if constexpr (FP8) {  // every slot has its own row scales: scale the item's sum before it joins the others

@@ -18,6 +18,11 @@ constexpr int kGateCols = 16;  // columns of the per-slot gate table = MFMA N
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// Index of the calling wavefront inside its workgroup, as a SCALAR: tid >> 6 is the same in all 64 lanes, but the
+// compiler cannot know that, and everything derived from a per-lane value (loop bounds, base pointers of the
+// wave's share of the work) would live in vector registers and be branched on through the EXEC mask.
+__device__ __forceinline__ int wave_index(int tid) { return __builtin_amdgcn_readfirstlane(tid >> 6); }
+
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
   if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // keep NaN a NaN
@@ -95,6 +100,18 @@ struct Stage {
   uint4 bl[PK ? 1 : NB];  // unused when the halves are packed into bh
 };
 
+// Issue slots between the last MFMA of a code path and whatever comes after a branch.  A matrix-core result lands
+// several slots after its instruction was issued; the compiler pads a too-early reader with s_nop, but its padding
+// has been seen to fall short when the reader (typically a register-allocator copy of the accumulators) sits
+// behind a TAKEN uniform branch — the wave then continues with the accumulator as it was before its last MFMA.
+// So every conditionally executed group of MFMAs below ends with the padding itself, fenced so that nothing is
+// scheduled across it.  (The generated code is also checked after every build: mfma_hazard_check.py.)
+__device__ __forceinline__ void mfma_settle() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 7");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int NA, int NB, bool PK, int P, class Load, class Compute>
 __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
   Stage<NA, NB, PK> st[P];
@@ -111,15 +128,20 @@ __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
       load(st[p], s + p + P);
     }
   }
+  mfma_settle();
 #pragma unroll
   for (int p = 0; p < P; ++p)
     if (s + p < nst) {
       compute(st[p]);
+      mfma_settle();
       if (s + p + P < nst) load(st[p], s + p + P);
     }
 #pragma unroll
   for (int p = 0; p < P; ++p)
-    if (s + P + p < nst) compute(st[p]);
+    if (s + P + p < nst) {
+      compute(st[p]);
+      mfma_settle();
+    }
 }
 
 // ------------------------------------------------------------------------------------------

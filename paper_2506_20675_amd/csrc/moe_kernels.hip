@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
   // sizes, and waves that walk them in lockstep keep meeting on the same memory channels — the staggered start
   // reads 3-5 % faster than the aligned one on this chip, and faster than any other pattern tried.
   const int lane = threadIdx.x & 63;
-  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const size_t wave = (size_t)blockIdx.x * 4 + wave_index(threadIdx.x);
   const size_t beg = wave * n16_per_wave < n16 ? wave * n16_per_wave : n16;
   const size_t end = beg + n16_per_wave < n16 ? beg + n16_per_wave : n16;
   const size_t nb = (end - beg) / 512;  // whole batches of 8 x 64 units

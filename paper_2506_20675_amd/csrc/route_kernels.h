@@ -32,7 +32,7 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
   __shared__ int s_rank[kMaxExperts];
   __shared__ float s_row[kMaxExperts * kGateCols];           // gate table by slot, built in LDS
   __shared__ int s_cnt[4], s_uni[4];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int E = g.E, A = g.T * g.top_k;
   const bool want_gates = g.slot_gate && (g.gates || s_gates_in);
   const int* s_ids = s_ids_in ? s_ids_in : s_ids_own;
@@ -256,7 +256,7 @@ __device__ __forceinline__ void route_body(const RouteArgs& g, const GroupArgs& 
   __shared__ float s_sel[kMaxTopK];
   __shared__ float s_gates[kMaxTopK];
   __shared__ float s_prob[kMaxExperts];
-  const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int t = blockIdx.x, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int E = g.E, top_k = g.top_k;
   const float* x = g.hidden + (size_t)t * g.d;
   const int n_batches = (E + kRouteBatch - 1) / kRouteBatch;
@@ -329,7 +329,7 @@ constexpr int kLogitExperts = 16;
 
 __global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, double* __restrict__ logits) {
   __shared__ double s_part[kLogitWaves][kLogitExperts];
-  const int t = blockIdx.x, e_lo = blockIdx.y * kLogitExperts, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int t = blockIdx.x, e_lo = blockIdx.y * kLogitExperts, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int nE = min(kLogitExperts, g.E - e_lo);
   const float* x = g.hidden + (size_t)t * g.d;
   const int n_batches = (nE + kRouteBatch - 1) / kRouteBatch;
