@@ -208,6 +208,33 @@ def main():
         stream_gbs = max(stream_gbs, probe.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     del probe
 
+    # ---- the gate/up kernel's weight loads alone (same grid, walk, loads and pipeline depth; no fragments, no
+    # matrix-core instructions): what the bytes cost on this access pattern, next to the real kernel's time ------
+    twin = None
+    if not fp8 and args.layout == "tiled":
+        n_list = sorted({min(n, cfg.n_experts) for n in (cfg.top_k, 2 * cfg.top_k, 3 * cfg.top_k, 4 * cfg.top_k)})
+        us = {}
+        for n in n_list:
+            reps = []
+            for rep in range(5):
+                w = lw[(rep + n) % L]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                binding.moe_weight_load_twin(w.tensors[1], w.tensors[2], n, cfg.ffn // 16, cfg.d // 32, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                reps.append(e0.elapsed_time(e1) * 1e3)
+            us[n] = float(np.median(reps[1:]))
+        # time = a + b * slots (least squares), read at this run's mean number of live slots
+        xs, ys = np.array(list(us.keys()), dtype=np.float64), np.array(list(us.values()))
+        b_fit, a_fit = np.polyfit(xs, ys, 1) if len(xs) > 1 else (0.0, ys[0])
+        mean_slots = float((nu_h.astype(np.int64) + cfg.n_shared).mean())
+        twin = {"us_by_slots": {str(k): round(v, 2) for k, v in us.items()},
+                "fit_us": [round(float(a_fit), 2), round(float(b_fit), 3)],
+                "us_at_mean_live_slots": round(float(a_fit + b_fit * mean_slots), 2),
+                "gateup_kernel_avg_launch_us": roofline["avg_launch_us"],
+                "note": "one HIP event pair per launch in both figures"}
+
     # ---- CPU oracle beside it (bounded sample, single thread) ---------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -253,7 +280,8 @@ def main():
                                + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
                                + f", rho={args.rho}, {L} rotating resident layers, {args.layout} weight layout"},
         "frac_hbm_peak": round(float(value / HBM_PEAK_GBS), 4),
-        "by_K": by_k, "roofline": roofline, "stream_read_GBps": round(stream_gbs, 1), "cpu_baseline": cpu,
+        "by_K": by_k, "roofline": roofline, "stream_read_GBps": round(stream_gbs, 1),
+        "gateup_load_twin": twin, "cpu_baseline": cpu,
     }
     print(json.dumps(res))
 

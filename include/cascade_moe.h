@@ -272,6 +272,16 @@ moe_status moe_ctx_profile_read(moe_ctx* ctx, double* ms_sum, int64_t* steps);
  * published HBM peak. */
 moe_status moe_stream_read_probe(const void* src, int64_t bytes, float* sink, void* stream);
 
+/* Measurement aid: the weight loads of the tiled bf16 gate/up kernel and nothing else — the same grid (`tiles` x
+ * `slots` wavefronts), each streaming the tile row of matrix a and the tile row of matrix b (`steps` contiguous
+ * 1 KB blocks each, `slot_stride` bytes from one slot's matrix to the next) with the same non-temporal 128-bit
+ * loads at the same software-pipeline depth, folding the words into `sink` (DEVICE, >= 4096 words) instead of
+ * feeding matrix-core instructions.  What it takes is the cost of the bytes alone on this access pattern: the
+ * difference to the real kernel bounds what any other arithmetic formulation of the step (wavefront dot products
+ * instead of matrix cores) could gain.  a, b: DEVICE, 16-byte aligned, each at least slots*slot_stride bytes. */
+moe_status moe_weight_load_twin(const void* a, const void* b, int32_t slots, int32_t tiles, int32_t steps,
+                                int64_t slot_stride, float* sink, void* stream);
+
 /* The launch plan moe_verify_layer would use for T tokens in flight on a layer of this shape, layout
  * (MOE_LAYOUT_*) and weight type (MOE_WEIGHT_*).  Pure host arithmetic (no device, no context): the plan
  * depends only on its arguments, because the union of experts the T tokens form (Section 2.4) is known on

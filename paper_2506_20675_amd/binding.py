@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED
 
 EXPORTS = ("moe_strerror", "moe_abi_version", "moe_ctx_create", "moe_ctx_destroy", "moe_ctx_workspace_bytes", "moe_ctx_tune",
            "moe_route", "moe_group", "moe_verify_layer", "moe_verify_layer_noalloc", "moe_verify_stack", "moe_chained_stack", "moe_decoder_stack", "moe_pack_matrix",
-           "moe_stream_read_probe", "moe_plan_query",
+           "moe_stream_read_probe", "moe_weight_load_twin", "moe_plan_query",
            "moe_ctx_profile", "moe_ctx_profile_read", "moe_pack_weights",
            "cascade_utility", "cascade_default_params", "cascade_ctrl_create", "cascade_ctrl_destroy",
            "cascade_next_k", "cascade_observe", "cascade_get_state")
@@ -125,6 +125,8 @@ def lib():
     L.moe_plan_query.argtypes = [ctypes.POINTER(MoeShape), c_int32, c_int32, c_int32, ctypes.POINTER(MoePlanInfo)]
     L.moe_stream_read_probe.restype = ctypes.c_int
     L.moe_stream_read_probe.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
+    L.moe_weight_load_twin.restype = ctypes.c_int
+    L.moe_weight_load_twin.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int64, c_void_p, c_void_p]
     L.cascade_utility.restype = c_double
     L.cascade_utility.argtypes = [c_double, c_double, c_double]
     L.cascade_default_params.restype = None
@@ -450,6 +452,13 @@ def moe_stream_read_probe(src, sink, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib().moe_stream_read_probe(_ptr(src), nbytes - nbytes % 16, _ptr(sink), _stream_ptr(stream)),
            "moe_stream_read_probe")
+
+
+def moe_weight_load_twin(a, b, slots, tiles, steps, sink, stream=None):
+    """The tiled bf16 gate/up kernel's weight loads alone, over the first `slots` matrices of a and b ([n, rows, K])."""
+    slot_stride = a.stride(0) * a.element_size()
+    _check(lib().moe_weight_load_twin(_ptr(a), _ptr(b), slots, tiles, steps, slot_stride, _ptr(sink), _stream_ptr(stream)),
+           "moe_weight_load_twin")
 
 
 # ---- host side ---------------------------------------------------------------------------------

@@ -77,6 +77,34 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
   if (lane == 0) atomicXor(reinterpret_cast<unsigned int*>(sink) + (blockIdx.x & 4095), acc);
 }
 
+// ------------------------------------------------------------------------------------------
+// Measurement aid: the weight loads of the tiled bf16 gate/up kernel and nothing else.  Same grid (one wave per
+// 16-row tile of each of `slots` matrices pairs), same walk (the tile row of matrix a and the tile row of matrix
+// b, `steps` contiguous 1 KB blocks each), same non-temporal 128-bit loads, same software pipeline of depth 6 —
+// but no activation fragments, no matrix-core instructions and no epilogue: the loaded words are XOR-folded into
+// `sink`.  Its duration is what ANY arithmetic formulation of the gate/up step (matrix cores, wavefront dot
+// products, ...) has to pay for the bytes alone on this access pattern.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void weight_load_twin_kernel(const char* __restrict__ a, const char* __restrict__ b,
+                                                             int steps, size_t slot_stride, float* __restrict__ sink) {
+  const int lane = threadIdx.x;
+  const char* pa = a + (size_t)blockIdx.y * slot_stride + (size_t)blockIdx.x * steps * 1024;
+  const char* pb = b + (size_t)blockIdx.y * slot_stride + (size_t)blockIdx.x * steps * 1024;
+  uint32_t acc = 0;
+  pipeline<2, 1, true, 6>(
+      steps,
+      [&](Stage<2, 1, true>& st, int s) {
+        st.a[0] = ld128<true>(pa, lane * 16 + (uint32_t)s * 1024);
+        st.a[1] = ld128<true>(pb, lane * 16 + (uint32_t)s * 1024);
+      },
+      [&](const Stage<2, 1, true>& st) {
+        acc ^= st.a[0].x ^ st.a[0].y ^ st.a[0].z ^ st.a[0].w ^ st.a[1].x ^ st.a[1].y ^ st.a[1].z ^ st.a[1].w;
+      });
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o);
+  if (lane == 0) atomicXor(reinterpret_cast<unsigned int*>(sink) + ((blockIdx.y * gridDim.x + blockIdx.x) & 4095), acc);
+}
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ------------------------------------------------------------------------------------------
@@ -874,6 +902,16 @@ moe_status moe_stream_read_probe(const void* src, int64_t bytes, float* sink, vo
   const size_t per_wave = ((n16 + blocks * 4 - 1) / (blocks * 4) + 511) / 512 * 512;  // whole batches of 8 loads
   hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const uint4*>(src), per_wave, n16, sink);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+moe_status moe_weight_load_twin(const void* a, const void* b, int32_t slots, int32_t tiles, int32_t steps,
+                                int64_t slot_stride, float* sink, void* stream) {
+  if (!a || !b || !sink || slots < 1 || slots > 65535 || tiles < 1 || steps < 1 || !aligned16(a) || !aligned16(b))
+    return MOE_ERR_INVALID_ARG;
+  if (slot_stride < (int64_t)tiles * steps * 1024 || slot_stride % 16) return MOE_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(weight_load_twin_kernel, dim3(tiles, slots), dim3(64), 0, (hipStream_t)stream,
+                     static_cast<const char*>(a), static_cast<const char*>(b), steps, (size_t)slot_stride, sink);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 

@@ -328,3 +328,14 @@ def test_measurement_aids_profile_and_stream_probe():
         torch.cuda.synchronize()
         fold = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
         assert fold == np.bitwise_xor.reduce(host), n_words
+    # the gate/up kernel's load twin: every word of the first `slots` matrices of both tensors reaches the sink once
+    for slots, tiles, steps in ((1, 1, 1), (2, 5, 7), (3, 4, 13)):
+        A = rng.integers(0, 2**16, (3, tiles * 16, steps * 32), dtype=np.uint16)
+        B = rng.integers(0, 2**16, (3, tiles * 16, steps * 32), dtype=np.uint16)
+        sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+        binding.moe_weight_load_twin(_dev(A), _dev(B), slots, tiles, steps, sink)
+        torch.cuda.synchronize()
+        fold = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        want = np.bitwise_xor.reduce(A[:slots].reshape(-1).view(np.uint32)) ^ np.bitwise_xor.reduce(B[:slots].reshape(-1).view(np.uint32))
+        assert fold == want, (slots, tiles, steps)
+
