@@ -92,7 +92,8 @@ int64_t moe_ctx_workspace_bytes(const moe_ctx* ctx);
  *                       tiled gate/up kernels have one fixed shape per weight type)
  *   dn_split_k          0 = automatic, or a power of two <= 16; clamped to what the shape allows and to the
  *                       largest split the workspace was sized for at creation
- *   fused_down          -1 = automatic, 0 = never fuse the down projection with the combine
+ *   fused_down          -1 = automatic, 0 = never fuse the down projection with the combine, 1 = always (tiled
+ *                       weights; measured slower than split-K + combine beyond ~40 MB of down-projection bytes)
  * Host only, no device work.  MOE_ERR_INVALID_ARG for any other value. */
 moe_status moe_ctx_tune(moe_ctx* ctx, int32_t gu_tiles, int32_t dn_tiles, int32_t dn_split_k, int32_t fused_down);
 

@@ -138,7 +138,7 @@ struct moe_ctx {
   int u_max;              // largest possible union: min(E, max_tokens * top_k)
   int ks_alloc;           // split-K slabs the partial buffer is sized for
   int plan_override[3];   // moe_ctx_tune: gate/up tiles, down tiles, split-K factor; zero = automatic
-  bool no_fused_down;     // moe_ctx_tune: always use the split-K down projection
+  int fused_mode;         // moe_ctx_tune: -1 automatic, 0 never fuse down + combine, 1 always (tiled weights)
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
@@ -185,7 +185,7 @@ double expected_slots(const moe_shape& s, int T) {
 }
 
 // plan_override: three ints (gate/up tiles, down tiles, split-K factor), each zero = automatic (moe_ctx_tune)
-Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, int T, bool tiled, bool fp8) {
+Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int T, bool tiled, bool fp8) {
   const double slots = expected_slots(s, T);
   Plan p;
   p.gu_R = tiled ? 1 : ((s.ffn / 16 / 2) * kWaves * slots >= 1536 ? 2 : 1);
@@ -212,7 +212,7 @@ Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, 
   // to 16 waves; every item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
-  if (tiled && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes && !no_fused_down) {
+  if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes))) {
     int C = 1;
     while (slots * C < 2 * kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
     p.dn_fused_C = C;
@@ -223,7 +223,7 @@ Plan plan_for(const moe_shape& s, const int* plan_override, bool no_fused_down, 
   return p;
 }
 Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
-  return plan_for(c->s, c->plan_override, c->no_fused_down, T, tiled, fp8);
+  return plan_for(c->s, c->plan_override, c->fused_mode, T, tiled, fp8);
 }
 
 // Geometry-dependent host fields of a context (automatic plan; slab buffer sized for the largest split-K factor
@@ -234,7 +234,7 @@ void ctx_set_shape(moe_ctx* c, const moe_shape& s, int dev) {
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
   c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
-  c->no_fused_down = false;
+  c->fused_mode = -1;
   c->ks_alloc = 1;
   for (int T = 1; T <= s.max_tokens; ++T)
     for (bool tiled : {false, true})
@@ -397,10 +397,11 @@ void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipS
 // launch of its own: it is the liveness test at the top of the expert kernels.
 // unique / n_unique / n_unique_extra: optional DEVICE outputs.
 // out == NULL: the slabs are left for the caller (chained stack: chain_kernel sums them); *ks_used gets the
-// split-K factor they were written with.
+// split-K factor they were written with.  defer_combine (with out != NULL): the same, unless the down projection
+// is the fused one, which writes `out` itself (*ks_used = 0: nothing is pending).
 moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
                         float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
-                        int* ks_used = nullptr, const ChainArgs* pre = nullptr) {
+                        int* ks_used = nullptr, const ChainArgs* pre = nullptr, bool defer_combine = false) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
   if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;  // FP8 is streamed in the tiled layout only
@@ -461,7 +462,7 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   }
   mark(c, st);
   if (ks_used) *ks_used = p.dn_KS;
-  if (out) {
+  if (out && !defer_combine) {
     const int n4 = T * (s.d / 4);
     hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
                        (const int32_t*)c->tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
@@ -575,12 +576,12 @@ moe_status moe_ctx_tune(moe_ctx* c, int32_t gu_tiles, int32_t dn_tiles, int32_t 
   auto tiles_ok = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
   if (!c || !tiles_ok(gu_tiles) || !tiles_ok(dn_tiles) || dn_split_k < 0 || dn_split_k > kMaxKS) return MOE_ERR_INVALID_ARG;
   if (dn_split_k & (dn_split_k - 1)) return MOE_ERR_INVALID_ARG;  // powers of two only
-  if (fused_down != -1 && fused_down != 0) return MOE_ERR_INVALID_ARG;
+  if (fused_down < -1 || fused_down > 1) return MOE_ERR_INVALID_ARG;
   c->plan_override[0] = gu_tiles;
   c->plan_override[1] = dn_tiles;
   // the slab buffer was sized at creation for the automatic plan: a larger split does not fit
   c->plan_override[2] = dn_split_k < c->ks_alloc ? dn_split_k : c->ks_alloc;
-  c->no_fused_down = fused_down == 0;
+  c->fused_mode = fused_down;
   return MOE_OK;
 }
 
@@ -595,7 +596,7 @@ moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int
   if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;
   if (fp8 && (s.d % 64 || s.ffn % 64)) return MOE_ERR_UNSUPPORTED_SHAPE;
   const int automatic[3] = {0, 0, 0};
-  const Plan p = plan_for(s, automatic, false, T, tiled, fp8);
+  const Plan p = plan_for(s, automatic, -1, T, tiled, fp8);
   out->routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;
   out->expected_slots = expected_slots(s, T);
   out->wide_router = s.n_experts >= kWideRouterExperts;
@@ -692,13 +693,32 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
   }
   if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
-  const size_t per = (size_t)T * c->s.d;
+  const moe_shape& s = c->s;
+  const size_t per = (size_t)T * s.d;
+  // With the one-workgroup-per-token router the slab sum of layer l-1 rides at the head of layer l's router launch
+  // (the same workgroup shape; what the chained stack does with its residual pass): one launch less per layer.
+  const bool merge = s.n_experts < kWideRouterExperts && s.d <= 4 * kChainVecs * kChainThreads;
+  int ks = 0;  // > 0: the previous layer's slabs are waiting to be summed into its `out`
   for (int l = 0; l < L; ++l) {
+    ChainArgs a{};
+    if (ks > 0) {
+      a.partial = c->partial, a.tok_slot = c->tok_slot, a.resid_out = out + (size_t)(l - 1) * per;
+      a.d = s.d, a.T = T, a.top_k = s.top_k, a.u_max = c->u_max, a.n_shared = s.n_shared, a.max_tokens = s.max_tokens;
+      a.KS = ks;
+    }
     if (moe_status rc = launch_layer(c, layers + l, hidden + l * per, T, out + l * per, nullptr, nullptr, nullptr,
-                                     nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st))
+                                     nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks,
+                                     ks > 0 ? &a : nullptr, merge))
       return rc;
+    if (!merge) ks = 0;
   }
-  return MOE_OK;
+  if (ks > 0) {
+    const int n4 = T * (s.d / 4);
+    hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
+                       (const int32_t*)c->tok_slot, out + (size_t)(L - 1) * per, s.d, T, s.top_k, c->u_max, s.n_shared,
+                       s.max_tokens, ks);
+  }
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const uint16_t* const* gammas, int32_t L,

@@ -275,24 +275,42 @@ def test_batch_invariance_and_determinism_on_gpu():
     ctx.close()
 
 
-def test_stack_matches_per_layer_oracle():
+@pytest.mark.parametrize("T", [1, 4, 9])
+def test_stack_matches_per_layer_oracle(T):
+    """moe_verify_stack on independent per-layer inputs, with the fused down projection (every layer writes its own
+    output) and with the split-K one, where the slab sum of layer l-1 rides in layer l's router launch and only the
+    last layer has a combine launch of its own; both layouts; every layer against the oracle, and the two plans
+    against each other within rounding."""
     import torch
     cfg = synth.TINY
-    L, T = 3, 4
+    L = 4
     Ws = [synth.layer_weights_host(cfg, 10 + l) for l in range(L)]
     Wds = [_weights_dev(W) for W in Ws]
-    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
     x = np.stack([synth.hidden_host(cfg, 10 + l, 0, T, 0.5) for l in range(L)])
-    out = torch.zeros((L, T, cfg.d), dtype=torch.float32, device="cuda")
-    nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
-    ctx.moe_verify_stack([ctx.weights(w) for w in Wds], _dev(x), out, nu)
-    torch.cuda.synchronize()
-    for l in range(L):
-        ref32, rids, _ = orc.layer(x[l], Ws[l], cfg.top_k, 0, "f32")
-        ref64, _, _ = orc.layer(x[l], Ws[l], cfg.top_k, 0, "f64")
-        _check_out(out[l].cpu().numpy(), ref32, ref64)
-        assert int(nu[l].item()) == orc.union(rids, cfg.n_experts)["n_unique"]
-    ctx.close()
+    refs = [(orc.layer(x[l], Ws[l], cfg.top_k, 0, "f32"), orc.layer(x[l], Ws[l], cfg.top_k, 0, "f64")) for l in range(L)]
+    outs = {}
+    for fused in (-1, 0):
+        for tiled in (False, True):
+            ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+            ctx.moe_ctx_tune(fused_down=fused)
+            layers = [_tiled(ctx, w) if tiled else ctx.weights(w) for w in Wds]
+            out = torch.full((L, T, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+            nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+            for rep in range(2):          # twice: the second pass meets the first one's slabs and tables
+                ctx.moe_verify_stack(layers, _dev(x), out, nu)
+            torch.cuda.synchronize()
+            for l in range(L):
+                (ref32, rids, _), (ref64, _, _) = refs[l]
+                _check_out(out[l].cpu().numpy(), ref32, ref64)
+                assert int(nu[l].item()) == orc.union(rids, cfg.n_experts)["n_unique"]
+            # the stack call gives what L single-layer calls give, bit for bit
+            for l in range(L):
+                one = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+                ctx.moe_verify_layer(layers[l], _dev(x[l]), one)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(one.cpu().numpy(), out[l].cpu().numpy())
+            outs[(fused, tiled)] = out.cpu().numpy()
+            ctx.close()
 
 
 def test_argument_errors_are_reported_not_launched():
