@@ -40,7 +40,8 @@ class Params:
     base_refresh: int = 100   # refresh t_base about this often (Section 5.3)
     s_max: int = 0            # cap on the backed-off set length; 0 = none
     converge_frac: float = 0.10  # early exit (3) of Section 5.6
-    backoff: int = 1          # 0 disables adaptive back-off (Section 5.5), for ablation
+    backoff: int = 2          # adaptive back-off (Section 5.5): 0 off (ablation); 2 every drop to K = 0 doubles S, the
+                              # first included (the paper's wording); 1 the first disabled phase keeps S
     hillclimb: int = 1        # 0: test only K_start (Section 7.4 ablation)
 
 
@@ -52,7 +53,8 @@ class Controller:
         self.p = p or Params()
         p = self.p
         if min(p.t_trial, p.max_trials, p.s_set, p.k_max, p.base_iters, p.base_refresh) < 1 \
-                or not (1 <= p.k_start <= p.k_max) or p.s_max < 0 or not (p.converge_frac >= 0.0):
+                or not (1 <= p.k_start <= p.k_max) or p.s_max < 0 or not (p.converge_frac >= 0.0) \
+                or p.backoff not in (0, 1, 2):
             raise ValueError("bad parameters")
         self.iters = 0
         self.t_base = math.nan
@@ -100,8 +102,9 @@ class Controller:
     def _enter_set(self, k_set: int):
         p = self.p
         if k_set == 0:
-            # Section 5.5: double S whenever K drops to 0; first disabled phase keeps S0.
-            if p.backoff and self.prev_set_k == 0:
+            # Section 5.5: "double the set phase length S whenever K drops to 0" (backoff = 2: every drop, the
+            # first included; backoff = 1: the first disabled phase keeps S, further consecutive ones double).
+            if p.backoff == 2 or (p.backoff == 1 and self.prev_set_k == 0):
                 self.s_cur = self.s_cur * 2
                 if p.s_max > 0 and self.s_cur > p.s_max:
                     self.s_cur = p.s_max

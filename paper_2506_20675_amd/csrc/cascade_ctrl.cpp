@@ -90,8 +90,11 @@ void enter_test(cascade_ctrl* c) {
 
 void enter_set(cascade_ctrl* c, int32_t k_set) {
   const cascade_params& p = c->p;
-  if (k_set == 0 && p.backoff && c->prev_set_k == 0) {
-    c->s_cur *= 2;  // consecutive drop to K = 0: test half as often
+  // Section 5.5: "double the set phase length S whenever K drops to 0".  backoff = 2 takes that literally (the
+  // first disabled set phase already lasts 2 S); backoff = 1 lets the first one keep S and doubles from the second
+  // consecutive drop on.  Any set phase that speculates puts S back.
+  if (k_set == 0 && p.backoff && (p.backoff == 2 || c->prev_set_k == 0)) {
+    c->s_cur *= 2;
     if (p.s_max > 0 && c->s_cur > p.s_max) c->s_cur = p.s_max;
   } else {
     c->s_cur = p.s_set;
@@ -180,7 +183,7 @@ void cascade_default_params(cascade_params* p) {
   p->base_refresh = 100;
   p->s_max = 0;
   p->converge_frac = 0.10;
-  p->backoff = 1;
+  p->backoff = 2;
   p->hillclimb = 1;
 }
 
@@ -192,7 +195,7 @@ cascade_ctrl* cascade_ctrl_create(const cascade_params* params) {
     cascade_default_params(&p);
   if (p.t_trial < 1 || p.max_trials < 1 || p.s_set < 1 || p.k_max < 1 || p.base_iters < 1 || p.base_refresh < 1 ||
       p.k_start < 1 || p.k_start > p.k_max || p.s_max < 0 || !(p.converge_frac >= 0.0) || p.s_set > (1 << 24) ||
-      p.s_max > (1 << 24))
+      p.s_max > (1 << 24) || p.backoff < 0 || p.backoff > 2)
     return nullptr;
   cascade_ctrl* c = new (std::nothrow) cascade_ctrl();
   if (!c) return nullptr;

@@ -19,24 +19,52 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
 import sys
 
 import numpy as np
 
 from . import binding, synth
 
-# Measured on MI355X, rho = 0.5.  *-layer: `python bench.py [--weights fp8]`, by_K latency_us of one
-# Mixtral-shaped layer-step.  *-stack32: `python -m paper_2506_20675_amd.stack_driver --iters 600 --layers 32
-# --static 0,1,2,3 [--weights fp8 | --chained | --decoder]`, median ms per iteration (K = 0..3 from the static runs, K = 4, 5
-# from the controller run where it chose them).
-MEASURED = {
-    "mixtral-bf16-layer": [122.7, 186.6, 226.8, 237.5, 240.7, 289.8, 288.1, 318.2, 299.2],
-    "mixtral-fp8-layer": [77.5, 108.6, 131.3, 136.9, 139.4, 165.2, 164.4, 175.6, 201.4],
-    "mixtral-bf16-stack32": [3.93, 5.87, 7.17, 8.03, 8.68, 9.11],
-    "mixtral-fp8-stack32": [2.46, 3.42, 4.15, 4.60, 4.89],
-    "mixtral-bf16-stack32-chained": [3.97, 6.54, 8.53, 9.97],
-    "mixtral-bf16-stack32-decoder": [4.81, 6.90, 8.23, 9.36],     # --decoder: attention stub + MoE per block
-}
+# Verification-cost tables measured on an MI355X (rho = 0.5) live in measured_costs.json next to this module, each
+# with the command that produced it; `--record NAME --bench-json FILE` (or --stack-json FILE) rewrites an entry from
+# a fresh bench.py / stack_driver line, so the tables follow the kernels instead of being typed in.
+_MEASURED_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "measured_costs.json")
+
+
+def _load_measured() -> dict:
+    with open(_MEASURED_FILE) as f:
+        return {name: entry["cost"] for name, entry in json.load(f).items()}
+
+
+MEASURED = _load_measured()
+
+
+def record_measured(name: str, cost, unit: str, command: str) -> None:
+    """Replace (or add) one table of measured_costs.json."""
+    with open(_MEASURED_FILE) as f:
+        data = json.load(f)
+    data[name] = {"cost": [round(float(c), 4) for c in cost], "unit": unit, "command": command}
+    with open(_MEASURED_FILE, "w") as f:
+        json.dump(data, f, indent=1, sort_keys=True)
+        f.write("\n")
+    MEASURED[name] = data[name]["cost"]
+
+
+def from_stack_json(line: str) -> np.ndarray:
+    """t_verify per iteration for K = 0, 1, ... from a stack_driver line: the static-K runs first, then the K the
+    controller run reached beyond them."""
+    d = json.loads(line)
+    cost, k = [], 0
+    while True:
+        v = d.get(f"static_{k}", {}).get("t_verify_ms_by_K", {}).get(str(k))
+        if v is None:
+            v = d.get("cascade", {}).get("t_verify_ms_by_K", {}).get(str(k))
+        if v is None:
+            break
+        cost.append(v)
+        k += 1
+    return np.array(cost)
 
 
 def monotone(cost) -> np.ndarray:
@@ -130,8 +158,8 @@ def run_cascade(trace: Trace, cost: np.ndarray, name="cascade", **params):
 
 ABLATION = (  # Section 7.4: the parts of the policy added one at a time
     ("test K_start only, disable when U < 1", dict(hillclimb=0, backoff=0)),
-    ("+ adaptive back-off", dict(hillclimb=0, backoff=1)),
-    ("+ hill-climbing (full policy)", dict(hillclimb=1, backoff=1)),
+    ("+ adaptive back-off", dict(hillclimb=0, backoff=2)),
+    ("+ hill-climbing (full policy)", dict(hillclimb=1, backoff=2)),
 )
 
 
@@ -168,6 +196,27 @@ def run_concurrent(traces, cost: np.ndarray, **params):
             "tokens_per_request": [int(v) for v in toks.sum(axis=0)], "k_max_per_request": params["k_max"]}
 
 
+def backoff_example(window=250, cost_ratio=2.0):
+    """The worked example of Section 5.5 from the start of a request: speculation never pays (no draft is ever
+    accepted, every speculative iteration costs `cost_ratio` x a plain one), t = 4, S = 16.  For no back-off and for
+    the two readings of "double S whenever K drops to 0": speculative-trial iterations among the first `window`
+    iterations, and the slowdown over never speculating.  The paper quotes "nearly 50" against "only 18" and a
+    worst-case slowdown of 14 % against 5 %."""
+    out = {}
+    for name, bo in (("no back-off", 0), ("first disabled phase keeps S", 1), ("every drop doubles S", 2)):
+        ctrl = binding.CascadeController(backoff=bo)
+        spec, t = 0, 0.0
+        for _ in range(window):
+            k = ctrl.next_k()
+            dt = cost_ratio if k > 0 else 1.0
+            ctrl.observe(k, 1, dt)
+            spec += k > 0
+            t += dt
+        ctrl.close()
+        out[name] = {"trial_iters": int(spec), "slowdown": round(t / window - 1.0, 4)}
+    return out
+
+
 def study(cost, iters=6000, seed_field=0, rates=synth.ACCEPT_RATES, period=synth.REGIME_PERIOD):
     cost = cost_table(cost)
     trace = Trace(iters, seed_field, rates, period)
@@ -191,6 +240,9 @@ def study(cost, iters=6000, seed_field=0, rates=synth.ACCEPT_RATES, period=synth
     # stretches against the time it takes to notice that acceptance has recovered
     for cap in (0, 32, 64, 128):
         res["backoff_cap"].append(rel(run_cascade(trace, cost, f"s_max={cap}", s_max=cap)))
+    # the two readings of the back-off rule on this trace, and on the paper's own worked example
+    res["backoff_reading"] = [rel(run_cascade(trace, cost, f"backoff={bo}", backoff=bo)) for bo in (1, 2)]
+    res["backoff_example_250"] = backoff_example()
     return res
 
 
@@ -201,8 +253,21 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=6000)
     ap.add_argument("--requests", type=int, default=0, help="also run this many concurrent requests (0 = skip)")
     ap.add_argument("--period", type=int, default=synth.REGIME_PERIOD, help="iterations an acceptance regime lasts")
+    ap.add_argument("--stack-json", default=None, help="file holding a stack_driver line; its t_verify per K is the table")
+    ap.add_argument("--record", default=None, metavar="NAME",
+                    help="store the table of --bench-json / --stack-json in measured_costs.json under NAME and exit")
+    ap.add_argument("--command", default="", help="with --record: the command that produced the line")
     a = ap.parse_args(argv)
-    if a.bench_json:
+    if a.record:
+        src = a.bench_json or a.stack_json
+        line = [l for l in open(src) if l.startswith("{")][-1]
+        cost = from_bench_json(line) if a.bench_json else from_stack_json(line)
+        record_measured(a.record, cost, "us per layer-step" if a.bench_json else "ms per iteration", a.command)
+        print(f"{a.record}: {list(MEASURED[a.record])}")
+        return 0
+    if a.stack_json:
+        cost = from_stack_json([l for l in open(a.stack_json) if l.startswith("{")][-1])
+    elif a.bench_json:
         cost = from_bench_json([l for l in open(a.bench_json) if l.startswith("{")][-1])
     elif a.cost == "model":
         cost = balls_in_bins()

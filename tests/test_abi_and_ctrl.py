@@ -68,7 +68,7 @@ def test_utility_matches_paper_examples_and_oracle():
 def test_default_params_are_the_papers():
     p = binding.cascade_default_params()
     assert (p.t_trial, p.max_trials, p.s_set, p.k_start, p.base_iters, p.base_refresh) == (4, 4, 16, 3, 4, 100)
-    assert p.k_max == 8 and p.converge_frac == 0.10 and p.backoff == 1 and p.hillclimb == 1
+    assert p.k_max == 8 and p.converge_frac == 0.10 and p.backoff == 2 and p.hillclimb == 1
     q = co.Params()
     for f in ("t_trial", "max_trials", "s_set", "k_max", "k_start", "base_iters", "base_refresh", "s_max",
               "converge_frac", "backoff", "hillclimb"):
@@ -79,7 +79,7 @@ def _replay(seed, n_iter=2500):
     rng = np.random.default_rng(seed)
     kw = dict(t_trial=int(rng.integers(1, 6)), max_trials=int(rng.integers(1, 6)), s_set=int(rng.integers(1, 24)),
               k_max=int(rng.integers(1, 9)), base_iters=int(rng.integers(1, 6)), base_refresh=int(rng.integers(5, 150)),
-              s_max=int(rng.choice([0, 64])), backoff=int(rng.integers(0, 2)), hillclimb=int(rng.integers(0, 2)))
+              s_max=int(rng.choice([0, 64])), backoff=int(rng.integers(0, 3)), hillclimb=int(rng.integers(0, 2)))
     if seed == 0:
         kw = {}
     kw["k_start"] = int(rng.integers(1, kw.get("k_max", 8) + 1)) if seed else 3

@@ -38,7 +38,8 @@ def test_low_acceptance_backoff_bounds_the_slowdown():
     tr = cs.Trace(4000, 2, rates=(0.1,))
     base = cs.run_static(tr, cost, 0)["tpot"]
     no_bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=0)
-    bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=1)
+    bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=2)
+    assert cs.run_cascade(tr, cost, hillclimb=1, backoff=1)["trial_iters"] >= bo["trial_iters"]   # the later start tests more
     assert bo["tpot"] < no_bo["tpot"]
     assert bo["trial_iters"] < no_bo["trial_iters"] / 3
     assert bo["tpot"] / base < 1.02                      # within 2 % of never speculating
