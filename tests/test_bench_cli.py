@@ -28,7 +28,8 @@ def test_fp8_needs_the_tiled_layout():
 def test_traffic_figure_comes_from_the_committed_counter_summaries():
     """roofline.traffic is read from profiles/: the files must be there, carry the line bench.py parses, and agree
     with the algorithmic bytes they quote to within a few percent (no wasted re-reads)."""
-    for name in ("gateup_kernel_mixtral_hbm_traffic.txt", "gateup_kernel_mixtral_fp8_hbm_traffic.txt"):
+    for name in ("gateup_kernel_mixtral_hbm_traffic.txt", "gateup_kernel_mixtral_fp8_hbm_traffic.txt",
+                 "gateup_kernel_olmoe_hbm_traffic.txt", "gateup_kernel_deepseek_hbm_traffic.txt"):
         text = open(os.path.join(ROOT, "profiles", name)).read()
         traffic = [int(l.split()[-1]) for l in text.splitlines() if l.startswith("traffic_bytes_per_launch gateup_kernel")]
         alg = [int(l.split("=")[-1]) for l in text.splitlines() if l.startswith("algorithmic bytes per launch")]
