@@ -330,9 +330,10 @@ typedef struct {
   int32_t base_refresh; /* re-measure t_base after about this many iterations    (100) */
   int32_t s_max;        /* cap on the backed-off set length, 0 = uncapped        (0)   */
   double converge_frac; /* early exit when successive utilities differ by less   (0.10)*/
-  int32_t backoff;      /* adaptive back-off (Section 5.5): 0 off; 2 every drop to K = 0 doubles S, the first
-                           included (the paper's wording); 1 the first disabled set phase keeps S and every
-                           further consecutive one doubles                       (2)   */
+  int32_t backoff;      /* adaptive back-off (Section 5.5): 0 off; 1 the first disabled set phase keeps S and every
+                           further consecutive one doubles (utility "persistently" below 1, as the section's
+                           figure puts it); 2 every drop to K = 0 doubles S, the first included (the section's
+                           sentence taken literally)                             (1)   */
   int32_t hillclimb;    /* 1 = hill-climbing search (Section 5.6) on             (1)   */
 } cascade_params;
 void cascade_default_params(cascade_params* p);

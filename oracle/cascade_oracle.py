@@ -40,8 +40,9 @@ class Params:
     base_refresh: int = 100   # refresh t_base about this often (Section 5.3)
     s_max: int = 0            # cap on the backed-off set length; 0 = none
     converge_frac: float = 0.10  # early exit (3) of Section 5.6
-    backoff: int = 2          # adaptive back-off (Section 5.5): 0 off (ablation); 2 every drop to K = 0 doubles S, the
-                              # first included (the paper's wording); 1 the first disabled phase keeps S
+    backoff: int = 1          # adaptive back-off (Section 5.5): 0 off (ablation); 1 the first disabled set phase keeps S
+                              # and every further consecutive one doubles (the section's figure: "persistently" below
+                              # 1); 2 every drop to K = 0 doubles S, the first included (the section's sentence)
     hillclimb: int = 1        # 0: test only K_start (Section 7.4 ablation)
 
 

@@ -158,8 +158,8 @@ def run_cascade(trace: Trace, cost: np.ndarray, name="cascade", **params):
 
 ABLATION = (  # Section 7.4: the parts of the policy added one at a time
     ("test K_start only, disable when U < 1", dict(hillclimb=0, backoff=0)),
-    ("+ adaptive back-off", dict(hillclimb=0, backoff=2)),
-    ("+ hill-climbing (full policy)", dict(hillclimb=1, backoff=2)),
+    ("+ adaptive back-off", dict(hillclimb=0, backoff=1)),
+    ("+ hill-climbing (full policy)", dict(hillclimb=1, backoff=1)),
 )
 
 

@@ -68,7 +68,7 @@ def test_utility_matches_paper_examples_and_oracle():
 def test_default_params_are_the_papers():
     p = binding.cascade_default_params()
     assert (p.t_trial, p.max_trials, p.s_set, p.k_start, p.base_iters, p.base_refresh) == (4, 4, 16, 3, 4, 100)
-    assert p.k_max == 8 and p.converge_frac == 0.10 and p.backoff == 2 and p.hillclimb == 1
+    assert p.k_max == 8 and p.converge_frac == 0.10 and p.backoff == 1 and p.hillclimb == 1
     q = co.Params()
     for f in ("t_trial", "max_trials", "s_set", "k_max", "k_start", "base_iters", "base_refresh", "s_max",
               "converge_frac", "backoff", "hillclimb"):

