@@ -323,6 +323,26 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.status == -1
     with pytest.raises(ValueError):
         ctx.moe_route(x[:2, :32].contiguous(), rw)
+    # the tuning aid takes 0 / 1 / 2 / 4 tiles, a power-of-two split up to 16, and -1 / 0 / 1 for the fused down kernel
+    for bad in ((3, 0, 0, -1), (0, 8, 0, -1), (0, 0, 3, -1), (0, 0, 32, -1), (0, 0, 0, 2), (0, 0, 0, -2)):
+        with pytest.raises(binding.MoeError) as e:
+            ctx.moe_ctx_tune(*bad)
+        assert e.value.status == -1
+    ctx.moe_ctx_tune(1, 4, 16, 0)                   # accepted; the split is clamped to what this shape allows
+    ctx.moe_ctx_tune()                              # back to automatic
+    # weights built for another geometry are refused by the binding before the library sees a pointer
+    other = binding.MoeContext(64, 128, 4, 2, 0, 4)
+    Wd = {n: torch.zeros(shp, dtype=torch.int16, device="cuda") for n, shp in
+          (("router_w", (4, 64)), ("w1", (4, 128, 64)), ("w3", (4, 128, 64)), ("w2", (4, 64, 128)))}
+    with pytest.raises(ValueError):
+        ctx.moe_verify_layer(other.weights(Wd), x[:2].contiguous(), torch.zeros((2, 64), device="cuda"))
+    # a stream that lives on this device is accepted explicitly
+    st = torch.cuda.Stream()
+    ok = binding.MoeContext(64, 128, 4, 2, 0, 4)
+    ok.moe_route(x[:2].contiguous(), rw, stream=st)
+    st.synchronize()
+    ok.close()
+    other.close()
     ctx.close()
 
 

@@ -89,3 +89,43 @@ def test_noalloc_entry_point_rejects_what_does_not_fit_and_bad_arguments():
                                     None, None, None, None, None)
     assert rc == -1, rc                                                  # T beyond max_tokens
     torch.cuda.synchronize()
+
+
+def test_noalloc_entry_point_replays_from_a_hip_graph():
+    """What the entry point is for: after one eager call (which looks the workspace address up), the call is captured
+    in a HIP graph — its workspace preparation is a kernel, not a memset node — and replays, with eager work and
+    synchronisation in between, give the eager bits for every input."""
+    import torch
+    cfg = synth.TINY
+    T = 4
+    W = synth.layer_weights_host(cfg, 44)
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    lw = ctx.moe_pack_weights(ctx.weights(_weights_dev(W)))
+    xs = [_dev(synth.hidden_host(cfg, 44, it, T, 0.5)) for it in range(3)]
+    eager = []
+    for x in xs:
+        o = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+        binding.moe_verify_layer_noalloc(ctx.shape, lw, x, o)
+        torch.cuda.synchronize()
+        eager.append(o)
+    x_static, out = xs[0].clone(), torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        binding.moe_verify_layer_noalloc(ctx.shape, lw, x_static, out)      # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            binding.moe_verify_layer_noalloc(ctx.shape, lw, x_static, out)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for x, want in zip(xs, eager):
+            x_static.copy_(x)
+            out.fill_(-1.0)
+            other = torch.zeros((9, cfg.d), dtype=torch.float32, device="cuda")
+            ctx.moe_verify_layer(lw, _dev(synth.hidden_host(cfg, 44, 9, 9, 0.5)), other)   # eager work in between
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want)
+    ctx.close()
