@@ -111,7 +111,7 @@ def test_layer_parity_mixtral_full_size():
     torch.cuda.synchronize()
     assert (Wd["w2"][3, 100:200].cpu().numpy().view(np.uint16) == W["w2"][3, 100:200]).all()
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
-    for it, (T, rho) in enumerate(((1, 0.5), (9, 0.0))):
+    for it, (T, rho) in enumerate(((1, 0.5), (9, 0.0), (4, 0.5), (8, 0.9))):
         x = synth.hidden_host(cfg, 0, 300 + it, T, rho)
         _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0), W, x, ctx, Wd)
     ctx.close()

@@ -78,7 +78,7 @@ def test_gpu_parity_inputs_route_the_same_under_fp32_accumulation():
     T_rho = ((1, 0.5), (2, 0.0), (5, 0.9), (9, 0.0), (9, 0.5), (9, 0.9))
     for cfg in (synth.TINY, synth.OLMOE, synth.DEEPSEEK, synth.MIXTRAL):                       # router parity
         _check(cfg, [(0, 100 + it, T, rho) for it, (T, rho) in enumerate(T_rho)])
-    _check(synth.MIXTRAL, [(0, 300, 1, 0.5), (0, 301, 9, 0.0), (0, 500, 1, 0.5), (0, 501, 5, 0.0)])   # full size, bf16 and FP8
+    _check(synth.MIXTRAL, [(0, 300, 1, 0.5), (0, 301, 9, 0.0), (0, 302, 4, 0.5), (0, 303, 8, 0.9), (0, 500, 1, 0.5), (0, 501, 5, 0.0)])   # full size, bf16 and FP8
     for cfg in (synth.OLMOE, synth.DEEPSEEK):
         _check(cfg, [(1, 200, 1, 0.5), (1, 201, 4, 0.0), (1, 202, 9, 0.9), (1, 400, 1, 0.5), (1, 401, 9, 0.9)])
     for cfg in (synth.PHI35, synth.QWEN15):
