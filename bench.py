@@ -31,8 +31,11 @@ BY_K_STEPS = 20        # layer-steps per K in the latency-vs-K table (a sample o
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=180)
-    ap.add_argument("--warmup", type=int, default=18)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 180; 36 with --stack)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps (default 18; 9 with --stack)")
+    ap.add_argument("--stack", type=int, default=0, metavar="L",
+                    help="a step = ONE moe_verify_stack call over L distinct resident layers (32 = the 90 GB Mixtral-shaped "
+                         "stack) instead of one moe_verify_layer call; latencies are still reported per layer")
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--layers", type=int, default=8, help="distinct resident layers rotated through")
     ap.add_argument("--config", default="mixtral-8x7b-shaped")
@@ -50,6 +53,10 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.steps is None:
+        args.steps = 36 if args.stack else 180
+    if args.warmup is None:
+        args.warmup = 9 if args.stack else 18
     fp8 = args.weights == "fp8"
     if fp8 and args.layout != "tiled":
         print("bench.py: FP8 weights are streamed in the tiled layout only", file=sys.stderr)
@@ -65,7 +72,10 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     expert_bytes = cfg.expert_bytes_fp8 if fp8 else cfg.expert_bytes
-    L, K_steps, W_steps = args.layers, args.steps, args.warmup
+    S = args.stack                       # layers per step in stack mode, 0 = single-layer steps
+    L, K_steps, W_steps = (S or args.layers), args.steps, args.warmup
+    LS = S or 1
+    by_k_steps = 4 if S else BY_K_STEPS  # a stack step is S layer-steps already
     T_MAX = 9
 
     # ---- resident inputs -------------------------------------------------------------------
@@ -87,17 +97,29 @@ def main():
     def k_of(i):
         return args.fixed_k if args.fixed_k >= 0 else i % T_MAX
 
-    hid = []
-    for i in range(total):
-        T = k_of(i) + 1
-        hid.append(torch.from_numpy(synth.hidden_host(cfg, i % L, i, T, args.rho)).cuda())
+    def hidden(layer, it, T):
+        """Input of one step: [T, d] for layer `layer`, or in stack mode [S, T, d] for layers 0..S-1 (independent
+        seeded per-layer inputs)."""
+        if S:
+            return torch.from_numpy(np.stack([synth.hidden_host(cfg, l, it, T, args.rho) for l in range(S)])).cuda()
+        return torch.from_numpy(synth.hidden_host(cfg, layer, it, T, args.rho)).cuda()
+
+    hid = [hidden(i % L, i, k_of(i) + 1) for i in range(total)]
     outs = [torch.empty((T_MAX, cfg.d), dtype=torch.float32, device="cuda") for _ in range(2)]
-    nu = torch.zeros((total,), dtype=torch.int32, device="cuda")
+    outs_stack = {T: torch.empty((S, T, cfg.d), dtype=torch.float32, device="cuda") for T in range(1, T_MAX + 1)} if S else None
+    nu = torch.zeros((total, LS), dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
 
+    def run(layer, x, nu_row, parity_slot):
+        """One step of the path on input x: a single layer, or the whole stack in one call."""
+        T = x.shape[-2]
+        if S:
+            ctx.moe_verify_stack(lw, x, outs_stack[T], nu_row)
+        else:
+            ctx.moe_verify_layer(lw[layer], x, outs[parity_slot][:T], n_unique=nu_row)
+
     def step(i):
-        T = k_of(i) + 1
-        ctx.moe_verify_layer(lw[i % L], hid[i], outs[i & 1][:T], n_unique=nu[i:i + 1])
+        run(i % L, hid[i], nu[i], i & 1)
 
     # ---- warm-up, then the timed region: exactly K_steps steps, nothing else on the stream -----
     for i in range(W_steps):
@@ -109,7 +131,7 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    nu_h = nu.cpu().numpy()[W_steps:]
+    nu_h = nu.cpu().numpy()[W_steps:].reshape(-1)          # one entry per layer-step
     ubytes = (nu_h.astype(np.int64) + cfg.n_shared) * expert_bytes
     value = ubytes.sum() / wall / 1e9
 
@@ -117,14 +139,13 @@ def main():
     # One event pair around each group of BY_K_STEPS steps (an event between every two steps would put an extra
     # packet into each kernel chain, and a pair around two or three steps would not amortise its own latency).
     k_list = [args.fixed_k] if args.fixed_k >= 0 else list(range(T_MAX))
-    sample = {k: [(j % L, 50_000 + 100 * k + j) for j in range(BY_K_STEPS)] for k in k_list}
-    s_hid = {k: [torch.from_numpy(synth.hidden_host(cfg, l, it, k + 1, args.rho)).cuda() for l, it in sample[k]]
-             for k in k_list}
-    s_nu = torch.zeros((len(k_list), BY_K_STEPS), dtype=torch.int32, device="cuda")
+    sample = {k: [(j % L, 50_000 + 100 * k + j) for j in range(by_k_steps)] for k in k_list}
+    s_hid = {k: [hidden(l, it, k + 1) for l, it in sample[k]] for k in k_list}
+    s_nu = torch.zeros((len(k_list), by_k_steps, LS), dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
 
     def sample_step(ki, k, j):
-        ctx.moe_verify_layer(lw[sample[k][j][0]], s_hid[k][j], outs[j & 1][:k + 1], n_unique=s_nu[ki, j:j + 1])
+        run(sample[k][j][0], s_hid[k][j], s_nu[ki, j], j & 1)
 
     by_k = {}
     for ki, k in enumerate(k_list):
@@ -132,22 +153,22 @@ def main():
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for j in range(BY_K_STEPS):
+            for j in range(by_k_steps):
                 sample_step(ki, k, j)
             e1.record()
             torch.cuda.synchronize()
-            reps.append(e0.elapsed_time(e1) / BY_K_STEPS)
+            reps.append(e0.elapsed_time(e1) / (by_k_steps * LS))          # per layer-step
         lat_ms = float(np.median(reps))
         # spread of single steps: one event pair per step (each pair puts extra packets into the chain, so these
         # run a few us above the grouped figure; they are reported for the p10/p90 spread only)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(BY_K_STEPS)]
-        for j in range(BY_K_STEPS):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(by_k_steps)]
+        for j in range(by_k_steps):
             evs[j][0].record()
             sample_step(ki, k, j)
             evs[j][1].record()
         torch.cuda.synchronize()
-        single = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
-        nu_k = s_nu[ki].cpu().numpy().astype(np.int64)
+        single = np.array([a.elapsed_time(b) * 1e3 / LS for a, b in evs])
+        nu_k = s_nu[ki].cpu().numpy().astype(np.int64).reshape(-1)
         gbs = float(((nu_k + cfg.n_shared) * expert_bytes).mean()) / (lat_ms * 1e-3) / 1e9
         by_k[str(k)] = {"latency_us": round(lat_ms * 1e3, 1), "mean_unique": round(float(nu_k.mean()), 2),
                         "unique_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
@@ -278,7 +299,11 @@ def main():
         "config": {"workload": f"{cfg.name} MoE layer d={cfg.d} E={cfg.n_experts} top{cfg.top_k} ffn={cfg.ffn} "
                                f"shared={cfg.n_shared}, {'FP8 E4M3 + per-row scale' if fp8 else 'bf16'} weights, T=K+1 with K "
                                + (f"= {args.fixed_k}" if args.fixed_k >= 0 else "cycling 0..8")
-                               + f", rho={args.rho}, {L} rotating resident layers, {args.layout} weight layout"},
+                               + f", rho={args.rho}, "
+                               + (f"stack of {S} distinct resident layers with independent seeded inputs, one moe_verify_stack "
+                                  f"call per step (latencies per layer)" if S else f"{L} rotating resident layers")
+                               + f", {args.layout} weight layout"},
+        "layer_steps_per_step": LS, "us_per_layer_step": round(wall / (K_steps * LS) * 1e6, 2),
         "frac_hbm_peak": round(float(value / HBM_PEAK_GBS), 4),
         "by_K": by_k, "roofline": roofline, "stream_read_GBps": round(stream_gbs, 1),
         "gateup_load_twin": twin, "cpu_baseline": cpu,

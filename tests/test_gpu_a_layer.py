@@ -323,6 +323,12 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.status == -1
     with pytest.raises(ValueError):
         ctx.moe_route(x[:2, :32].contiguous(), rw)
+    with pytest.raises(binding.MoeError) as e:       # an empty batch (T = 0) is refused, nothing is launched
+        ctx.moe_verify_layer(ctx.weights({"router_w": rw, "w1": torch.zeros((4, 64, 64), dtype=torch.int16, device="cuda"),
+                                          "w3": torch.zeros((4, 64, 64), dtype=torch.int16, device="cuda"),
+                                          "w2": torch.zeros((4, 64, 64), dtype=torch.int16, device="cuda")}),
+                             x[:0].contiguous(), torch.zeros((0, 64), device="cuda"))
+    assert e.value.status == -1
     # the tuning aid takes 0 / 1 / 2 / 4 tiles, a power-of-two split up to 16, and -1 / 0 / 1 for the fused down kernel
     for bad in ((3, 0, 0, -1), (0, 8, 0, -1), (0, 0, 3, -1), (0, 0, 32, -1), (0, 0, 0, 2), (0, 0, 0, -2)):
         with pytest.raises(binding.MoeError) as e:
