@@ -236,16 +236,16 @@ def main():
         n_list = sorted({min(n, cfg.n_experts) for n in (cfg.top_k, 2 * cfg.top_k, 3 * cfg.top_k, 4 * cfg.top_k)})
         us = {}
         for n in n_list:
-            reps = []
-            for rep in range(5):
+            # as in the per-kernel pass above: one event pair around every launch, launches back to back on rotating
+            # layers, one synchronisation at the end (a launch into an idle GPU would pay its wake-up as well)
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(9)]
+            for rep, (e0, e1) in enumerate(evs):
                 w = lw[(rep + n) % L]
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 binding.moe_weight_load_twin(w.tensors[1], w.tensors[2], n, cfg.ffn // 16, cfg.d // 32, sink)
                 e1.record()
-                torch.cuda.synchronize()
-                reps.append(e0.elapsed_time(e1) * 1e3)
-            us[n] = float(np.median(reps[1:]))
+            torch.cuda.synchronize()
+            us[n] = float(np.median([a.elapsed_time(b) * 1e3 for a, b in evs[1:]]))
         # time = a + b * slots (least squares), read at this run's mean number of live slots
         xs, ys = np.array(list(us.keys()), dtype=np.float64), np.array(list(us.values()))
         b_fit, a_fit = np.polyfit(xs, ys, 1) if len(xs) > 1 else (0.0, ys[0])
