@@ -114,6 +114,32 @@ __device__ void group_body(const GroupArgs& g, const int* s_ids_in, const float*
   for (int i = tid; i < n_unique * kGateCols; i += blockDim.x) g.slot_gate[i] = s_row[i];
 }
 
+// The same tables for a SINGLE token (decoding without speculation, T = 1), where the union is the token's own picks:
+// the slot of pick i is the number of picks with a smaller expert id.  No masks to merge, no scans, one barrier —
+// this runs at the tail of the router's only workgroup, on the critical path of every non-speculative step.
+// s_ids / s_gates: the top_k picks in LDS, written before the call (the call begins with a barrier).
+__device__ __forceinline__ void group_single_token(const GroupArgs& g, const int* s_ids, const float* s_gates) {
+  __syncthreads();
+  const int tid = threadIdx.x, k = g.top_k;
+  if (tid < k) {
+    const int id = s_ids[tid];
+    int slot = 0;
+    for (int j = 0; j < k; ++j) slot += s_ids[j] < id ? 1 : 0;  // the picks of one token are distinct
+    if (g.unique) g.unique[slot] = id;
+    if (g.slot_expert) g.slot_expert[slot] = id;
+    if (g.slot_mask) g.slot_mask[slot] = 1;  // token 0 is routed to every slot of the union
+    if (g.tok_slot) g.tok_slot[tid] = slot;
+    if (g.slot_gate && s_gates) g.slot_gate[slot * kGateCols] = s_gates[tid];
+  }
+  if (g.unique)
+    for (int e = k + tid; e < g.E; e += blockDim.x) g.unique[e] = -1;
+  if (tid == 0) {
+    if (g.n_unique) *g.n_unique = k;
+    if (g.n_unique_ws) *g.n_unique_ws = k;
+    if (g.n_unique_extra) *g.n_unique_extra = k;
+  }
+}
+
 __global__ __launch_bounds__(256) void group_kernel(GroupArgs g) { group_body(g, nullptr, nullptr); }
 
 // ------------------------------------------------------------------------------------------
@@ -311,7 +337,7 @@ __device__ __forceinline__ void route_body(const RouteArgs& g, const GroupArgs& 
     if (g.gates_out) g.gates_out[a] = gate;
     s_gates[tid] = gate;
   }
-  if (gridDim.x == 1) group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+  if (gridDim.x == 1) group_single_token(grp, s_ids, s_gates);  // one workgroup per token: a grid of one is T = 1
 }
 
 __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, GroupArgs grp) { route_body(g, grp); }
@@ -389,7 +415,10 @@ __global__ __launch_bounds__(1024) void topk_group_kernel(RouteArgs g, GroupArgs
     if (g.gates_out) g.gates_out[tid] = gate;
     s_gates[tid] = gate;
   }
-  group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+  if (T == 1)
+    group_single_token(grp, s_ids, s_gates);
+  else
+    group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
 }
 
 }  // namespace
