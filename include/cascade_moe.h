@@ -46,7 +46,7 @@ typedef enum {
   MOE_ERR_UNSUPPORTED_SHAPE = -2, /* geometry outside what the kernels are built for             */
   MOE_ERR_WORKSPACE = -3,         /* device workspace could not be allocated                     */
   MOE_ERR_HIP = -4,               /* a HIP runtime call or kernel launch failed                  */
-  MOE_ERR_UNIMPLEMENTED = -5
+  MOE_ERR_UNIMPLEMENTED = -5      /* kept for ABI stability: no call returns it at present         */
 } moe_status;
 
 /* Static description of a status code; never freed. */
@@ -143,8 +143,8 @@ enum { MOE_LAYOUT_ROW_MAJOR = 0, MOE_LAYOUT_TILED = 1 };
  *                      bits, no infinities, S.1111.111 = NaN, largest finite value 448), and one fp32
  *                      scale per OUTPUT channel (matrix row): weight = scale[row] * value(code).
  *                      Activations, accumulation and the router are as for bf16.  d and ffn must be
- *                      multiples of 64.  moe_verify_layer / moe_verify_stack take FP8 weights in the
- *                      TILED layout only (row-major FP8 returns MOE_ERR_UNIMPLEMENTED: pack first). */
+ *                      multiples of 64.  Both layouts are accepted; the TILED one is the one that
+ *                      streams at speed (row-major FP8 is read in 8-byte row pieces: pack first). */
 enum { MOE_WEIGHT_BF16 = 0, MOE_WEIGHT_FP8_E4M3 = 1 };
 
 /* One layer's weights: DEVICE pointers, caller-owned, alive until the stream drains.
@@ -299,8 +299,7 @@ moe_status moe_weight_load_twin(const void* a, const void* b, int32_t slots, int
  *                    (small unions of small experts); dn_tiles / dn_split_k are then unused
  *   launches         kernel launches of one moe_verify_layer call
  * Errors: MOE_ERR_INVALID_ARG for NULL pointers, T outside 1..max_tokens or unknown layout / dtype;
- * MOE_ERR_UNSUPPORTED_SHAPE as moe_ctx_create, and for FP8 when d or ffn is not a multiple of 64;
- * MOE_ERR_UNIMPLEMENTED for row-major FP8. */
+ * MOE_ERR_UNSUPPORTED_SHAPE as moe_ctx_create, and for FP8 when d or ffn is not a multiple of 64. */
 typedef struct {
   int32_t routed_slots, wide_router, packed_fragments, gu_tiles, dn_tiles, dn_split_k, dn_fused_chunks, launches;
   double expected_slots;

@@ -83,7 +83,8 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       nst,
       [&](Stage<2 * R, NB, PK>& st, int s) {
 #pragma unroll
-        for (int j = 0; j < 2 * R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+        for (int j = 0; j < 2 * R; ++j)
+          st.a[j] = ld_weights<TILED, FP8, NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
           st.bh[b] = ld128<false>(XH, b_off + (uint32_t)(s * NB + b) * 1024);
@@ -231,7 +232,8 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       nst,
       [&](Stage<R, NB, PK>& st, int s) {
 #pragma unroll
-        for (int j = 0; j < R; ++j) st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+        for (int j = 0; j < R; ++j)
+          st.a[j] = ld_weights<TILED, FP8, NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
         // The fragment loads are unconditional although H of a token that was not routed here was never written
         // (the address is inside the workspace, the value is whatever an earlier call left): a load under a
         // per-lane condition makes the compiler count on the smaller number of loads in flight and halves the

@@ -146,7 +146,8 @@ __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
 
 // ------------------------------------------------------------------------------------------
 // Weight addressing.  A step of a 16-row tile is 1 KB: 16 rows x 32 k of bf16, or 16 rows x 64 k of FP8.
-//   row-major [rows, K]:  lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg   (bf16 only)
+//   row-major [rows, K]:  bf16: lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg
+//                         FP8:  the lane's 16 codes are two 8-byte pieces of that row, k = 64 s + 8 kg and 32 further
 //   tiled              :  the same 1 KB stored contiguously, block index tile*(steps per row) + s, lane
 //                         l at byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
 // ------------------------------------------------------------------------------------------
@@ -155,11 +156,14 @@ struct WeightAddr {
   uint32_t lane_off, step_stride;
   size_t tile_stride;
   __device__ __forceinline__ WeightAddr(int K, int r, int kg, int lane) {
-    static_assert(TILED || !FP8, "FP8 weights are consumed in the tiled layout only");
     if constexpr (TILED) {
       lane_off = lane * 16;
       step_stride = 1024;
       tile_stride = (size_t)(K >> (FP8 ? 6 : 5)) * 1024;
+    } else if constexpr (FP8) {
+      lane_off = (uint32_t)r * K + kg * 8;
+      step_stride = 64;
+      tile_stride = (size_t)16 * K;
     } else {
       lane_off = ((uint32_t)r * K + kg * 8) * 2;
       step_stride = 64;
@@ -167,5 +171,18 @@ struct WeightAddr {
     }
   }
 };
+
+// The 16 weight bytes of a lane for one step: one 128-bit load, except row-major FP8 where the codes of the
+// step's two k-halves lie 32 bytes apart in the row.
+template <bool TILED, bool FP8, bool NT>
+__device__ __forceinline__ uint4 ld_weights(const char* base, uint32_t byte_off) {
+  if constexpr (!TILED && FP8) {
+    const uint2 a = *reinterpret_cast<const uint2*>(base + byte_off);
+    const uint2 b = *reinterpret_cast<const uint2*>(base + byte_off + 32);
+    return uint4{a.x, a.y, b.x, b.y};
+  } else {
+    return ld128<NT>(base, byte_off);
+  }
+}
 
 }  // namespace

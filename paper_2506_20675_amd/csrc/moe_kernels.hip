@@ -381,9 +381,13 @@ template <int R, int P>
 void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipStream_t st) {
   const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS), block(64 * kWaves);
   const bool pk = a.T <= kPackedTokens;
-  if (fp8) {  // tiled only (checked by the caller)
+  constexpr int PF = P > 4 ? 4 : P;  // an FP8 stage carries the fragments of two k-steps: depth 4 at most
+  if (fp8 && tiled) {
     if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, true, false>), grid, block, 0, st, a);
+  } else if (fp8) {
+    if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, PF, false, false, true, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((down_kernel<R, kWaves, PF, false, false, true, false>), grid, block, 0, st, a);
   } else if (tiled) {
     if (pk) hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((down_kernel<R, kWaves, P, true, true, false, false>), grid, block, 0, st, a);
@@ -404,7 +408,6 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
                         int* ks_used = nullptr, const ChainArgs* pre = nullptr, bool defer_combine = false) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
-  if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;  // FP8 is streamed in the tiled layout only
   const Plan p = plan_for(c, T, tiled, fp8);
   mark(c, st);
   launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st, pre);
@@ -414,7 +417,13 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
                 c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_mask, c->slot_gate,
                 c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
   const bool pk = T <= kPackedTokens;  // must match what route_kernel wrote
-  if (fp8) {
+  if (fp8 && !tiled) {
+    // row-major FP8 (the layout checkpoints come in; the tiled one is the fast path): two tile pairs per wave,
+    // four waves splitting d, whatever the plan says
+    const dim3 grid((s.ffn / 16 + 1) / 2, routed_slots + s.n_shared), block(64 * kWaves);
+    if (pk) hipLaunchKernelGGL((gateup_kernel<2, kWaves, 3, false, false, true, true>), grid, block, 0, st, ga);
+    else hipLaunchKernelGGL((gateup_kernel<2, kWaves, 3, false, false, true, false>), grid, block, 0, st, ga);
+  } else if (fp8) {
     // FP8 needs twice the fragment bytes per weight byte, and those come from L2: two tile pairs per wave
     // share each fragment load, and a shallow pipeline keeps four waves per SIMD (measured best of
     // {1, 2, 4} tile pairs x depths 2..10)
@@ -593,7 +602,6 @@ moe_status moe_plan_query(const moe_shape* shape, int32_t T, int32_t layout, int
   if (layout != MOE_LAYOUT_ROW_MAJOR && layout != MOE_LAYOUT_TILED) return MOE_ERR_INVALID_ARG;
   if (dtype != MOE_WEIGHT_BF16 && dtype != MOE_WEIGHT_FP8_E4M3) return MOE_ERR_INVALID_ARG;
   const bool tiled = layout == MOE_LAYOUT_TILED, fp8 = dtype == MOE_WEIGHT_FP8_E4M3;
-  if (fp8 && !tiled) return MOE_ERR_UNIMPLEMENTED;
   if (fp8 && (s.d % 64 || s.ffn % 64)) return MOE_ERR_UNSUPPORTED_SHAPE;
   const int automatic[3] = {0, 0, 0};
   const Plan p = plan_for(s, automatic, -1, T, tiled, fp8);
@@ -687,10 +695,8 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
                             float* out, int32_t* n_unique_per_layer_opt, void* stream) {
   if (!c || !layers || L < 1 || !hidden || !out || T < 1 || T > c->s.max_tokens) return MOE_ERR_INVALID_ARG;
   if (!aligned16(hidden) || !aligned16(out)) return MOE_ERR_INVALID_ARG;
-  for (int l = 0; l < L; ++l) {
+  for (int l = 0; l < L; ++l)
     if (!weights_ok(c, layers + l)) return MOE_ERR_INVALID_ARG;
-    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
-  }
   if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   const moe_shape& s = c->s;
@@ -728,10 +734,8 @@ moe_status moe_chained_stack(moe_ctx* c, const moe_layer_weights* layers, const 
   if (!(eps >= 0.f) || !aligned16(x_in) || !aligned16(x_out) || (trace_opt && !aligned16(trace_opt)))
     return MOE_ERR_INVALID_ARG;
   if (c->s.d > 4 * kChainVecs * kChainThreads) return MOE_ERR_UNSUPPORTED_SHAPE;
-  for (int l = 0; l < L; ++l) {
+  for (int l = 0; l < L; ++l)
     if (!weights_ok(c, layers + l) || !gammas[l] || !aligned16(gammas[l])) return MOE_ERR_INVALID_ARG;
-    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
-  }
   if (moe_status st = check_stream_device(c, stream)) return st;
   hipStream_t st = (hipStream_t)stream;
   const moe_shape& s = c->s;
@@ -793,7 +797,6 @@ moe_status moe_decoder_stack(moe_ctx* c, const moe_layer_weights* layers, const 
   if (s.d > 4 * kChainVecs * kChainThreads) return MOE_ERR_UNSUPPORTED_SHAPE;
   for (int l = 0; l < L; ++l) {
     if (!weights_ok(c, layers + l)) return MOE_ERR_INVALID_ARG;
-    if (layers[l].dtype == MOE_WEIGHT_FP8_E4M3 && layers[l].layout != MOE_LAYOUT_TILED) return MOE_ERR_UNIMPLEMENTED;
     const moe_attn_weights& a = attn[l];
     if (!a.wqkv || !a.wo || !a.gamma_attn || !a.gamma_moe) return MOE_ERR_INVALID_ARG;
     if (!aligned16(a.wqkv) || !aligned16(a.wo) || !aligned16(a.gamma_attn) || !aligned16(a.gamma_moe))

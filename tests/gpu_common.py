@@ -99,7 +99,7 @@ def _check_layer(cfg_like, W, x, ctx=None, Wd=None, gate_mode=0):
 
 
 
-def _run_layer_fp8(ctx, Wd, x):
+def _run_layer_fp8(ctx, Wd, x, tiled=True):
     import torch
     s = ctx.shape
     T = x.shape[0]
@@ -108,14 +108,23 @@ def _run_layer_fp8(ctx, Wd, x):
     gates = torch.zeros((T, s.top_k), dtype=torch.float32, device="cuda")
     uniq = torch.full((s.n_experts,), -7, dtype=torch.int32, device="cuda")
     nu = torch.full((1,), -7, dtype=torch.int32, device="cuda")
-    ctx.moe_verify_layer(_tiled(ctx, Wd), _dev(x), out, ids, gates, uniq, nu)
+    ctx.moe_verify_layer(_tiled(ctx, Wd) if tiled else ctx.weights(Wd), _dev(x), out, ids, gates, uniq, nu)
     torch.cuda.synchronize()
     return out.cpu().numpy(), ids.cpu().numpy(), gates.cpu().numpy(), uniq.cpu().numpy(), int(nu.item())
 
 
-def _check_layer_fp8(ctx, W, Wd, x, k, ns):
+def _check_layer_fp8(ctx, W, Wd, x, k, ns, row_major=True):
+    """The tiled layout (the one that is streamed at speed) and, unless switched off, the plain row-major one the
+    oracle reads: other kernels with other summation splits, each held to the oracle in its own right."""
+    rel = _check_layer_fp8_one(ctx, W, Wd, x, k, ns, True)
+    if row_major:
+        rel = max(rel, _check_layer_fp8_one(ctx, W, Wd, x, k, ns, False))
+    return rel
+
+
+def _check_layer_fp8_one(ctx, W, Wd, x, k, ns, tiled):
     gm = ctx.shape.gate_mode
-    out, ids, gates, uniq, nu = _run_layer_fp8(ctx, Wd, x)
+    out, ids, gates, uniq, nu = _run_layer_fp8(ctx, Wd, x, tiled)
     ref32, rids, rgates = orc.layer_fp8(x, W, k, ns, "f32", gm)
     ref64, rids64, _ = orc.layer_fp8(x, W, k, ns, "f64", gm)
     E = W["q1"].shape[0]

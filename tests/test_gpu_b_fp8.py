@@ -101,13 +101,13 @@ def test_fp8_argument_errors():
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 4)
     x = torch.zeros((2, cfg.d), dtype=torch.float32, device="cuda")
     out = torch.zeros((2, cfg.d), dtype=torch.float32, device="cuda")
-    with pytest.raises(binding.MoeError) as e:
-        ctx.moe_verify_layer(ctx.weights(Wd), x, out)          # row-major FP8 is not streamed: pack first
-    assert e.value.status == -5                                  # MOE_ERR_UNIMPLEMENTED
     lw = ctx.weights(Wd)
     lw.c.w3_scale = None                                         # a missing scale vector is an argument error
     with pytest.raises(binding.MoeError) as e:
         ctx.moe_pack_weights(lw)
+    assert e.value.status == -1
+    with pytest.raises(binding.MoeError) as e:
+        ctx.moe_verify_layer(lw, x, out)
     assert e.value.status == -1
     ctx.close()
     ctx = binding.MoeContext(96, 160, 4, 2, 0, 4)              # d, ffn not multiples of 64
