@@ -58,9 +58,6 @@ def main():
     if args.warmup is None:
         args.warmup = 9 if args.stack else 18
     fp8 = args.weights == "fp8"
-    if fp8 and args.layout != "tiled":
-        print("bench.py: FP8 weights are streamed in the tiled layout only", file=sys.stderr)
-        sys.exit(2)
 
     import torch
     from paper_2506_20675_amd import binding, synth

@@ -73,7 +73,9 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   }
   const char* XH = reinterpret_cast<const char*>(g.xf_hi) + (size_t)s_beg * (1024 * NB);
   const char* XL = reinterpret_cast<const char*>(g.xf_lo) + (size_t)s_beg * (1024 * NB);
-  const uint32_t b_off = lane * 16;
+  uint32_t b_off[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) b_off[b] = frag_lane_off<TILED, FP8>(r, kg, lane, b);
 
   f32x4 acc[2 * R];
 #pragma unroll
@@ -84,11 +86,11 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       [&](Stage<2 * R, NB, PK>& st, int s) {
 #pragma unroll
         for (int j = 0; j < 2 * R; ++j)
-          st.a[j] = ld_weights<TILED, FP8, NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+          st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-          st.bh[b] = ld128<false>(XH, b_off + (uint32_t)(s * NB + b) * 1024);
-          if constexpr (!PK) st.bl[b] = ld128<false>(XL, b_off + (uint32_t)(s * NB + b) * 1024);
+          st.bh[b] = ld128<false>(XH, b_off[b] + (uint32_t)s * (NB * 1024));
+          if constexpr (!PK) st.bl[b] = ld128<false>(XL, b_off[b] + (uint32_t)s * (NB * 1024));
         }
       },
       [&](const Stage<2 * R, NB, PK>& st) {
@@ -222,7 +224,9 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       reinterpret_cast<const char*>(g.hf_hi) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
   const char* HL =
       reinterpret_cast<const char*>(g.hf_lo) + ((size_t)slot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
-  const uint32_t b_off = lane * 16;
+  uint32_t b_off[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) b_off[b] = frag_lane_off<TILED, FP8>(r, kg, lane, b);
 
   f32x4 acc[R];
 #pragma unroll
@@ -233,15 +237,15 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
       [&](Stage<R, NB, PK>& st, int s) {
 #pragma unroll
         for (int j = 0; j < R; ++j)
-          st.a[j] = ld_weights<TILED, FP8, NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
+          st.a[j] = ld128<NT>(base[j], wa.lane_off + (uint32_t)s * wa.step_stride);
         // The fragment loads are unconditional although H of a token that was not routed here was never written
         // (the address is inside the workspace, the value is whatever an earlier call left): a load under a
         // per-lane condition makes the compiler count on the smaller number of loads in flight and halves the
         // effective prefetch depth.  The unrouted columns are masked to zero where they are consumed.
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-          st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
-          if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+          st.bh[b] = ld128<false>(HH, b_off[b] + (uint32_t)s * (NB * 1024));
+          if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off[b] + (uint32_t)s * (NB * 1024));
         }
       },
       [&](const Stage<R, NB, PK>& st) {

@@ -146,10 +146,14 @@ __device__ __forceinline__ void pipeline(int nst, Load load, Compute compute) {
 
 // ------------------------------------------------------------------------------------------
 // Weight addressing.  A step of a 16-row tile is 1 KB: 16 rows x 32 k of bf16, or 16 rows x 64 k of FP8.
-//   row-major [rows, K]:  bf16: lane (r, kg) reads 16 B at row tile*16 + r, k = 32 s + 8 kg
-//                         FP8:  the lane's 16 codes are two 8-byte pieces of that row, k = 64 s + 8 kg and 32 further
+//   row-major [rows, K]:  lane (r, kg) reads 16 contiguous bytes of row tile*16 + r:
+//                         bf16: k = 32 s + 8 kg .. + 7;   FP8: k = 64 s + 16 kg .. + 15
 //   tiled              :  the same 1 KB stored contiguously, block index tile*(steps per row) + s, lane
 //                         l at byte 16 l — what moe_pack_weights produces; one wave load = 1 KB contiguous
+// An FP8 lane feeds its first 8 codes to one MFMA and its last 8 to the next.  In the tiled layout those are
+// k-group kg of k-step 2s and of k-step 2s + 1; in the row-major one they are the adjacent k-groups 2 kg and
+// 2 kg + 1 of the 64-k block.  A matrix product does not care in which order k is walked as long as both
+// operands agree, so the row-major kernels fetch the matching activation units instead (frag_lane_off).
 // ------------------------------------------------------------------------------------------
 template <bool TILED, bool FP8>
 struct WeightAddr {
@@ -161,7 +165,7 @@ struct WeightAddr {
       step_stride = 1024;
       tile_stride = (size_t)(K >> (FP8 ? 6 : 5)) * 1024;
     } else if constexpr (FP8) {
-      lane_off = (uint32_t)r * K + kg * 8;
+      lane_off = (uint32_t)r * K + kg * 16;
       step_stride = 64;
       tile_stride = (size_t)16 * K;
     } else {
@@ -172,16 +176,15 @@ struct WeightAddr {
   }
 };
 
-// The 16 weight bytes of a lane for one step: one 128-bit load, except row-major FP8 where the codes of the
-// step's two k-halves lie 32 bytes apart in the row.
-template <bool TILED, bool FP8, bool NT>
-__device__ __forceinline__ uint4 ld_weights(const char* base, uint32_t byte_off) {
+// Byte offset, inside the fragments of one pipeline step (NB k-steps of 1 KB), of the activation unit that lane
+// (n, kg) multiplies with the b-th half of its weight load.
+template <bool TILED, bool FP8>
+__device__ __forceinline__ uint32_t frag_lane_off(int n, int kg, int lane, int b) {
   if constexpr (!TILED && FP8) {
-    const uint2 a = *reinterpret_cast<const uint2*>(base + byte_off);
-    const uint2 b = *reinterpret_cast<const uint2*>(base + byte_off + 32);
-    return uint4{a.x, a.y, b.x, b.y};
+    const int g = 2 * kg + b;  // k-group (8 k) inside the 64-k block
+    return (uint32_t)((g >> 2) * 64 + (g & 3) * 16 + n) * 16;
   } else {
-    return ld128<NT>(base, byte_off);
+    return (uint32_t)lane * 16 + (uint32_t)b * 1024;
   }
 }
 
