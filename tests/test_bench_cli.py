@@ -20,9 +20,10 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.stdout.strip() == ""
 
 
-def test_fp8_needs_the_tiled_layout():
-    r = _bench("--weights", "fp8", "--layout", "row")
-    assert r.returncode != 0 and "tiled" in r.stderr and r.stdout.strip() == ""
+def test_unknown_layout_or_weight_type_is_refused_by_the_parser():
+    for bad in (("--layout", "blocked"), ("--weights", "int4")):
+        r = _bench(*bad)
+        assert r.returncode == 2 and "invalid choice" in r.stderr and r.stdout.strip() == ""
 
 
 def test_traffic_figure_comes_from_the_committed_counter_summaries():
