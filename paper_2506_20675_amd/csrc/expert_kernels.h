@@ -6,8 +6,47 @@
 namespace {
 
 // ------------------------------------------------------------------------------------------
+// Step 5: out[t] = sum over the token's own picks i = 0 .. top_k-1 (the slot each landed in comes from
+// the grouping step), then the shared experts; k-chunks ascending inside each.  A fixed order — the
+// order of the defining sum — so reruns are bit-identical and no floating-point atomics are needed.
+// ------------------------------------------------------------------------------------------
+struct CombineArgs {
+  const float* partial;      // [(u_max + n_shared) * KS, max_tokens, d] slabs of the down projection
+  const int32_t* tok_slot;   // [T, top_k]
+  float* out;                // [T, d]
+  int d, T, top_k, u_max, n_shared, max_tokens, KS;
+};
+
+// float4 number i of out[T, d]
+__device__ __forceinline__ void combine_one(const CombineArgs& g, int i) {
+  const int per_tok = g.d >> 2;
+  const int t = i / per_tok, c4 = i - t * per_tok;
+  float4 s = float4{0.f, 0.f, 0.f, 0.f};
+  const size_t slab = (size_t)g.max_tokens * g.d;
+  const float* p0 = g.partial + (size_t)t * g.d + (size_t)c4 * 4;
+  // flat walk over (pick, k-chunk): unrolled by 8 so that eight slab loads are in flight at a time
+  const int n = (g.top_k + g.n_shared) * g.KS;
+#pragma unroll 8
+  for (int q = 0; q < n; ++q) {
+    const int j = q / g.KS, k = q - j * g.KS;
+    const int u = j < g.top_k ? g.tok_slot[t * g.top_k + j] : g.u_max + (j - g.top_k);
+    const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * g.KS + k) * slab);
+    s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+  }
+  *reinterpret_cast<float4*>(g.out + (size_t)t * g.d + (size_t)c4 * 4) = s;
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs g) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < g.T * (g.d >> 2)) combine_one(g, i);
+}
+
+// ------------------------------------------------------------------------------------------
 // Step 3: gate/up projections + SiLU*mul for every unique expert (and shared expert).
 // grid = (row blocks of 16*R rows of ffn, min(E, T*top_k) + n_shared slots); block = W waves that split d.
+// With cmb_rows = 1 the grid has one more row in front, y = 0, whose workgroups do not project anything: they sum
+// the slabs another layer's down projection left (`cmb`) — independent work that then needs no launch of its
+// own.  That row is dispatched first and is done within a couple of microseconds.
 // ------------------------------------------------------------------------------------------
 struct GateupArgs {
   const void *w1, *w3, *sw1, *sw3;      // [E,ffn,d] / [n_shared,ffn,d], bf16 or FP8 codes
@@ -19,6 +58,8 @@ struct GateupArgs {
   const float* slot_gate;               // [u_max+n_shared, 16] gate of token column n
   uint16_t *hf_hi, *hf_lo;              // [u_max + n_shared] fragments of gate*silu(G)*U, ffn*16 elements each
   int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
+  int cmb_rows;                         // 0, or 1: row y = 0 of the grid runs the slab sum `cmb`
+  CombineArgs cmb;
 };
 
 template <int R, int W, int P, bool TILED, bool NT, bool FP8, bool PK>
@@ -32,7 +73,12 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
   float gate;
   bool routed;  // token column r's token goes through this expert (its gate may still be 0 after underflow)
   const int col = PK ? (r & (kPackedTokens - 1)) : r;
-  int slot = blockIdx.y;  // slot of the union, or routed_slots + s for shared expert s
+  int slot = (int)blockIdx.y - g.cmb_rows;  // slot of the union, or routed_slots + s for shared expert s
+  if (slot < 0) {  // the slab-sum row: uniform over the workgroup
+    const int n4 = g.cmb.T * (g.cmb.d >> 2);
+    for (int i = blockIdx.x * (64 * W) + tid; i < n4; i += gridDim.x * (64 * W)) combine_one(g.cmb, i);
+    return;
+  }
   if (slot < g.routed_slots) {
     // independent loads (one round trip); the tables are in bounds for every slot of the grid
     const int nu = *g.n_unique;
@@ -314,6 +360,12 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 // combine — happens in registers, the 16 waves meet in LDS in a fixed order, and out[t] is written directly:
 // no slabs, no combine launch.  (On large experts the split-K kernel above streams better: it shares each H
 // fragment among 4 row tiles.)   grid = d / 16.
+// halves = 2 (when d / 16 alone would leave compute units without a workgroup): two workgroups per tile, each
+// owning 8 of its 16 rows.  A lane whose row belongs to the other workgroup loads the address of its partner lane
+// (row r ^ 8) instead — the same 16 bytes, so the pair costs one request and the workgroup fetches only its own 128-byte
+// pieces of each 1 KB block — and the matrix core then computes that row twice; output row i depends on weight row
+// i alone, so the rows a workgroup owns are exactly what the other variant computes, and only those are stored.
+// grid = d / 16 * halves.
 // ------------------------------------------------------------------------------------------
 struct DownFusedArgs {
   const void *w2, *sw2;
@@ -324,6 +376,7 @@ struct DownFusedArgs {
   const int32_t* slot_mask;
   float* out;  // [T, d]
   int d, ffn, T, n_shared, u_max, C;  // C = k-chunks per slot
+  int halves;                         // 1 or 2 workgroups per 16-row tile
 };
 
 constexpr int kFusedWaves = 16;
@@ -333,11 +386,14 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[kFusedWaves * 64];
   const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
-  const int tile = blockIdx.x, col = PK ? (r & (kPackedTokens - 1)) : r;
+  const int col = PK ? (r & (kPackedTokens - 1)) : r;
+  const int tile = g.halves == 2 ? blockIdx.x >> 1 : blockIdx.x, half = blockIdx.x & 1;
+  const int r_load = g.halves == 2 ? (r & 7) | (half << 3) : r;  // the row whose weights this lane loads
+  const bool own = g.halves != 2 || (kg >> 1) == half;           // the lane's output rows 4 kg .. 4 kg + 3 are this workgroup's
   const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);
   const int nu = *g.n_unique, n_items = (nu + g.n_shared) * g.C;
   const int nsteps = g.ffn >> (FP8 ? 6 : 5), chunk = (nsteps + g.C - 1) / g.C;
-  const WeightAddr<true, FP8> wa(g.ffn, r, kg, lane);
+  const WeightAddr<true, FP8> wa(g.ffn, r_load, kg, kg * 16 + r_load);
   const uint32_t b_off = lane * 16;
   f32x4 total = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int item = wave; item < n_items; item += kFusedWaves) {
@@ -413,36 +469,8 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
   }
   if constexpr (PK)
     y.x += __shfl_xor(y.x, 8), y.y += __shfl_xor(y.y, 8), y.z += __shfl_xor(y.z, 8), y.w += __shfl_xor(y.w, 8);
-  if (r < g.T && (!PK || r < kPackedTokens))
+  if (own && r < g.T && (!PK || r < kPackedTokens))
     *reinterpret_cast<float4*>(g.out + (size_t)r * g.d + (size_t)tile * 16 + kg * 4) = y;
-}
-
-// ------------------------------------------------------------------------------------------
-// Step 5: out[t] = sum over the token's own picks i = 0 .. top_k-1 (the slot each landed in comes from
-// the grouping step), then the shared experts; k-chunks ascending inside each.  A fixed order — the
-// order of the defining sum — so reruns are bit-identical and no floating-point atomics are needed.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
-                                                      const int32_t* __restrict__ tok_slot, float* __restrict__ out,
-                                                      int d, int T, int top_k, int u_max, int n_shared,
-                                                      int max_tokens, int KS) {
-  const int i = blockIdx.x * 256 + threadIdx.x;  // float4 index inside [T, d]
-  const int per_tok = d >> 2;
-  if (i >= T * per_tok) return;
-  const int t = i / per_tok, c4 = i - t * per_tok;
-  float4 s = float4{0.f, 0.f, 0.f, 0.f};
-  const size_t slab = (size_t)max_tokens * d;
-  const float* p0 = partial + (size_t)t * d + (size_t)c4 * 4;
-  // flat walk over (pick, k-chunk): unrolled by 8 so that eight slab loads are in flight at a time
-  const int n = (top_k + n_shared) * KS;
-#pragma unroll 8
-  for (int q = 0; q < n; ++q) {
-    const int j = q / KS, k = q - j * KS;
-    const int u = j < top_k ? tok_slot[t * top_k + j] : u_max + (j - top_k);
-    const float4 v = *reinterpret_cast<const float4*>(p0 + ((size_t)u * KS + k) * slab);
-    s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
-  }
-  *reinterpret_cast<float4*>(out + (size_t)t * d + (size_t)c4 * 4) = s;
 }
 
 // One-off re-layout of a row-major [rows, K] bf16 matrix into the tiled order (see WeightAddr).

@@ -139,6 +139,8 @@ struct moe_ctx {
   int ks_alloc;           // split-K slabs the partial buffer is sized for
   int plan_override[3];   // moe_ctx_tune: gate/up tiles, down tiles, split-K factor; zero = automatic
   int fused_mode;         // moe_ctx_tune: -1 automatic, 0 never fuse down + combine, 1 always (tiled weights)
+  int n_sets;             // copies of the routing workspace (moe_verify_stack routes that many layers ahead)
+  size_t set_stride;      // bytes from one copy to the next; the pointers below name copy 0
   char* ws;
   size_t ws_bytes;
   uint16_t *xf_hi, *xf_lo, *hf_hi, *hf_lo;  // activation fragments (see frag_unit)
@@ -158,6 +160,7 @@ constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 constexpr size_t kFusedDownBytes = (size_t)36 << 20;  // most down-projection bytes per step for the fused down + combine launch
+constexpr int kFusedHalvesBelow = 256;  // fused down + combine: fewer row tiles than this -> two workgroups per tile
 constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
 // Launch plan of the two expert kernels for one (T, weight layout).
@@ -214,7 +217,7 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
   if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes))) {
     int C = 1;
-    while (slots * C < 2 * kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
+    while (slots * C < kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
     p.dn_fused_C = C;
   }
   if (plan_override[0] > 0) p.gu_R = plan_override[0];
@@ -228,9 +231,10 @@ Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
 
 // Geometry-dependent host fields of a context (automatic plan; slab buffer sized for the largest split-K factor
 // any T can ask for).
-void ctx_set_shape(moe_ctx* c, const moe_shape& s, int dev) {
+void ctx_set_shape(moe_ctx* c, const moe_shape& s, int dev, int n_sets) {
   c->s = s;
   c->device = dev;
+  c->n_sets = n_sets;
   c->profiling = false;
   c->u_max = s.max_tokens * s.top_k < s.n_experts ? s.max_tokens * s.top_k : s.n_experts;
   c->plan_override[0] = c->plan_override[1] = c->plan_override[2] = 0;
@@ -247,7 +251,8 @@ void ctx_set_shape(moe_ctx* c, const moe_shape& s, int dev) {
 // Carves the workspace of a context out of `base` (256-byte aligned pieces) and returns its size; base == NULL
 // only measures.  The pieces whose CONTENT a layer-step relies on before writing them come first — the
 // activation fragments of the router input (their padded token columns are read by the matrix cores) and the
-// per-slot tables (the shared experts' gate rows are constant 1) — and *init_bytes gets their total size.
+// per-slot tables (the shared experts' gate rows are constant 1) — and *init_bytes gets their total size.  That
+// leading part, the routing workspace, is laid out c->n_sets times back to back (the pointers name copy 0).
 size_t ctx_layout(moe_ctx* c, char* base, size_t* init_bytes = nullptr) {
   const moe_shape& s = c->s;
   const size_t A = (size_t)s.max_tokens * s.top_k;
@@ -263,6 +268,8 @@ size_t ctx_layout(moe_ctx* c, char* base, size_t* init_bytes = nullptr) {
   const size_t o_se = carve((size_t)c->u_max * 4), o_sg = carve(n_slots * kGateCols * 4), o_ts = carve(A * 4);
   const size_t o_sm = carve((size_t)c->u_max * 4);
   if (init_bytes) *init_bytes = off;
+  c->set_stride = off;
+  off *= (size_t)c->n_sets;
   const size_t o_hh = carve(n_slots * s.ffn * kGateCols * 2);
   const size_t o_hl = carve(n_slots * s.ffn * kGateCols * 2);
   const size_t o_part = carve(n_slots * c->ks_alloc * s.max_tokens * s.d * 4);
@@ -271,7 +278,7 @@ size_t ctx_layout(moe_ctx* c, char* base, size_t* init_bytes = nullptr) {
   const size_t nq = (size_t)s.n_heads * s.head_dim, nqkv = nq + 2 * (size_t)s.n_kv_heads * s.head_dim;
   const size_t o_hb = carve((size_t)s.max_tokens * s.d * 4), o_qkv = carve((size_t)s.max_tokens * nqkv * 4 + 16);
   const size_t o_ah = carve(nq * kGateCols * 2 + 16), o_al = carve(nq * kGateCols * 2 + 16);
-  const size_t o_lg = carve((size_t)s.max_tokens * s.n_experts * 8);
+  const size_t o_lg = carve((size_t)c->n_sets * s.max_tokens * s.n_experts * 8);
   if (!base) return off;
   c->ws = base;
   c->xf_hi = reinterpret_cast<uint16_t*>(base + o_xh);
@@ -339,6 +346,53 @@ void mark(moe_ctx* c, hipStream_t st) {
   c->events.push_back(e);
 }
 
+// One copy of the routing workspace: what steps 1 and 2 leave for the expert kernels and the slab sum.
+struct RouteSet {
+  uint16_t *xf_hi, *xf_lo;
+  int32_t *n_unique, *slot_expert, *tok_slot, *slot_mask;
+  float* slot_gate;
+};
+RouteSet route_set(const moe_ctx* c, int b) {
+  const size_t off = (size_t)b * c->set_stride;
+  auto at = [off](auto* p) { return reinterpret_cast<decltype(p)>(reinterpret_cast<char*>(p) + off); };
+  return RouteSet{at(c->xf_hi), at(c->xf_lo), at(c->n_unique), at(c->slot_expert), at(c->tok_slot), at(c->slot_mask),
+                  at(c->slot_gate)};
+}
+
+RouteArgs route_args(const moe_ctx* c, const float* hidden, const uint16_t* router_w, int T, int32_t* ids,
+                     float* gates) {
+  const moe_shape& s = c->s;
+  return RouteArgs{hidden, router_w, s.d, s.n_experts, s.top_k, T, s.gate_mode, c->ids, ids, c->gates, gates,
+                   c->xf_hi, c->xf_lo};
+}
+GroupArgs group_args(const moe_ctx* c, int T, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra) {
+  const moe_shape& s = c->s;
+  return GroupArgs{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
+                   c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_mask, c->slot_gate};
+}
+
+// Steps 1 and 2 for B <= kRouteAhead layers at once (moe_verify_stack: every layer's input is known up front): layer
+// l0 + b is routed into copy b of the routing workspace.  Two launches, whatever B is.
+void launch_route_ahead(moe_ctx* c, const moe_layer_weights* layers, int B, const float* hidden, int T,
+                        int32_t* n_unique_extra, hipStream_t st) {
+  const moe_shape& s = c->s;
+  const RouteArgs ra = route_args(c, hidden, nullptr, T, nullptr, nullptr);
+  const GroupArgs ga = group_args(c, T, nullptr, nullptr, n_unique_extra);
+  AheadArgs aa{};
+  for (int b = 0; b < B; ++b) aa.router_w[b] = layers[b].router_w;
+  aa.hidden_stride = (size_t)T * s.d;
+  aa.set_stride = c->set_stride;
+  aa.logits_stride = (size_t)s.max_tokens * s.n_experts;
+  if (s.n_experts >= kWideRouterExperts) {
+    const dim3 grid(T, (s.n_experts + kLogitExperts - 1) / kLogitExperts, B);
+    hipLaunchKernelGGL(logits_ahead_kernel, grid, dim3(64 * kLogitWaves), 0, st, ra, ga, aa, c->logits);
+    hipLaunchKernelGGL(topk_group_ahead_kernel, dim3(B), dim3(1024), 0, st, ra, ga, aa, (const double*)c->logits);
+    return;
+  }
+  hipLaunchKernelGGL(route_ahead_kernel, dim3(T, B), dim3(64 * kRouteWaves), 0, st, ra, ga, aa);
+  if (T > 1) hipLaunchKernelGGL(group_ahead_kernel, dim3(B), dim3(256), 0, st, ra, ga, aa);
+}
+
 // Steps 1 and 2.  ids / gates / unique / n_unique / n_unique_extra: optional DEVICE outputs.
 // pre != NULL (chained stacks): the slab sum + residual + RMSNorm pass that produces `hidden` runs first — inside
 // the router's launch when the router is the one-workgroup-per-token kernel.
@@ -346,10 +400,8 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
                             float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
                             const ChainArgs* pre = nullptr) {
   const moe_shape& s = c->s;
-  RouteArgs ra{hidden, router_w, s.d, s.n_experts, s.top_k, T, s.gate_mode, c->ids, ids, c->gates, gates,
-               c->xf_hi, c->xf_lo};
-  GroupArgs ga{c->ids, c->gates, T, s.top_k, s.n_experts, unique, n_unique, nullptr, nullptr, nullptr,
-               c->n_unique, n_unique_extra, c->slot_expert, c->tok_slot, c->slot_mask, c->slot_gate};
+  const RouteArgs ra = route_args(c, hidden, router_w, T, ids, gates);
+  const GroupArgs ga = group_args(c, T, unique, n_unique, n_unique_extra);
   if (pre && s.n_experts >= kWideRouterExperts)
     hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre);
   if (s.n_experts >= kWideRouterExperts) {
@@ -369,7 +421,7 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
 
 template <int R, int P>
 void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // row-major bf16 weights
-  const dim3 grid((c->s.ffn / 16 + R - 1) / R, a.routed_slots + c->s.n_shared);
+  const dim3 grid((c->s.ffn / 16 + R - 1) / R, a.routed_slots + c->s.n_shared + a.cmb_rows);
   if (a.T <= kPackedTokens)
     hipLaunchKernelGGL((gateup_kernel<R, kWaves, P, false, false, false, true>), grid, dim3(64 * kWaves), 0, st, a);
   else
@@ -397,43 +449,50 @@ void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipS
   }
 }
 
-// One layer-step after validation: router, gate/up, down, slab sum.  The expert-union step has no
-// launch of its own: it is the liveness test at the top of the expert kernels.
-// unique / n_unique / n_unique_extra: optional DEVICE outputs.
+void launch_combine(const CombineArgs& a, hipStream_t st) {
+  const int n4 = a.T * (a.d / 4);
+  hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, a);
+}
+CombineArgs combine_args(const moe_ctx* c, const RouteSet& rs, int T, float* out, int ks) {
+  const moe_shape& s = c->s;
+  return CombineArgs{c->partial, rs.tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, ks};
+}
+
+// Steps 3 to 5 of one layer-step, on the routing tables and activation fragments in `rs`.  The expert-union step has
+// no launch of its own: it is the liveness test at the top of the expert kernels.
 // out == NULL: the slabs are left for the caller (chained stack: chain_kernel sums them); *ks_used gets the
 // split-K factor they were written with.  defer_combine (with out != NULL): the same, unless the down projection
 // is the fused one, which writes `out` itself (*ks_used = 0: nothing is pending).
-moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
-                        float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
-                        int* ks_used = nullptr, const ChainArgs* pre = nullptr, bool defer_combine = false) {
+// cmb != NULL: the gate/up launch also sums the slabs another layer-step left (see GateupArgs).
+moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weights* w, int T, float* out,
+                          hipStream_t st, int* ks_used, bool defer_combine, const CombineArgs* cmb) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
   const Plan p = plan_for(c, T, tiled, fp8);
-  mark(c, st);
-  launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st, pre);
-  mark(c, st);
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
+  const int cr = cmb ? 1 : 0;
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
-                c->xf_hi, c->xf_lo, c->n_unique, c->slot_expert, c->slot_mask, c->slot_gate,
-                c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max};
-  const bool pk = T <= kPackedTokens;  // must match what route_kernel wrote
+                rs.xf_hi, rs.xf_lo, rs.n_unique, rs.slot_expert, rs.slot_mask, rs.slot_gate,
+                c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max, cr, cmb ? *cmb : CombineArgs{}};
+  const unsigned rows = routed_slots + s.n_shared + cr;
+  const bool pk = T <= kPackedTokens;  // must match what the router wrote
   if (fp8 && !tiled) {
     // row-major FP8 (the layout checkpoints come in; the tiled one is the fast path): two tile pairs per wave,
     // four waves splitting d, whatever the plan says
-    const dim3 grid((s.ffn / 16 + 1) / 2, routed_slots + s.n_shared), block(64 * kWaves);
+    const dim3 grid((s.ffn / 16 + 1) / 2, rows), block(64 * kWaves);
     if (pk) hipLaunchKernelGGL((gateup_kernel<2, kWaves, 3, false, false, true, true>), grid, block, 0, st, ga);
     else hipLaunchKernelGGL((gateup_kernel<2, kWaves, 3, false, false, true, false>), grid, block, 0, st, ga);
   } else if (fp8) {
     // FP8 needs twice the fragment bytes per weight byte, and those come from L2: two tile pairs per wave
     // share each fragment load, and a shallow pipeline keeps four waves per SIMD (measured best of
     // {1, 2, 4} tile pairs x depths 2..10)
-    const dim3 grid((s.ffn / 16 + 1) / 2, routed_slots + s.n_shared);
+    const dim3 grid((s.ffn / 16 + 1) / 2, rows);
     if (pk) hipLaunchKernelGGL((gateup_kernel<2, 1, 3, true, true, true, true>), grid, dim3(64), 0, st, ga);
     else hipLaunchKernelGGL((gateup_kernel<2, 1, 3, true, true, true, false>), grid, dim3(64), 0, st, ga);
   } else if (tiled) {
     // one wave per 16-row tile pair over the whole of d (splitting d over 2 or 4 waves when the union
     // is small on a small expert was measured: no gain, the step is bound by launch latencies there)
-    const dim3 grid(s.ffn / 16, routed_slots + s.n_shared);
+    const dim3 grid(s.ffn / 16, rows);
     if (pk) hipLaunchKernelGGL((gateup_kernel<1, 1, 6, true, true, false, true>), grid, dim3(64), 0, st, ga);
     else hipLaunchKernelGGL((gateup_kernel<1, 1, 6, true, true, false, false>), grid, dim3(64), 0, st, ga);
   } else {
@@ -447,9 +506,10 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   if (p.dn_fused_C > 0) {
     // down projection and combine in one launch; with no `out` (chained stack) the summed term goes to the slab
     // buffer as a plain [T, d] array and *ks_used = 0 tells the caller so
-    DownFusedArgs fa{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
-                     c->slot_mask, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C};
-    const dim3 grid(s.d / 16), block(64 * kFusedWaves);
+    DownFusedArgs fa{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, rs.n_unique, rs.slot_expert,
+                     rs.slot_mask, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C,
+                     s.d / 16 < kFusedHalvesBelow ? 2 : 1};
+    const dim3 grid(s.d / 16 * fa.halves), block(64 * kFusedWaves);
     if (fp8) {
       if (pk) hipLaunchKernelGGL((down_fused_kernel<4, true, true>), grid, block, 0, st, fa);
       else hipLaunchKernelGGL((down_fused_kernel<4, true, false>), grid, block, 0, st, fa);
@@ -462,8 +522,8 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
     mark(c, st);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
   }
-  DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, c->n_unique, c->slot_expert,
-              c->slot_mask, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
+  DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, rs.n_unique, rs.slot_expert,
+              rs.slot_mask, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
   switch (p.dn_R) {
     case 4: launch_down<4, 4>(c, da, tiled, fp8, st); break;
     case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
@@ -471,13 +531,21 @@ moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hid
   }
   mark(c, st);
   if (ks_used) *ks_used = p.dn_KS;
-  if (out && !defer_combine) {
-    const int n4 = T * (s.d / 4);
-    hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
-                       (const int32_t*)c->tok_slot, out, s.d, T, s.top_k, c->u_max, s.n_shared, s.max_tokens, p.dn_KS);
-  }
+  if (out && !defer_combine) launch_combine(combine_args(c, rs, T, out, p.dn_KS), st);
   mark(c, st);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// One layer-step after validation: router, gate/up, down, slab sum.
+// unique / n_unique / n_unique_extra: optional DEVICE outputs; ks_used / pre: see launch_experts and
+// launch_route_and_group.
+moe_status launch_layer(moe_ctx* c, const moe_layer_weights* w, const float* hidden, int T, float* out, int32_t* ids,
+                        float* gates, int32_t* unique, int32_t* n_unique, int32_t* n_unique_extra, hipStream_t st,
+                        int* ks_used = nullptr, const ChainArgs* pre = nullptr) {
+  mark(c, st);
+  launch_route_and_group(c, hidden, w->router_w, T, ids, gates, unique, n_unique, n_unique_extra, st, pre);
+  mark(c, st);
+  return launch_experts(c, route_set(c, 0), w, T, out, st, ks_used, false, nullptr);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -544,7 +612,7 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
   moe_ctx* c = new (std::nothrow) moe_ctx();
   if (!c) return MOE_ERR_WORKSPACE;
-  ctx_set_shape(c, s, dev);
+  ctx_set_shape(c, s, dev, kRouteAhead);
   c->ws_bytes = ctx_layout(c, nullptr);
   if (c->ws_bytes > ((size_t)8 << 30) || hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes) != hipSuccess) {
     (void)hipGetLastError();
@@ -560,12 +628,13 @@ moe_status moe_ctx_create(const moe_shape* shape, moe_ctx** out) {
   if (s.n_shared > 0) {  // shared-expert slots carry gate 1 for every token column
     float ones[kMaxShared * kGateCols];
     for (int i = 0; i < s.n_shared * kGateCols; ++i) ones[i] = 1.f;
-    if (hipMemcpy(c->slot_gate + (size_t)c->u_max * kGateCols, ones, sizeof(float) * s.n_shared * kGateCols,
-                  hipMemcpyHostToDevice) != hipSuccess) {
-      (void)hipFree(c->ws);
-      delete c;
-      return MOE_ERR_HIP;
-    }
+    for (int b = 0; b < c->n_sets; ++b)
+      if (hipMemcpy(reinterpret_cast<char*>(c->slot_gate + (size_t)c->u_max * kGateCols) + b * c->set_stride, ones,
+                    sizeof(float) * s.n_shared * kGateCols, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(c->ws);
+        delete c;
+        return MOE_ERR_HIP;
+      }
   }
   *out = c;
   return MOE_OK;
@@ -670,7 +739,7 @@ moe_status moe_verify_layer_noalloc(const moe_shape* shape, const moe_layer_weig
   }
   if (!slot.have_shape || memcmp(&slot.shape, &s, sizeof(s)) != 0) {
     slot.have_shape = false;
-    ctx_set_shape(&slot.ctx, s, dev);
+    ctx_set_shape(&slot.ctx, s, dev, 1);  // single layer-steps only: one copy of the routing workspace
     const size_t need = ctx_layout(&slot.ctx, nullptr, &slot.init_bytes);
     if (need > kScratchBytes) return MOE_ERR_WORKSPACE;  // this geometry needs more than the fixed workspace
     slot.ctx.ws_bytes = ctx_layout(&slot.ctx, slot.base);
@@ -701,28 +770,38 @@ moe_status moe_verify_stack(moe_ctx* c, const moe_layer_weights* layers, int32_t
   hipStream_t st = (hipStream_t)stream;
   const moe_shape& s = c->s;
   const size_t per = (size_t)T * s.d;
-  // With the one-workgroup-per-token router the slab sum of layer l-1 rides at the head of layer l's router launch
-  // (the same workgroup shape; what the chained stack does with its residual pass): one launch less per layer.
-  const bool merge = s.n_experts < kWideRouterExperts && s.d <= 4 * kChainVecs * kChainThreads;
+  if (c->profiling) {  // per-kernel timing wants the same marks per layer-step as a single call
+    for (int l = 0; l < L; ++l)
+      if (moe_status rc = launch_layer(c, layers + l, hidden + l * per, T, out + l * per, nullptr, nullptr, nullptr,
+                                       nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st))
+        return rc;
+    return MOE_OK;
+  }
+  // The inputs of all layers are here before the first layer runs (they do not depend on one another), so routing
+  // is done ahead, for up to kRouteAhead layers per pair of launches, and the slab sum of layer l rides in the
+  // gate/up launch of layer l + 1: two launches per layer-step instead of four or five.  Only this call can do that:
+  // in a decoder the input of layer l + 1 is the output of layer l (moe_chained_stack, moe_decoder_stack).
   int ks = 0;  // > 0: the previous layer's slabs are waiting to be summed into its `out`
-  for (int l = 0; l < L; ++l) {
-    ChainArgs a{};
-    if (ks > 0) {
-      a.partial = c->partial, a.tok_slot = c->tok_slot, a.resid_out = out + (size_t)(l - 1) * per;
-      a.d = s.d, a.T = T, a.top_k = s.top_k, a.u_max = c->u_max, a.n_shared = s.n_shared, a.max_tokens = s.max_tokens;
-      a.KS = ks;
+  for (int l0 = 0; l0 < L; l0 += c->n_sets) {
+    const int B = L - l0 < c->n_sets ? L - l0 : c->n_sets;
+    if (ks > 0) {  // its pick-to-slot table is in the last copy, which the routing below overwrites
+      launch_combine(combine_args(c, route_set(c, c->n_sets - 1), T, out + (size_t)(l0 - 1) * per, ks), st);
+      ks = 0;
     }
-    if (moe_status rc = launch_layer(c, layers + l, hidden + l * per, T, out + l * per, nullptr, nullptr, nullptr,
-                                     nullptr, n_unique_per_layer_opt ? n_unique_per_layer_opt + l : nullptr, st, &ks,
-                                     ks > 0 ? &a : nullptr, merge))
-      return rc;
-    if (!merge) ks = 0;
+    launch_route_ahead(c, layers + l0, B, hidden + (size_t)l0 * per, T,
+                       n_unique_per_layer_opt ? n_unique_per_layer_opt + l0 : nullptr, st);
+    for (int b = 0; b < B; ++b) {
+      const int l = l0 + b;
+      CombineArgs cmb{};
+      if (ks > 0) cmb = combine_args(c, route_set(c, b - 1), T, out + (size_t)(l - 1) * per, ks);
+      if (moe_status rc = launch_experts(c, route_set(c, b), layers + l, T, out + (size_t)l * per, st, &ks, true,
+                                         ks > 0 ? &cmb : nullptr))
+        return rc;
+    }
   }
   if (ks > 0) {
-    const int n4 = T * (s.d / 4);
-    hipLaunchKernelGGL(combine_kernel, dim3((n4 + 255) / 256), dim3(256), 0, st, (const float*)c->partial,
-                       (const int32_t*)c->tok_slot, out + (size_t)(L - 1) * per, s.d, T, s.top_k, c->u_max, s.n_shared,
-                       s.max_tokens, ks);
+    const int last = (L - 1) % c->n_sets;
+    launch_combine(combine_args(c, route_set(c, last), T, out + (size_t)(L - 1) * per, ks), st);
   }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }

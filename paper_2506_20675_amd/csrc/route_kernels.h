@@ -353,7 +353,7 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
 constexpr int kLogitWaves = 8;
 constexpr int kLogitExperts = 16;
 
-__global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, double* __restrict__ logits) {
+__device__ __forceinline__ void logits_body(const RouteArgs& g, double* __restrict__ logits) {
   __shared__ double s_part[kLogitWaves][kLogitExperts];
   const int t = blockIdx.x, e_lo = blockIdx.y * kLogitExperts, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int nE = min(kLogitExperts, g.E - e_lo);
@@ -375,7 +375,12 @@ __global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, d
   }
 }
 
-__global__ __launch_bounds__(1024) void topk_group_kernel(RouteArgs g, GroupArgs grp, const double* __restrict__ logits) {
+__global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, double* __restrict__ logits) {
+  logits_body(g, logits);
+}
+
+__device__ __forceinline__ void topk_group_body(const RouteArgs& g, const GroupArgs& grp,
+                                                const double* __restrict__ logits) {
   __shared__ double s_logit[kMaxTokens * kMaxExperts];
   __shared__ int s_ids[kMaxTokens * kMaxTopK];
   __shared__ float s_sel[kMaxTokens * kMaxTopK];
@@ -419,6 +424,62 @@ __global__ __launch_bounds__(1024) void topk_group_kernel(RouteArgs g, GroupArgs
     group_single_token(grp, s_ids, s_gates);
   else
     group_body(grp, s_ids, s_gates);  // begins with a barrier: the picks are in LDS by then
+}
+
+__global__ __launch_bounds__(1024) void topk_group_kernel(RouteArgs g, GroupArgs grp, const double* __restrict__ logits) {
+  topk_group_body(g, grp, logits);
+}
+
+// ------------------------------------------------------------------------------------------
+// Routing AHEAD for a batch of layers whose inputs are all known before the first of them runs — the stack of
+// independent per-layer inputs (moe_verify_stack), never a decoder, where layer l + 1 reads what layer l wrote.
+// The routing workspace (activation fragments, picks, gates, slot tables) exists in kRouteAhead copies one
+// `set_stride` apart; layer b of the batch is routed by the workgroups with batch index b into copy b, with the
+// same bodies as above, so every table and every fragment is bit-identical to what a launch per layer produces.
+// Two launches per batch instead of one or two per layer.
+// ------------------------------------------------------------------------------------------
+constexpr int kRouteAhead = 16;
+struct AheadArgs {
+  const uint16_t* router_w[kRouteAhead];  // the batch's router matrices
+  size_t hidden_stride;                   // floats between the inputs of consecutive layers
+  size_t set_stride;                      // bytes between consecutive copies of the routing workspace
+  size_t logits_stride;                   // doubles between the logits of consecutive layers
+};
+
+template <class P>
+__device__ __forceinline__ void to_set(P*& p, size_t bytes) {
+  if (p) p = reinterpret_cast<P*>(reinterpret_cast<char*>(p) + bytes);
+}
+// Arguments of batch layer b from those of batch layer 0.  The caller-visible outputs of single calls (picks, gates,
+// union, lists) are not batched and must be NULL, except the per-layer union size n_unique_extra[b].
+__device__ __forceinline__ void ahead_args(RouteArgs& g, GroupArgs& grp, const AheadArgs& a, int b) {
+  const size_t off = (size_t)b * a.set_stride;
+  g.hidden += (size_t)b * a.hidden_stride;
+  g.router_w = a.router_w[b];
+  to_set(g.ids_ws, off), to_set(g.gates_ws, off), to_set(g.xf_hi, off), to_set(g.xf_lo, off);
+  grp.ids = g.ids_ws, grp.gates = g.gates_ws;
+  to_set(grp.n_unique_ws, off), to_set(grp.slot_expert, off), to_set(grp.tok_slot, off);
+  to_set(grp.slot_mask, off), to_set(grp.slot_gate, off);
+  if (grp.n_unique_extra) grp.n_unique_extra += b;
+}
+
+__global__ __launch_bounds__(64 * kRouteWaves) void route_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a) {
+  ahead_args(g, grp, a, blockIdx.y);  // grid (T, batch)
+  route_body(g, grp);
+}
+__global__ __launch_bounds__(256) void group_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a) {
+  ahead_args(g, grp, a, blockIdx.x);  // grid (batch)
+  group_body(grp, nullptr, nullptr);
+}
+__global__ __launch_bounds__(64 * kLogitWaves) void logits_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a,
+                                                                        double* __restrict__ logits) {
+  ahead_args(g, grp, a, blockIdx.z);  // grid (T, expert blocks, batch)
+  logits_body(g, logits + (size_t)blockIdx.z * a.logits_stride);
+}
+__global__ __launch_bounds__(1024) void topk_group_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a,
+                                                                const double* __restrict__ logits) {
+  ahead_args(g, grp, a, blockIdx.x);  // grid (batch)
+  topk_group_body(g, grp, logits + (size_t)blockIdx.x * a.logits_stride);
 }
 
 }  // namespace

@@ -276,25 +276,44 @@ def test_batch_invariance_and_determinism_on_gpu():
 
 
 @pytest.mark.parametrize("T", [1, 4, 9])
-def test_stack_matches_per_layer_oracle(T):
-    """moe_verify_stack on independent per-layer inputs, with the fused down projection (every layer writes its own
-    output) and with the split-K one, where the slab sum of layer l-1 rides in layer l's router launch and only the
-    last layer has a combine launch of its own; both layouts; every layer against the oracle, and the two plans
-    against each other within rounding."""
+@pytest.mark.parametrize("wide", [False, True], ids=["router-per-token", "wide-router"])
+def test_stack_matches_per_layer_oracle(T, wide):
+    """moe_verify_stack on independent per-layer inputs: routing runs ahead for batches of 16 layers (19 layers here:
+    a full batch and a ragged one) and, with the split-K down projection, the slab sum of layer l rides in the
+    gate/up launch of layer l + 1 (a launch of its own only at a batch boundary and after the last layer); with the
+    fused down projection every layer writes its own output.  Both layouts, both router kinds (8 experts: one
+    workgroup per token; 40 experts top-4 with a shared expert: logits + top-k kernels); every layer against the
+    oracle, and the stack call against single-layer calls, bit for bit."""
     import torch
-    cfg = synth.TINY
-    L = 4
-    Ws = [synth.layer_weights_host(cfg, 10 + l) for l in range(L)]
+    L = 19
+    if wide:
+        d, ffn, E, k, ns = 128, 96, 40, 4, 1
+        rng = np.random.default_rng(77)
+        bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+        Ws = []
+        for l in range(L):
+            Ws.append(dict(router_w=bf(rng.normal(0, 0.3, (E, d))), w1=bf(rng.normal(0, 0.1, (E, ffn, d))),
+                           w3=bf(rng.normal(0, 0.1, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))),
+                           sw1=bf(rng.normal(0, 0.1, (ns, ffn, d))), sw3=bf(rng.normal(0, 0.1, (ns, ffn, d))),
+                           sw2=bf(rng.normal(0, 0.1, (ns, d, ffn)))))
+        x = rng.normal(size=(L, T, d)).astype(np.float32)
+    else:
+        cfg = synth.TINY
+        d, ffn, E, k, ns = cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0
+        Ws = [synth.layer_weights_host(cfg, 10 + l) for l in range(L)]
+        x = np.stack([synth.hidden_host(cfg, 10 + l, 0, T, 0.5) for l in range(L)])
     Wds = [_weights_dev(W) for W in Ws]
-    x = np.stack([synth.hidden_host(cfg, 10 + l, 0, T, 0.5) for l in range(L)])
-    refs = [(orc.layer(x[l], Ws[l], cfg.top_k, 0, "f32"), orc.layer(x[l], Ws[l], cfg.top_k, 0, "f64")) for l in range(L)]
-    outs = {}
+    refs = [(orc.layer(x[l], Ws[l], k, ns, "f32"), orc.layer(x[l], Ws[l], k, ns, "f64")) for l in range(L)]
+    for l in range(L):
+        _, _, logits = orc.route(x[l], Ws[l]["router_w"], k, "f64")
+        srt = np.sort(logits, axis=1)[:, ::-1]
+        assert (srt[:, k - 1] - srt[:, k]).min() > 1e-9, "seed produces a routing near-tie; pick another"
     for fused in (-1, 0):
         for tiled in (False, True):
-            ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+            ctx = binding.MoeContext(d, ffn, E, k, ns, 9)
             ctx.moe_ctx_tune(fused_down=fused)
             layers = [_tiled(ctx, w) if tiled else ctx.weights(w) for w in Wds]
-            out = torch.full((L, T, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+            out = torch.full((L, T, d), float("nan"), dtype=torch.float32, device="cuda")
             nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
             for rep in range(2):          # twice: the second pass meets the first one's slabs and tables
                 ctx.moe_verify_stack(layers, _dev(x), out, nu)
@@ -302,14 +321,13 @@ def test_stack_matches_per_layer_oracle(T):
             for l in range(L):
                 (ref32, rids, _), (ref64, _, _) = refs[l]
                 _check_out(out[l].cpu().numpy(), ref32, ref64)
-                assert int(nu[l].item()) == orc.union(rids, cfg.n_experts)["n_unique"]
+                assert int(nu[l].item()) == orc.union(rids, E)["n_unique"]
             # the stack call gives what L single-layer calls give, bit for bit
             for l in range(L):
-                one = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+                one = torch.zeros((T, d), dtype=torch.float32, device="cuda")
                 ctx.moe_verify_layer(layers[l], _dev(x[l]), one)
                 torch.cuda.synchronize()
                 np.testing.assert_array_equal(one.cpu().numpy(), out[l].cpu().numpy())
-            outs[(fused, tiled)] = out.cpu().numpy()
             ctx.close()
 
 
