@@ -196,9 +196,10 @@ moe_status moe_verify_layer(moe_ctx* ctx, const moe_layer_weights* w, const floa
  * launch plan, same results as moe_verify_layer on a fresh context of `shape`, but the workspace is a fixed
  * 32 MiB array inside the library's device code (every GPU the library runs on holds it until the process ends),
  * and the call itself allocates nothing: no hipMalloc / hipFree, no event objects, no allocating library routine.
- *   - The geometry's workspace (what moe_ctx_workspace_bytes reports for a context of `shape`; 12 MiB for the
- *     Mixtral-8x7B-shaped layer at max_tokens 9, under 23 MiB for every Table 1 shape at max_tokens 16) must fit
- *     the array; a geometry that needs more returns MOE_ERR_WORKSPACE and launches nothing.
+ *   - The geometry's workspace (that of a context of `shape`, less the extra copies of the routing tables that
+ *     only moe_verify_stack uses; 12 MiB for the Mixtral-8x7B-shaped layer at max_tokens 9, under 23 MiB for every
+ *     Table 1 shape at max_tokens 16) must fit the array; a geometry that needs more returns MOE_ERR_WORKSPACE and
+ *     launches nothing.
  *   - All calls on one GPU share that GPU's array, which keeps the last call's contents; each call first clears
  *     the part a layer-step reads before writing (a small fill kernel on `stream`).  Calls that overlap on one GPU
  *     — from different streams or threads — race: serialise them.  The array's device address is looked up on the
@@ -209,7 +210,12 @@ moe_status moe_verify_layer_noalloc(const moe_shape* shape, const moe_layer_weig
                                     int32_t* n_unique_opt, void* stream);
 
 /* L layers back to back on one stream without host synchronisation: layer l reads hidden[l] and
- * writes out[l] (independent per-layer inputs; the method's cost model needs no chaining).
+ * writes out[l] (independent per-layer inputs; the method's cost model — Section 2.4: the bytes of the unique
+ * experts of every layer — needs no chaining).  Because no layer's input depends on another layer's output, the
+ * call routes up to 16 layers ahead in one pair of launches and lets the slab sum of one layer ride in the next
+ * layer's gate/up launch: two launches per layer-step.  The results are bit-identical to L moe_verify_layer calls.
+ * A decoder cannot be run this way (its layer l + 1 reads what layer l wrote): see moe_chained_stack and
+ * moe_decoder_stack, which pay the router's launch in every layer.
  * layers: HOST array of L structs (copied during the call).  hidden, out: DEVICE [L,T,d].
  * n_unique_per_layer_opt: DEVICE [L] int32 or NULL. */
 moe_status moe_verify_stack(moe_ctx* ctx, const moe_layer_weights* layers, int32_t L, const float* hidden,
