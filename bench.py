@@ -149,9 +149,10 @@ def main():
         reps = []
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            # lead-in: the last few steps of the group, untimed, so that the first timed step follows a busy GPU as
-            # every step of a decode loop does (a launch into an idle GPU pays its wake-up, 10-20 us)
-            for j in range(by_k_steps - min(4, by_k_steps), by_k_steps):
+            # lead-in: the group once untimed, so that the first timed step follows a busy GPU as every step of a
+            # decode loop does (a launch into an idle GPU pays its wake-up, 10-20 us); the whole group, so that every
+            # step of the sample is launched equally often (the counter summaries under profiles/ average over them)
+            for j in range(by_k_steps):
                 sample_step(ki, k, j)
             e0.record()
             for j in range(by_k_steps):
