@@ -159,7 +159,9 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
-constexpr size_t kFusedDownBytes = (size_t)36 << 20;  // most down-projection bytes per step for the fused down + combine launch
+// most down-projection bytes per step for the fused down + combine launch: bf16 weights in a call that pays for the
+// slab sum's launch; FP8 weights, or a call in which the slab sum rides in another launch (moe_verify_stack)
+constexpr size_t kFusedDownBytes = (size_t)90 << 20, kFusedDownBytesLow = (size_t)36 << 20;
 constexpr int kFusedHalvesBelow = 256;  // fused down + combine: fewer row tiles than this -> two workgroups per tile
 constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
@@ -188,7 +190,8 @@ double expected_slots(const moe_shape& s, int T) {
 }
 
 // plan_override: three ints (gate/up tiles, down tiles, split-K factor), each zero = automatic (moe_ctx_tune)
-Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int T, bool tiled, bool fp8) {
+Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int T, bool tiled, bool fp8,
+              bool combine_rides = false) {
   const double slots = expected_slots(s, T);
   Plan p;
   p.gu_R = tiled ? 1 : ((s.ffn / 16 / 2) * kWaves * slots >= 1536 ? 2 : 1);
@@ -209,15 +212,17 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
       break;
     }
   }
-  // small unions of small experts (up to 36 MB of down-projection weights expected in the step): the step is
-  // latency-bound and one launch less is worth more than the better streaming of the split-K kernel (measured:
-  // 5-8 % on an OLMoE-like layer at K = 0, break-even near 40 MB, a loss beyond).  Items = live slots x C, dealt
-  // to 16 waves; every item keeps >= 8 steps.
+  // small unions of small experts: the step is latency-bound and one launch less is worth more than the better
+  // streaming of the split-K kernel.  Measured on the 64-expert shapes, bf16: the fused launch wins up to about
+  // 90 MB of expected down-projection bytes (K <= 2 or 3), then loses; with FP8 weights, whose fused kernel
+  // streams relatively worse, up to about 36 MB; and where the slab sum costs no launch anyway only at K = 0.
+  // Items = live slots x C, dealt to 16 waves, one item per wave where the union allows; every item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
-  if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= (double)kFusedDownBytes))) {
+  const double fused_limit = (double)(fp8 || combine_rides ? kFusedDownBytesLow : kFusedDownBytes);
+  if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= fused_limit))) {
     int C = 1;
-    while (slots * C < kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;
+    while (slots * (2 * C) <= kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;  // at most one item per wave
     p.dn_fused_C = C;
   }
   if (plan_override[0] > 0) p.gu_R = plan_override[0];
@@ -225,8 +230,8 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   if (plan_override[2] > 0) p.dn_KS = plan_override[2] < cap ? plan_override[2] : cap;
   return p;
 }
-Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8) {
-  return plan_for(c->s, c->plan_override, c->fused_mode, T, tiled, fp8);
+Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8, bool combine_rides = false) {
+  return plan_for(c->s, c->plan_override, c->fused_mode, T, tiled, fp8, combine_rides);
 }
 
 // Geometry-dependent host fields of a context (automatic plan; slab buffer sized for the largest split-K factor
@@ -468,7 +473,7 @@ moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weight
                           hipStream_t st, int* ks_used, bool defer_combine, const CombineArgs* cmb) {
   const moe_shape& s = c->s;
   const bool tiled = w->layout == MOE_LAYOUT_TILED, fp8 = w->dtype == MOE_WEIGHT_FP8_E4M3;
-  const Plan p = plan_for(c, T, tiled, fp8);
+  const Plan p = plan_for(c, T, tiled, fp8, defer_combine || !out);  // the slab sum rides in another launch
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
   const int cr = cmb ? 1 : 0;
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,

@@ -219,10 +219,10 @@ def test_layer_parity_two_shared_experts(T):
 
 
 def test_layer_parity_mid_size_takes_the_split_k_plan_by_itself():
-    """A layer large enough (8 experts of 2048 x 5632: 46 MB of down-projection weights expected at T = 2) that the
+    """A layer large enough (8 experts of 2048 x 8192: 117 MB of down-projection weights expected at T = 2) that the
     automatic plan leaves the fused kernel and picks the split-K down projection with 4 row tiles per wave, as on the
     Mixtral-shaped layer; T = 2 (packed) and T = 9 (split fragments)."""
-    d, ffn, E, k = 2048, 5632, 8, 2
+    d, ffn, E, k = 2048, 8192, 8, 2
     W, rng = _small_layer(d, ffn, E, k, 0, 77)
     ctx = binding.MoeContext(d, ffn, E, k, 0, 9)
     Wd = _weights_dev(W)
