@@ -216,13 +216,20 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   // streaming of the split-K kernel.  Measured on the 64-expert shapes, bf16: the fused launch wins up to about
   // 90 MB of expected down-projection bytes (K <= 2 or 3), then loses; with FP8 weights, whose fused kernel
   // streams relatively worse, up to about 36 MB; and where the slab sum costs no launch anyway only at K = 0.
-  // Items = live slots x C, dealt to 16 waves, one item per wave where the union allows; every item keeps >= 8 steps.
+  // Items = live slots x k-chunks, dealt to 16 waves; every item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
   const double fused_limit = (double)(fp8 || combine_rides ? kFusedDownBytesLow : kFusedDownBytes);
   if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= fused_limit))) {
+    // the split that gives the 16 waves the fewest rounds of the shortest items for the expected union, an item
+    // costing its steps plus about 6 steps' worth of pipeline restart
     int C = 1;
-    while (slots * (2 * C) <= kFusedWaves && nsteps / (2 * C) >= 8) C *= 2;  // at most one item per wave
+    double best = 1e30;
+    for (int c = 1; c <= 8 && (c == 1 || nsteps / c >= 8); c *= 2) {
+      const int rounds = ((int)(slots * c + 0.999) + kFusedWaves - 1) / kFusedWaves;
+      const double cost = rounds * ((nsteps + c - 1) / c + 6.0);
+      if (cost < best) best = cost, C = c;
+    }
     p.dn_fused_C = C;
   }
   if (plan_override[0] > 0) p.gu_R = plan_override[0];
