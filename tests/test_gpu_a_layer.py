@@ -331,6 +331,40 @@ def test_stack_matches_per_layer_oracle(T, wide):
             ctx.close()
 
 
+def test_stack_with_mixed_layer_formats():
+    """Every layer of a stack brings its own weight struct: bf16 and FP8, row-major and tiled, mixed in one call.  Each
+    layer against the oracle of its own format, and against a single-layer call bit for bit."""
+    import torch
+    cfg = synth.TINY
+    T, L = 5, 8
+    ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
+    Ws, layers, keep = [], [], []
+    for l in range(L):
+        fp8, tiled = bool(l & 1), bool(l & 2)
+        W = synth.layer_weights_fp8_host(cfg, 30 + l) if fp8 else synth.layer_weights_host(cfg, 30 + l)
+        Wd = _weights_dev(W)
+        keep.append(Wd)
+        Ws.append((W, fp8))
+        layers.append(_tiled(ctx, Wd) if tiled else ctx.weights(Wd))
+    x = np.stack([synth.hidden_host(cfg, 30 + l, 1, T, 0.5) for l in range(L)])
+    out = torch.full((L, T, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+    nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+    ctx.moe_ctx_tune(fused_down=0)                # split-K: the slab sums ride in the next layer's gate/up launch
+    ctx.moe_verify_stack(layers, _dev(x), out, nu)
+    torch.cuda.synchronize()
+    for l, (W, fp8) in enumerate(Ws):
+        lay = orc.layer_fp8 if fp8 else orc.layer
+        ref32, rids, _ = lay(x[l], W, cfg.top_k, 0, "f32")
+        ref64, _, _ = lay(x[l], W, cfg.top_k, 0, "f64")
+        _check_out(out[l].cpu().numpy(), ref32, ref64)
+        assert int(nu[l].item()) == orc.union(rids, cfg.n_experts)["n_unique"]
+        one = torch.zeros((T, cfg.d), dtype=torch.float32, device="cuda")
+        ctx.moe_verify_layer(layers[l], _dev(x[l]), one)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(one.cpu().numpy(), out[l].cpu().numpy())
+    ctx.close()
+
+
 def test_argument_errors_are_reported_not_launched():
     import torch
     ctx = binding.MoeContext(64, 64, 4, 2, 0, 4)
