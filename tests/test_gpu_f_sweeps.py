@@ -117,7 +117,7 @@ def test_gate_that_underflows_to_zero_still_counts_as_routed():
 def test_random_valid_configurations_match_the_oracle(block):
     """48 seeded random draws over everything a caller may legally combine: d and ffn at the granularity of the
     weight type, 1 .. 256 experts (narrow and wide routers, top_k up to 16), 0 .. 8 shared experts, 1 .. 16 tokens,
-    both gate rules, bf16 in both layouts or FP8, token correlation 0 / 0.5 / 1.  Each is run twice on one context
+    both gate rules, bf16 or FP8 in both layouts, token correlation 0 / 0.5 / 1.  Each is run twice on one context
     (the second run meets the first one's workspace) and compared with the fp64 oracle: ids, gates, union, output.
     (The same generator passed 1200 draws when this test was written.)"""
     import torch
@@ -132,7 +132,7 @@ def test_random_valid_configurations_match_the_oracle(block):
         if rng.random() < 0.5:
             k = min(k, 4)
         ns, T, gm = int(rng.choice([0, 0, 1, 2, 8])), int(rng.integers(1, 17)), int(rng.integers(0, 2))
-        tiled = True if fp8 else bool(rng.integers(0, 2))
+        tiled = bool(seed & 1) if fp8 else bool(rng.integers(0, 2))   # FP8: by seed parity, no draw (keeps the screened streams)
         rho = float(rng.choice([0.0, 0.5, 1.0]))
         case = f"seed={seed} fp8={fp8} d={d} ffn={ffn} E={E} k={k} ns={ns} T={T} gate_mode={gm} tiled={tiled} rho={rho}"
         bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
@@ -198,7 +198,7 @@ def test_random_valid_chained_and_decoder_blocks_match_the_oracle(block):
         if rng.random() < 0.5:
             k = min(k, 4)
         ns, T, gm = int(rng.choice([0, 0, 1, 2, 8])), int(rng.integers(1, 17)), int(rng.integers(0, 2))
-        tiled = True if fp8 else bool(rng.integers(0, 2))
+        tiled = bool(seed & 1) if fp8 else bool(rng.integers(0, 2))
         decoder = bool(rng.integers(0, 2))
         dh, Hkv = int(rng.choice([32, 64, 96, 128])), int(rng.integers(1, 4))
         H = Hkv * int(rng.choice([1, 2, 4]))
