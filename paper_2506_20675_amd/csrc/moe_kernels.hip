@@ -240,6 +240,7 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   if (plan_override[2] > 0) p.dn_KS = plan_override[2] < cap ? plan_override[2] : cap;
   return p;
 }
+bool plan_override_free(const moe_ctx* c) { return c->plan_override[1] == 0; }  // moe_ctx_tune left the down tiles alone
 Plan plan_for(const moe_ctx* c, int T, bool tiled, bool fp8, bool combine_rides = false) {
   return plan_for(c->s, c->plan_override, c->fused_mode, T, tiled, fp8, combine_rides);
 }
@@ -539,10 +540,18 @@ moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weight
   }
   DownArgs da{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, rs.n_unique, rs.slot_expert,
               rs.slot_mask, c->partial, s.d, s.ffn, T, routed_slots, c->u_max, s.max_tokens, p.dn_KS};
-  switch (p.dn_R) {
-    case 4: launch_down<4, 4>(c, da, tiled, fp8, st); break;
-    case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
-    default: launch_down<1, 8>(c, da, tiled, fp8, st); break;
+  if (fp8 && tiled && !pk && p.dn_R == 4 && plan_override_free(c)) {
+    // FP8 weights with split fragments (T > 8) need as many fragment bytes from L2 as weight bytes from HBM at 4
+    // row tiles per wave; 8 tiles at depth 2 halve that (measured: 63 -> 60 us on the Mixtral-shaped layer at T = 9;
+    // with packed fragments, and with bf16 weights, 4 tiles at depth 4 stay faster)
+    const dim3 grid((s.d / 16 + 7) / 8, routed_slots + s.n_shared, da.KS), block(64 * kWaves);
+    hipLaunchKernelGGL((down_kernel<8, kWaves, 2, true, true, true, false>), grid, block, 0, st, da);
+  } else {
+    switch (p.dn_R) {
+      case 4: launch_down<4, 4>(c, da, tiled, fp8, st); break;
+      case 2: launch_down<2, 4>(c, da, tiled, fp8, st); break;
+      default: launch_down<1, 8>(c, da, tiled, fp8, st); break;
+    }
   }
   mark(c, st);
   if (ks_used) *ks_used = p.dn_KS;

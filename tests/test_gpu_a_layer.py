@@ -139,9 +139,9 @@ def test_fp8_layer_parity_mixtral_full_size():
     assert (Wd["q2"][3, 100:200].cpu().numpy() == W["q2"][3, 100:200]).all()
     assert (Wd["s1"].cpu().numpy() == W["s1"]).all()
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
-    for it, (T, rho) in enumerate(((1, 0.5), (5, 0.0))):
+    for it, (T, rho) in enumerate(((1, 0.5), (5, 0.0), (9, 0.5))):   # T = 9: split fragments, 8 row tiles per wave
         x = synth.hidden_host(cfg, 0, 500 + it, T, rho)
-        _check_layer_fp8(ctx, W, Wd, x, cfg.top_k, 0)
+        _check_layer_fp8(ctx, W, Wd, x, cfg.top_k, 0, row_major=T < 9)
     ctx.close()
 
 
