@@ -29,7 +29,8 @@ struct ChainArgs {
 constexpr int kChainThreads = 1024;
 constexpr int kChainVecs = 4;  // float4 per thread: d <= 4 * 4 * 1024
 
-__device__ __forceinline__ void chain_body(const ChainArgs& g) {
+// xs != NULL: the normalised row also goes there (LDS of the calling kernel, d floats).
+__device__ __forceinline__ void chain_body(const ChainArgs& g, float* xs = nullptr) {
   __shared__ float s_ss[kChainThreads / 64];
   const int t = blockIdx.x, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int per_tok = g.d >> 2;
@@ -82,6 +83,7 @@ __device__ __forceinline__ void chain_body(const ChainArgs& g) {
       y.z = (v[q].z / root) * bf16_to_f32(gb.y & 0xffffu);
       y.w = (v[q].w / root) * bf16_to_f32(gb.y >> 16);
       if (g.xn_out) *reinterpret_cast<float4*>(g.xn_out + (size_t)t * g.d + (size_t)c4 * 4) = y;
+      if (xs) *reinterpret_cast<float4*>(xs + (size_t)c4 * 4) = y;
       if (g.xf_hi) {  // this thread's 4 values are one half of the 8-value fragment unit k8 = c4 / 2
         uint16_t hi[4], lo[4];
         split_bf16(y.x, hi[0], lo[0]);
@@ -111,6 +113,20 @@ __global__ __launch_bounds__(kChainThreads) void chain_route_kernel(ChainArgs c,
   __threadfence_block();
   __syncthreads();
   route_body(r, grp);
+}
+
+// In front of a wide router (logits_kernel: one workgroup per (token, 16 experts)) the same saving: every expert
+// block of a token repeats the token's pass — a few KB of slabs and one row of the stream, L2 hits after the first
+// block — keeps the normalised row in LDS and takes its logits from there; expert block 0 alone writes the pass's
+// outputs.  Same arithmetic on the same values as chain_kernel followed by logits_kernel, so the same bits.
+// Requires c.gamma != NULL and d <= kChainLogitsMaxD (the row must fit the LDS array).
+constexpr int kChainLogitsMaxD = 8192;
+__global__ __launch_bounds__(kChainThreads) void chain_logits_kernel(ChainArgs c, RouteArgs r, double* __restrict__ logits) {
+  __shared__ __align__(16) float s_x[kChainLogitsMaxD];
+  if (blockIdx.y != 0) c.resid_out = nullptr, c.xn_out = nullptr, c.xf_hi = nullptr, c.xf_lo = nullptr;
+  chain_body(c, s_x);
+  __syncthreads();
+  logits_body<kChainThreads / 64>(r, logits, s_x);
 }
 
 // ------------------------------------------------------------------------------------------

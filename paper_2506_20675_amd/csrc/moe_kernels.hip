@@ -418,13 +418,16 @@ void launch_route_and_group(moe_ctx* c, const float* hidden, const uint16_t* rou
   const moe_shape& s = c->s;
   const RouteArgs ra = route_args(c, hidden, router_w, T, ids, gates);
   const GroupArgs ga = group_args(c, T, unique, n_unique, n_unique_extra);
-  if (pre && s.n_experts >= kWideRouterExperts)
-    hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre);
   if (s.n_experts >= kWideRouterExperts) {
     // many experts: logits over (token, 16 experts) workgroups, then one workgroup for top-k + union (measured
     // faster than the one-workgroup-per-token router even for a single token, where it costs a launch more)
     const dim3 grid(T, (s.n_experts + kLogitExperts - 1) / kLogitExperts);
-    hipLaunchKernelGGL(logits_kernel, grid, dim3(64 * kLogitWaves), 0, st, ra, c->logits);
+    if (pre && pre->gamma && s.d <= kChainLogitsMaxD) {
+      hipLaunchKernelGGL(chain_logits_kernel, grid, dim3(kChainThreads), 0, st, *pre, ra, c->logits);
+    } else {
+      if (pre) hipLaunchKernelGGL(chain_kernel, dim3(T), dim3(kChainThreads), 0, st, *pre);
+      hipLaunchKernelGGL(logits_kernel, grid, dim3(64 * kLogitWaves), 0, st, ra, c->logits);
+    }
     hipLaunchKernelGGL(topk_group_kernel, dim3(1), dim3(1024), 0, st, ra, ga, (const double*)c->logits);
     return;
   }

@@ -353,11 +353,16 @@ __global__ __launch_bounds__(64 * kRouteWaves) void route_kernel(RouteArgs g, Gr
 constexpr int kLogitWaves = 8;
 constexpr int kLogitExperts = 16;
 
-__device__ __forceinline__ void logits_body(const RouteArgs& g, double* __restrict__ logits) {
+// WAVES: wavefronts of the workgroup.  x_row != NULL: token t's input row is there (possibly in LDS) and not at
+// g.hidden.
+template <int WAVES>
+__device__ __forceinline__ void logits_body(const RouteArgs& g, double* __restrict__ logits,
+                                            const float* x_row = nullptr) {
+  constexpr int kLogitWaves = WAVES;  // shadows the namespace constant inside this body
   __shared__ double s_part[kLogitWaves][kLogitExperts];
   const int t = blockIdx.x, e_lo = blockIdx.y * kLogitExperts, tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63;
   const int nE = min(kLogitExperts, g.E - e_lo);
-  const float* x = g.hidden + (size_t)t * g.d;
+  const float* x = x_row ? x_row : g.hidden + (size_t)t * g.d;
   const int n_batches = (nE + kRouteBatch - 1) / kRouteBatch;
   const int n_items = (g.d >> 9) * n_batches;
   if (lane < kLogitExperts) s_part[wave][lane] = 0.0;
@@ -376,7 +381,7 @@ __device__ __forceinline__ void logits_body(const RouteArgs& g, double* __restri
 }
 
 __global__ __launch_bounds__(64 * kLogitWaves) void logits_kernel(RouteArgs g, double* __restrict__ logits) {
-  logits_body(g, logits);
+  logits_body<kLogitWaves>(g, logits);
 }
 
 __device__ __forceinline__ void topk_group_body(const RouteArgs& g, const GroupArgs& grp,
@@ -474,7 +479,7 @@ __global__ __launch_bounds__(256) void group_ahead_kernel(RouteArgs g, GroupArgs
 __global__ __launch_bounds__(64 * kLogitWaves) void logits_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a,
                                                                         double* __restrict__ logits) {
   ahead_args(g, grp, a, blockIdx.z);  // grid (T, expert blocks, batch)
-  logits_body(g, logits + (size_t)blockIdx.z * a.logits_stride);
+  logits_body<kLogitWaves>(g, logits + (size_t)blockIdx.z * a.logits_stride);
 }
 __global__ __launch_bounds__(1024) void topk_group_ahead_kernel(RouteArgs g, GroupArgs grp, AheadArgs a,
                                                                 const double* __restrict__ logits) {
