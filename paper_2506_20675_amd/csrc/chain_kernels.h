@@ -18,7 +18,7 @@ struct ChainArgs {
   const float* moe_out;    // [T, d]: the MoE term already summed (fused down projection), or NULL
   const float* partial;
   const int32_t* tok_slot;
-  const float* resid_in;   // [T, d], or NULL: no residual stream, resid_out gets the MoE term alone
+  const float* resid_in;   // [T, d] the stream the MoE term is added to
   float* resid_out;        // [T, d] or NULL
   const uint16_t* gamma;   // [d] bf16 or NULL
   float* xn_out;           // [T, d] fp32 normalised output, or NULL
@@ -53,12 +53,8 @@ __device__ __forceinline__ void chain_body(const ChainArgs& g, float* xs = nullp
         m.x += p.x, m.y += p.y, m.z += p.z, m.w += p.w;
       }
       if (g.moe_out) m = *reinterpret_cast<const float4*>(g.moe_out + o);
-      if (g.resid_in) {
-        const float4 x = *reinterpret_cast<const float4*>(g.resid_in + o);
-        v[q] = float4{x.x + m.x, x.y + m.y, x.z + m.z, x.w + m.w};
-      } else {
-        v[q] = m;
-      }
+      const float4 x = *reinterpret_cast<const float4*>(g.resid_in + o);
+      v[q] = float4{x.x + m.x, x.y + m.y, x.z + m.z, x.w + m.w};
       if (g.resid_out) *reinterpret_cast<float4*>(g.resid_out + o) = v[q];
       ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
     }
