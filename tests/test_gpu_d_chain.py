@@ -77,6 +77,50 @@ def test_chained_stack_teacher_forced_and_free_running():
     ctx.close()
 
 
+@pytest.mark.parametrize("d", [256, 16384], ids=["pass-in-the-logits-launch", "pass-in-its-own-launch"])
+@pytest.mark.parametrize("fused", [-1, 0], ids=["fused-down", "split-k-down"])
+def test_chained_stack_with_a_wide_router(d, fused):
+    """Three blocks behind a 40- or 32-expert router (logits + top-k kernels) with a shared expert: from the second block on
+    the slab sum + residual + RMSNorm pass has a pending MoE term to add — slabs of the split-K down projection, or the
+    fused kernel's summed term — and runs inside the logits launch (d <= 8192) or in front of it (d = 16384, the
+    largest d the chained calls take).  Free-running chain against the oracle's chain, T = 1 and 5."""
+    import torch
+    E, k, ns, ffn, L = (40 if d == 256 else 32), 4, 1, 64, 3
+    rng = np.random.default_rng(1000 + d + fused)
+    bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+    sw = 0.1 * (256 / d) ** 0.5                          # keeps the MoE term O(1) at both widths
+    Ws = [dict(router_w=bf(rng.normal(0, 0.3, (E, d))), w1=bf(rng.normal(0, sw, (E, ffn, d))),
+               w3=bf(rng.normal(0, sw, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))),
+               sw1=bf(rng.normal(0, sw, (ns, ffn, d))), sw3=bf(rng.normal(0, sw, (ns, ffn, d))),
+               sw2=bf(rng.normal(0, 0.1, (ns, d, ffn)))) for _ in range(L)]
+    gs = [bf(1 + 0.1 * rng.normal(size=d)) for _ in range(L)]
+    ctx = binding.MoeContext(d, ffn, E, k, ns, 9)
+    ctx.moe_ctx_tune(fused_down=fused)
+    Wds = [_weights_dev(W) for W in Ws]
+    lws = [ctx.moe_pack_weights(ctx.weights(w)) for w in Wds]
+    gds = [_dev(g) for g in gs]
+    for T in (1, 5):
+        x0 = rng.normal(size=(T, d)).astype(np.float32)
+        xL, trace, ids = orc.chained_stack(x0, Ws, gs, k, ns, 1e-5, "f64")
+        for l in range(L):                                # the routing must not hinge on the last bits of the stream
+            n = orc.rmsnorm(trace[l].astype(np.float32), gs[l], 1e-5, "f64").astype(np.float32)
+            _, _, logits = orc.route(n, Ws[l]["router_w"], k, "f64")
+            srt = np.sort(logits, axis=1)[:, ::-1]
+            assert (srt[:, k - 1] - srt[:, k]).min() > 1e-4, "seed produces a thin routing margin; pick another"
+        out = torch.zeros((T, d), dtype=torch.float32, device="cuda")
+        tr = torch.zeros((L, T, d), dtype=torch.float32, device="cuda")
+        nu = torch.zeros((L,), dtype=torch.int32, device="cuda")
+        ctx.moe_chained_stack(lws, gds, _dev(x0), out, 1e-5, tr, nu)
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert int(nu[l].item()) == orc.union(ids[l], E)["n_unique"]
+            e = tr[l].cpu().numpy().astype(np.float64) - trace[l]
+            assert np.sqrt((e ** 2).sum() / (trace[l].astype(np.float64) ** 2).sum()) <= 1e-4
+        e = out.cpu().numpy().astype(np.float64) - xL
+        assert np.sqrt((e ** 2).sum() / (xL.astype(np.float64) ** 2).sum()) <= 1e-4
+    ctx.close()
+
+
 @pytest.mark.parametrize("T", [1, 4, 9])
 def test_decoder_block_parity_tiny(T):
     cfg = synth.TINY
