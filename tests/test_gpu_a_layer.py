@@ -171,6 +171,22 @@ def test_layer_parity_ragged_shapes(shape):
     _check_layer((d, ffn, E, k, ns), W, x)
 
 
+@pytest.mark.parametrize("shape", [(16384, 64, 4, 2, 1, 3), (16384, 32, 64, 8, 0, 2)], ids=["router-per-token", "wide-router"])
+def test_layer_parity_widest_rows(shape):
+    """d = 16384: 32 chunks of 512 per router row, 512 k-steps per gate/up wave, the largest row the chained calls and
+    the slab sum take; both router kinds, both layouts."""
+    d, ffn, E, k, ns, T = shape
+    rng = np.random.default_rng(sum(shape))
+    bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
+    W = dict(router_w=bf(rng.normal(0, 0.05, (E, d))), w1=bf(rng.normal(0, 0.0125, (E, ffn, d))),
+             w3=bf(rng.normal(0, 0.0125, (E, ffn, d))), w2=bf(rng.normal(0, 0.1, (E, d, ffn))))
+    if ns:
+        W.update(sw1=bf(rng.normal(0, 0.0125, (ns, ffn, d))), sw3=bf(rng.normal(0, 0.0125, (ns, ffn, d))),
+                 sw2=bf(rng.normal(0, 0.1, (ns, d, ffn))))
+    x = rng.normal(size=(T, d)).astype(np.float32)
+    _check_layer((d, ffn, E, k, ns), W, x)
+
+
 def _small_layer(d, ffn, E, k, ns, seed):
     rng = np.random.default_rng(seed)
     bf = lambda a: synth.f32_to_bf16_bits(a.astype(np.float32))
