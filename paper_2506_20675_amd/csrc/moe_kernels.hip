@@ -165,6 +165,7 @@ constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 // most down-projection bytes per step for the fused down + combine launch: bf16 weights in a call that pays for the
 // slab sum's launch; FP8 weights, or a call in which the slab sum rides in another launch (moe_verify_stack)
 constexpr size_t kFusedDownBytes = (size_t)90 << 20, kFusedDownBytesLow = (size_t)36 << 20;
+constexpr size_t kFusedDownBytesWide = (size_t)200 << 20;  // bf16, single call, d / 16 >= 256: one workgroup per row tile
 constexpr int kFusedHalvesBelow = 256;  // fused down + combine: fewer row tiles than this -> two workgroups per tile
 constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
@@ -219,10 +220,14 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   // streaming of the split-K kernel.  Measured on the 64-expert shapes, bf16: the fused launch wins up to about
   // 90 MB of expected down-projection bytes (K <= 2 or 3), then loses; with FP8 weights, whose fused kernel
   // streams relatively worse, up to about 36 MB; and where the slab sum costs no launch anyway only at K = 0.
+  // Where d gives every compute unit a whole row tile (no half tiles: half the fragment bytes per weight byte)
+  // the fused kernel streams about 15 % slower than split-K and pays up to about 200 MB (Phi-3.5-like layer at
+  // K = 0 and 1: 2 us; the Mixtral-shaped layer starts at 235 MB and loses 0.3-0.9 us).
   // Items = live slots x k-chunks, dealt to 16 waves; every item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
-  const double fused_limit = (double)(fp8 || combine_rides ? kFusedDownBytesLow : kFusedDownBytes);
+  const double fused_limit = (double)(fp8 || combine_rides ? kFusedDownBytesLow
+                                    : s.d / 16 >= kFusedHalvesBelow ? kFusedDownBytesWide : kFusedDownBytes);
   if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= fused_limit))) {
     // the split that gives the 16 waves the fewest rounds of the shortest items for the expected union, an item
     // costing its steps plus about 6 steps' worth of pipeline restart

@@ -141,7 +141,7 @@ def test_launch_plan_is_host_arithmetic_with_sane_invariants():
     """moe_plan_query needs no device.  For every benchmark shape, weight type and T: the split-K factor is a power of
     two that leaves every wave at least 4 k-steps, the workspace rule (slabs per slot <= 16) holds, tile counts are
     from the instantiated set, the fused down + combine launch is chosen only while the expected down-projection
-    bytes stay under its limit (90 MB for bf16, 36 MB for FP8), and the launch count follows from the choices."""
+    bytes stay under its limit (bf16: 90 MB, or 200 MB where d gives at least 256 row tiles; FP8: 36 MB), and the launch count follows from the choices."""
     from paper_2506_20675_amd import synth
     seen_fused = seen_split = False
     for cfg in (synth.TINY, synth.MIXTRAL, synth.OLMOE, synth.DEEPSEEK, synth.PHI35, synth.QWEN15):
@@ -160,13 +160,14 @@ def test_launch_plan_is_host_arithmetic_with_sane_invariants():
                     assert 1 <= ks <= 16 and ks & (ks - 1) == 0
                     assert ks == 1 or nsteps // (4 * ks) >= 4
                     bytes_dn = p["expected_slots"] * cfg.d * cfg.ffn * (1 if dtype else 2)
+                    fused_limit = (36 if dtype else (200 if cfg.d // 16 >= 256 else 90)) * 2**20
                     if p["dn_fused_chunks"] > 0:
                         seen_fused = True
-                        assert layout == binding.MOE_LAYOUT_TILED and bytes_dn <= (36 if dtype else 90) * 2**20
+                        assert layout == binding.MOE_LAYOUT_TILED and bytes_dn <= fused_limit
                         assert nsteps // p["dn_fused_chunks"] >= 8 or p["dn_fused_chunks"] == 1   # >= 8 k-steps per item
                     else:
                         seen_split = True
-                        assert layout == binding.MOE_LAYOUT_ROW_MAJOR or bytes_dn > (36 if dtype else 90) * 2**20
+                        assert layout == binding.MOE_LAYOUT_ROW_MAJOR or bytes_dn > fused_limit
                     router = 2 if (p["wide_router"] or T > 1) else 1
                     assert p["launches"] == router + 1 + (1 if p["dn_fused_chunks"] > 0 else 2)
     assert seen_fused and seen_split
