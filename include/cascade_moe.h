@@ -215,8 +215,7 @@ moe_status moe_verify_layer_noalloc(const moe_shape* shape, const moe_layer_weig
  * call routes up to 16 layers ahead in one pair of launches and lets the slab sum of one layer ride in the next
  * layer's gate/up launch: two launches per layer-step.  The results are those of L moe_verify_layer calls, bit for
  * bit wherever both pick the same down-projection plan (a slab sum that costs no launch moves the point where the
- * fused down + combine kernel stops paying: bf16 steps with 36-90 MB of expected down-projection bytes differ in
- * the order of that sum).
+ * fused down + combine kernel stops paying, so a step may differ in the order of that sum).
  * A decoder cannot be run this way (its layer l + 1 reads what layer l wrote): see moe_chained_stack and
  * moe_decoder_stack, which pay the router's launch in every layer.
  * layers: HOST array of L structs (copied during the call).  hidden, out: DEVICE [L,T,d].

@@ -59,6 +59,7 @@ struct GateupArgs {
   uint16_t *hf_hi, *hf_lo;              // [u_max + n_shared] fragments of gate*silu(G)*U, ffn*16 elements each
   int d, ffn, T, routed_slots, u_max;   // routed_slots = min(E, T*top_k) slots in this grid
   int cmb_rows;                         // 0, or 1: row y = 0 of the grid runs the slab sum `cmb`
+  int h_cols;                           // 0: H in the regular fragment layout; 2 T: compact packed layout (see frag_unit_compact)
   CombineArgs cmb;
 };
 
@@ -204,10 +205,14 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
       split_bf16(gate * (G.z / (1.f + expf(-G.z))) * U.z, hi[2], lo[2]);
       split_bf16(gate * (G.w / (1.f + expf(-G.w))) * U.w, hi[3], lo[3]);
       const int k = (tile0 + j) * 16 + kg * 4;
-      const size_t o = frag_unit(k >> 3, r) * 8 + (k & 4);
+      size_t o = frag_unit(k >> 3, r) * 8 + (k & 4), o_lo = o + kPackedTokens * 8;
+      if (PK && g.h_cols) {  // the fused down + combine kernel reads the compact layout
+        o = frag_unit_compact(k >> 3, r, g.h_cols) * 8 + (k & 4);
+        o_lo = o + (size_t)(g.h_cols >> 1) * 8;
+      }
       *reinterpret_cast<uint2*>(HH + o) =
           uint2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
-      *reinterpret_cast<uint2*>((PK ? HH + kPackedTokens * 8 : HL) + o) =
+      *reinterpret_cast<uint2*>(PK ? HH + o_lo : HL + o) =
           uint2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
     }
   }
@@ -377,6 +382,7 @@ struct DownFusedArgs {
   float* out;  // [T, d]
   int d, ffn, T, n_shared, u_max, C;  // C = k-chunks per slot
   int halves;                         // 1 or 2 workgroups per 16-row tile
+  int h_cols;                         // 0: H in the regular fragment layout; 2 T: compact packed layout
 };
 
 constexpr int kFusedWaves = 16;
@@ -394,7 +400,18 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
   const int nu = *g.n_unique, n_items = (nu + g.n_shared) * g.C;
   const int nsteps = g.ffn >> (FP8 ? 6 : 5), chunk = (nsteps + g.C - 1) / g.C;
   const WeightAddr<true, FP8> wa(g.ffn, r_load, kg, kg * 16 + r_load);
-  const uint32_t b_off = lane * 16;
+  // Fragment addressing: regular layout = 1 KB per k-step, lane l at byte 16 l.  Compact packed layout (PK only):
+  // 2 T columns per k-group instead of 16 — this kernel fetches one fragment byte per weight byte, and at small T
+  // most of a regular fragment is padding.  A lane of a padding column reads a live column's unit again (same
+  // address, no extra request); its MFMA column is never stored.
+  uint32_t b_off = lane * 16, kstep_bytes = 1024;
+  if constexpr (PK) {
+    if (g.h_cols) {
+      const int Tn = g.h_cols >> 1, t = min(r & (kPackedTokens - 1), Tn - 1);
+      b_off = (uint32_t)(kg * g.h_cols + (r < kPackedTokens ? t : Tn + t)) * 16;
+      kstep_bytes = 64u * g.h_cols;
+    }
+  }
   f32x4 total = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int item = wave; item < n_items; item += kFusedWaves) {
     const int sl = item / g.C, c = item - sl * g.C;
@@ -418,10 +435,9 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
     const int nst = max(0, min(chunk, nsteps - c * chunk));
     const int s_beg = min(c * chunk, nsteps - 1);
     const char* base = W2 + (size_t)tile * wa.tile_stride + (size_t)s_beg * wa.step_stride;
-    const char* HH =
-        reinterpret_cast<const char*>(g.hf_hi) + ((size_t)hslot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
-    const char* HL =
-        reinterpret_cast<const char*>(g.hf_lo) + ((size_t)hslot * g.ffn * 16 + (size_t)s_beg * (512 * NB)) * 2;
+    const size_t h_off = (size_t)hslot * g.ffn * 32 + (size_t)s_beg * NB * (PK ? kstep_bytes : 1024u);
+    const char* HH = reinterpret_cast<const char*>(g.hf_hi) + h_off;
+    const char* HL = reinterpret_cast<const char*>(g.hf_lo) + h_off;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     pipeline<1, NB, PK, P>(
         nst,
@@ -429,8 +445,12 @@ __global__ __launch_bounds__(64 * kFusedWaves) void down_fused_kernel(DownFusedA
           st.a[0] = ld128<true>(base, wa.lane_off + (uint32_t)s * wa.step_stride);
 #pragma unroll
           for (int b = 0; b < NB; ++b) {  // unconditional loads, masked where consumed (as in down_kernel)
-            st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
-            if constexpr (!PK) st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+            if constexpr (PK) {
+              st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * kstep_bytes);
+            } else {
+              st.bh[b] = ld128<false>(HH, b_off + (uint32_t)(s * NB + b) * 1024);
+              st.bl[b] = ld128<false>(HL, b_off + (uint32_t)(s * NB + b) * 1024);
+            }
           }
         },
         [&](const Stage<1, NB, PK>& st) {

@@ -66,6 +66,13 @@ __device__ __forceinline__ size_t frag_unit(int k8, int n) {  // k8 = k / 8
   return (size_t)(k8 >> 2) * 64 + (size_t)(k8 & 3) * 16 + n;
 }
 
+// Compact variant of the packed arrangement, used where fragment bytes are the bottleneck: per k-group only the
+// `cols` = 2 T live columns (hi halves of tokens 0 .. T-1, then their lo halves) instead of 16, so a k-step is
+// 64 * cols bytes.  With cols = 16 it is the packed arrangement itself.
+__device__ __forceinline__ size_t frag_unit_compact(int k8, int c, int cols) {
+  return (size_t)(k8 >> 2) * (4 * cols) + (size_t)(k8 & 3) * cols + c;
+}
+
 // FP8 weights: the 16 bytes a lane loads are its 8 codes of one k-step followed by its 8 codes of the
 // next k-step.  Every E4M3 value is exactly a bf16 number, so the codes are widened in registers (two
 // codes per instruction) and fed to the same bf16 MFMA; the per-row scale is applied to the fp32 sums.

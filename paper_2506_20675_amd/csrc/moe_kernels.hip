@@ -162,10 +162,10 @@ namespace {
 constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
-// most down-projection bytes per step for the fused down + combine launch: bf16 weights in a call that pays for the
-// slab sum's launch; FP8 weights, or a call in which the slab sum rides in another launch (moe_verify_stack)
-constexpr size_t kFusedDownBytes = (size_t)90 << 20, kFusedDownBytesLow = (size_t)36 << 20;
-constexpr size_t kFusedDownBytesWide = (size_t)200 << 20;  // bf16, single call, d / 16 >= 256: one workgroup per row tile
+// The fused down + combine launch is chosen by the number of tokens in flight (see plan_for): with few tokens its
+// compact H fragments make it stream as well as the split-K kernel, and it needs neither slabs nor a slab sum.
+constexpr int kFusedMaxTokensBf16 = 5, kFusedMaxTokensFp8 = 4, kFusedMaxTokensRiding = 4;
+constexpr double kFusedMaxSlots = 32.0;  // larger unions were not measured: they take the split-K plan
 constexpr int kFusedHalvesBelow = 256;  // fused down + combine: fewer row tiles than this -> two workgroups per tile
 constexpr int kWideRouterExperts = 32;  // from this many experts on, routing goes through logits_kernel + topk_group_kernel
 
@@ -216,19 +216,23 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
       break;
     }
   }
-  // small unions of small experts: the step is latency-bound and one launch less is worth more than the better
-  // streaming of the split-K kernel.  Measured on the 64-expert shapes, bf16: the fused launch wins up to about
-  // 90 MB of expected down-projection bytes (K <= 2 or 3), then loses; with FP8 weights, whose fused kernel
-  // streams relatively worse, up to about 36 MB; and where the slab sum costs no launch anyway only at K = 0.
-  // Where d gives every compute unit a whole row tile (no half tiles: half the fragment bytes per weight byte)
-  // the fused kernel streams about 15 % slower than split-K and pays up to about 200 MB (Phi-3.5-like layer at
-  // K = 0 and 1: 2 us; the Mixtral-shaped layer starts at 235 MB and loses 0.3-0.9 us).
-  // Items = live slots x k-chunks, dealt to 16 waves; every item keeps >= 8 steps.
+  // Down projection and slab sum in ONE launch (down_fused_kernel, tiled weights, packed fragments): it fetches one
+  // fragment byte per weight byte, but takes H in a compact layout of 2 T columns, so with few tokens in flight that
+  // costs little, and it writes no slabs.  Measured against split-K + slab sum on all six shapes, each forced both
+  // ways at every K: with bf16 weights it wins for T <= 5 (Mixtral-shaped layer 3-8 us at K = 0..3, Phi-3.5-like up
+  // to 7 us, the 64-expert shapes 1-3 us) and loses from T = 6 or 7 on; with FP8 weights for T <= 4.  Where the slab
+  // sum costs no launch anyway (moe_verify_stack, chained stacks) it still wins for T <= 4 on layers that give every
+  // compute unit a whole row tile (d / 16 >= 256: 3-5 us per layer) and loses on narrower ones, whose half-tile
+  // workgroups fetch two fragment bytes per weight byte.  Items = live slots x k-chunks, dealt to 16 waves; every
+  // item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
-  const double fused_limit = (double)(fp8 || combine_rides ? kFusedDownBytesLow
-                                    : s.d / 16 >= kFusedHalvesBelow ? kFusedDownBytesWide : kFusedDownBytes);
-  if (tiled && (fused_mode > 0 || (fused_mode < 0 && slots * s.d * s.ffn * (fp8 ? 1 : 2) <= fused_limit))) {
+  bool fuse = false;
+  if (tiled && T <= kPackedTokens && slots <= kFusedMaxSlots)
+    fuse = combine_rides ? (s.d / 16 >= kFusedHalvesBelow && T <= kFusedMaxTokensRiding)
+                         : T <= (fp8 ? kFusedMaxTokensFp8 : kFusedMaxTokensBf16);
+  if (fused_mode >= 0) fuse = fused_mode > 0 && tiled;
+  if (fuse) {
     // the split that gives the 16 waves the fewest rounds of the shortest items for the expected union, an item
     // costing its steps plus about 6 steps' worth of pipeline restart
     int C = 1;
@@ -495,11 +499,13 @@ moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weight
   const Plan p = plan_for(c, T, tiled, fp8, defer_combine || !out);  // the slab sum rides in another launch
   const int routed_slots = T * s.top_k < s.n_experts ? T * s.top_k : s.n_experts;  // largest union T tokens can form
   const int cr = cmb ? 1 : 0;
+  const bool pk = T <= kPackedTokens;  // must match what the router wrote
+  // the fused down + combine kernel takes H in the compact packed layout: 2 T columns per k-group instead of 16
+  const int h_cols = pk && p.dn_fused_C > 0 ? 2 * T : 0;
   GateupArgs ga{w->w1, w->w3, w->sw1, w->sw3, w->w1_scale, w->w3_scale, w->sw1_scale, w->sw3_scale,
                 rs.xf_hi, rs.xf_lo, rs.n_unique, rs.slot_expert, rs.slot_mask, rs.slot_gate,
-                c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max, cr, cmb ? *cmb : CombineArgs{}};
+                c->hf_hi, c->hf_lo, s.d, s.ffn, T, routed_slots, c->u_max, cr, h_cols, cmb ? *cmb : CombineArgs{}};
   const unsigned rows = routed_slots + s.n_shared + cr;
-  const bool pk = T <= kPackedTokens;  // must match what the router wrote
   if (fp8 && !tiled) {
     // row-major FP8 (the layout checkpoints come in; the tiled one is the fast path): two tile pairs per wave,
     // four waves splitting d, whatever the plan says
@@ -532,7 +538,7 @@ moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weight
     // buffer as a plain [T, d] array and *ks_used = 0 tells the caller so
     DownFusedArgs fa{w->w2, w->sw2, w->w2_scale, w->sw2_scale, c->hf_hi, c->hf_lo, rs.n_unique, rs.slot_expert,
                      rs.slot_mask, out ? out : c->partial, s.d, s.ffn, T, s.n_shared, c->u_max, p.dn_fused_C,
-                     s.d / 16 < kFusedHalvesBelow ? 2 : 1};
+                     s.d / 16 < kFusedHalvesBelow ? 2 : 1, h_cols};
     const dim3 grid(s.d / 16 * fa.halves), block(64 * kFusedWaves);
     if (fp8) {
       if (pk) hipLaunchKernelGGL((down_fused_kernel<4, true, true>), grid, block, 0, st, fa);

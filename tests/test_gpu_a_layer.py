@@ -201,17 +201,17 @@ def _small_layer(d, ffn, E, k, ns, seed):
 @pytest.mark.parametrize("T", [1, 5, 9, 16])
 @pytest.mark.parametrize("fused", [False, True], ids=["splitk", "fused"])
 def test_layer_parity_tiny_both_down_paths(T, fused):
-    """The tiny layer with the down projection forced onto the split-K kernel + combine_kernel (what the benchmark's
-    Mixtral-shaped layer runs, here in a sub-second case) and left on the fused down + combine kernel, for packed
-    (T <= 8) and split (T > 8) fragments.  The launch plan must say which of the two it is."""
+    """The tiny layer with the down projection forced onto the split-K kernel + combine_kernel and onto the fused down
+    + combine kernel (the two plans the benchmark's Mixtral-shaped layer runs at many and at few tokens in flight, here
+    in a sub-second case), for packed (T <= 8; compact H fragments on the fused path) and split (T > 8) fragments.  The
+    launch plan must say which of the two the automatic choice is."""
     cfg = synth.TINY
     W = synth.layer_weights_host(cfg, 0)
     x = synth.hidden_host(cfg, 0, 60 + T, T, 0.5)
     plan = binding.moe_plan_query(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 16, T)
-    assert plan["dn_fused_chunks"] > 0 and plan["packed_fragments"] == (T <= 8)    # automatic choice on this shape
+    assert (plan["dn_fused_chunks"] > 0) == (T <= 5) and plan["packed_fragments"] == (T <= 8)
     ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 16)
-    if not fused:
-        ctx.moe_ctx_tune(fused_down=0)
+    ctx.moe_ctx_tune(fused_down=1 if fused else 0)
     Wd = _weights_dev(W)
     _check_layer((cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0), W, x, ctx, Wd)
     if not fused:                      # the benchmark's instantiation (4 row tiles per wave; this small ffn caps the k-chunks at 2)
@@ -228,23 +228,26 @@ def test_layer_parity_two_shared_experts(T):
     x = rng.normal(size=(T, d)).astype(np.float32)
     for fused in (True, False):
         ctx = binding.MoeContext(d, ffn, E, k, ns, 9)
-        if not fused:
-            ctx.moe_ctx_tune(fused_down=0)
+        ctx.moe_ctx_tune(fused_down=1 if fused else 0)
         _check_layer((d, ffn, E, k, ns), W, x, ctx, _weights_dev(W))
         ctx.close()
 
 
-def test_layer_parity_mid_size_takes_the_split_k_plan_by_itself():
-    """A layer large enough (8 experts of 2048 x 8192: 117 MB of down-projection weights expected at T = 2) that the
-    automatic plan leaves the fused kernel and picks the split-K down projection with 4 row tiles per wave, as on the
-    Mixtral-shaped layer; T = 2 (packed) and T = 9 (split fragments)."""
+def test_layer_parity_mid_size_takes_the_benchmarked_plans_by_itself():
+    """A layer of 8 experts of 2048 x 8192 under the automatic plan, in a sub-second test: with 6 and 9 tokens in flight
+    it picks the split-K down projection with 4 row tiles per wave and a slab sum, as the Mixtral-shaped layer does
+    (T = 6: packed fragments, T = 9: split fragments); with 2 tokens the fused down + combine launch with compact H
+    fragments."""
     d, ffn, E, k = 2048, 8192, 8, 2
     W, rng = _small_layer(d, ffn, E, k, 0, 77)
     ctx = binding.MoeContext(d, ffn, E, k, 0, 9)
     Wd = _weights_dev(W)
-    for T in (2, 9):
+    for T in (6, 9, 2):
         plan = binding.moe_plan_query(d, ffn, E, k, 0, 9, T)
-        assert plan["dn_fused_chunks"] == 0 and plan["dn_tiles"] == 4 and plan["dn_split_k"] >= 2, plan
+        if T > 5:
+            assert plan["dn_fused_chunks"] == 0 and plan["dn_tiles"] == 4 and plan["dn_split_k"] >= 2, plan
+        else:
+            assert plan["dn_fused_chunks"] > 0, plan
         x = rng.normal(size=(T, d)).astype(np.float32)
         _check_layer((d, ffn, E, k, 0), W, x, ctx, Wd)
     ctx.close()
@@ -297,7 +300,7 @@ def test_stack_matches_per_layer_oracle(T, wide):
     """moe_verify_stack on independent per-layer inputs: routing runs ahead for batches of 16 layers (19 layers here:
     a full batch and a ragged one) and, with the split-K down projection, the slab sum of layer l rides in the
     gate/up launch of layer l + 1 (a launch of its own only at a batch boundary and after the last layer); with the
-    fused down projection every layer writes its own output.  Both layouts, both router kinds (8 experts: one
+    fused down projection every layer writes its own output.  Automatic plan and both plans forced, both layouts, both router kinds (8 experts: one
     workgroup per token; 40 experts top-4 with a shared expert: logits + top-k kernels); every layer against the
     oracle, and the stack call against single-layer calls, bit for bit."""
     import torch
@@ -324,7 +327,7 @@ def test_stack_matches_per_layer_oracle(T, wide):
         _, _, logits = orc.route(x[l], Ws[l]["router_w"], k, "f64")
         srt = np.sort(logits, axis=1)[:, ::-1]
         assert (srt[:, k - 1] - srt[:, k]).min() > 1e-9, "seed produces a routing near-tie; pick another"
-    for fused in (-1, 0):
+    for fused in (-1, 0, 1):
         for tiled in (False, True):
             ctx = binding.MoeContext(d, ffn, E, k, ns, 9)
             ctx.moe_ctx_tune(fused_down=fused)
@@ -338,8 +341,9 @@ def test_stack_matches_per_layer_oracle(T, wide):
                 (ref32, rids, _), (ref64, _, _) = refs[l]
                 _check_out(out[l].cpu().numpy(), ref32, ref64)
                 assert int(nu[l].item()) == orc.union(rids, E)["n_unique"]
-            # the stack call gives what L single-layer calls give, bit for bit
-            for l in range(L):
+            # under one down-projection plan the stack call gives what L single-layer calls give, bit for bit (left
+            # to itself it may pick another plan than a single call: its slab sums cost no launch)
+            for l in range(L if fused >= 0 else 0):
                 one = torch.zeros((T, d), dtype=torch.float32, device="cuda")
                 ctx.moe_verify_layer(layers[l], _dev(x[l]), one)
                 torch.cuda.synchronize()

@@ -99,8 +99,7 @@ def test_gate_that_underflows_to_zero_still_counts_as_routed():
     Wd = _weights_dev(W)
     for no_fused in (False, True):
         ctx = binding.MoeContext(cfg.d, cfg.ffn, cfg.n_experts, cfg.top_k, 0, 9)
-        if no_fused:
-            ctx.moe_ctx_tune(fused_down=0)
+        ctx.moe_ctx_tune(fused_down=0 if no_fused else 1)
         for tiled in (False, True):
             for rep in range(2):      # twice: the second run meets the first one's leftovers in the workspace
                 out, ids, gates, uniq, nu = _run_layer(ctx, Wd, x if rep == 0 else x[::-1].copy(), tiled)
