@@ -221,15 +221,15 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   // costs little, and it writes no slabs.  Measured against split-K + slab sum on all six shapes, each forced both
   // ways at every K: with bf16 weights it wins for T <= 5 (Mixtral-shaped layer 3-8 us at K = 0..3, Phi-3.5-like up
   // to 7 us, the 64-expert shapes 1-3 us) and loses from T = 6 or 7 on; with FP8 weights for T <= 4.  Where the slab
-  // sum costs no launch anyway (moe_verify_stack, chained stacks) it still wins for T <= 4 on layers that give every
-  // compute unit a whole row tile (d / 16 >= 256: 3-5 us per layer) and loses on narrower ones, whose half-tile
-  // workgroups fetch two fragment bytes per weight byte.  Items = live slots x k-chunks, dealt to 16 waves; every
+  // sum costs no launch anyway (moe_verify_stack, chained stacks) it still wins for T <= 4 with bf16 weights on
+  // layers that give every compute unit a whole row tile (d / 16 >= 256: 3-5 us per layer); it loses on narrower
+  // ones, whose half-tile workgroups fetch two fragment bytes per weight byte, and is level or worse with FP8 weights.  Items = live slots x k-chunks, dealt to 16 waves; every
   // item keeps >= 8 steps.
   p.dn_fused_C = 0;
   const int nsteps = s.ffn / (fp8 ? 64 : 32);
   bool fuse = false;
   if (tiled && T <= kPackedTokens && slots <= kFusedMaxSlots)
-    fuse = combine_rides ? (s.d / 16 >= kFusedHalvesBelow && T <= kFusedMaxTokensRiding)
+    fuse = combine_rides ? (!fp8 && s.d / 16 >= kFusedHalvesBelow && T <= kFusedMaxTokensRiding)
                          : T <= (fp8 ? kFusedMaxTokensFp8 : kFusedMaxTokensBf16);
   if (fused_mode >= 0) fuse = fused_mode > 0 && tiled;
   if (fuse) {
