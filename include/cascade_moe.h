@@ -88,12 +88,13 @@ int64_t moe_ctx_workspace_bytes(const moe_ctx* ctx);
 
 /* Tuning aid: override parts of the launch plan of THIS context for all later calls (what moe_plan_query
  * describes; the kernels and their results per element are the same, only the split of the work changes).
- *   gu_tiles, dn_tiles  0 = automatic, or 1, 2, 4 (gu_tiles is honoured for row-major weights only: the
- *                       tiled gate/up kernels have one fixed shape per weight type)
+ *   gu_tiles, dn_tiles  0 = automatic, or 1, 2, 4 (gu_tiles is honoured for row-major bf16 weights and, as
+ *                       1 or 2 tile pairs per wavefront, for tiled FP8 weights with T <= 8; the other gate/up
+ *                       kernels have one fixed shape)
  *   dn_split_k          0 = automatic, or a power of two <= 16; clamped to what the shape allows and to the
  *                       largest split the workspace was sized for at creation
- *   fused_down          -1 = automatic, 0 = never fuse the down projection with the combine, 1 = always (tiled
- *                       weights; measured slower than split-K + combine beyond ~40 MB of down-projection bytes)
+ *   fused_down          -1 = automatic (few tokens in flight), 0 = never fuse the down projection with the
+ *                       combine, 1 = always (tiled weights)
  * Host only, no device work.  MOE_ERR_INVALID_ARG for any other value. */
 moe_status moe_ctx_tune(moe_ctx* ctx, int32_t gu_tiles, int32_t dn_tiles, int32_t dn_split_k, int32_t fused_down);
 
