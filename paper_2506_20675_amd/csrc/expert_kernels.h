@@ -221,7 +221,7 @@ __global__ __launch_bounds__(64 * W) void gateup_kernel(GateupArgs g) {
 // ------------------------------------------------------------------------------------------
 // Step 4: down projection, split-K over (expert, k-chunk).  The gate is already folded into H, so
 // every slab is a plain partial sum of out.
-// grid = (row blocks of 16*R rows of d, min(E, T*top_k) + n_shared slots, KS k-chunks); block = W waves
+// grid = (row blocks of 16*R rows of d, KS k-chunks, min(E, T*top_k) + n_shared slots); block = W waves
 // splitting the chunk.
 // ------------------------------------------------------------------------------------------
 struct DownArgs {
@@ -240,8 +240,10 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
   constexpr int NB = FP8 ? 2 : 1;
   __shared__ float4 red[W > 1 ? W * R * 64 : 1];
   const int tid = threadIdx.x, wave = wave_index(tid), lane = tid & 63, r = lane & 15, kg = lane >> 4;
-  const int ks = blockIdx.z;
-  int slot = blockIdx.y;
+  // the slot is the slowest grid index: workgroups are dispatched in index order, so those of slots beyond the
+  // union (they read the union's size and exit) come after all the live ones instead of between them
+  const int ks = blockIdx.y;
+  int slot = blockIdx.z;
   const char* W2;
   const float* S2 = nullptr;
   const size_t per = (size_t)g.ffn * g.d * (FP8 ? 1 : 2);

@@ -460,7 +460,7 @@ void launch_gateup(const moe_ctx* c, const GateupArgs& a, hipStream_t st) {  // 
 // are read in 64-byte row segments whose cache lines are completed by the next k-step -> cached loads.
 template <int R, int P>
 void launch_down(const moe_ctx* c, const DownArgs& a, bool tiled, bool fp8, hipStream_t st) {
-  const dim3 grid((c->s.d / 16 + R - 1) / R, a.routed_slots + c->s.n_shared, a.KS), block(64 * kWaves);
+  const dim3 grid((c->s.d / 16 + R - 1) / R, a.KS, a.routed_slots + c->s.n_shared), block(64 * kWaves);
   const bool pk = a.T <= kPackedTokens;
   constexpr int PF = P > 4 ? 4 : P;  // an FP8 stage carries the fragments of two k-steps: depth 4 at most
   if (fp8 && tiled) {
@@ -562,7 +562,7 @@ moe_status launch_experts(moe_ctx* c, const RouteSet& rs, const moe_layer_weight
     // FP8 weights with split fragments (T > 8) need as many fragment bytes from L2 as weight bytes from HBM at 4
     // row tiles per wave; 8 tiles at depth 2 halve that (measured: 63 -> 60 us on the Mixtral-shaped layer at T = 9;
     // with packed fragments, and with bf16 weights, 4 tiles at depth 4 stay faster)
-    const dim3 grid((s.d / 16 + 7) / 8, routed_slots + s.n_shared, da.KS), block(64 * kWaves);
+    const dim3 grid((s.d / 16 + 7) / 8, da.KS, routed_slots + s.n_shared), block(64 * kWaves);
     hipLaunchKernelGGL((down_kernel<8, kWaves, 2, true, true, true, false>), grid, block, 0, st, da);
   } else {
     switch (p.dn_R) {
