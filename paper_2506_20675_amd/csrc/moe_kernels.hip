@@ -221,7 +221,8 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   // fragment byte per weight byte, but takes H in a compact layout of 2 T columns, so with few tokens in flight that
   // costs little, and it writes no slabs.  Measured against split-K + slab sum on all six shapes, each forced both
   // ways at every K: with bf16 weights it wins for T <= 5 (Mixtral-shaped layer 3-8 us at K = 0..3, Phi-3.5-like up
-  // to 7 us, the 64-expert shapes 1-3 us) and loses from T = 6 or 7 on; with FP8 weights for T <= 4.  Where the slab
+  // to 7 us, the 64-expert shapes 1-3 us), at T = 6 still by 2-4 us on the 4096-wide layers, and loses from T = 6 or
+  // 7 on; with FP8 weights for T <= 4.  Where the slab
   // sum costs no launch anyway (moe_verify_stack, chained stacks) it still wins for T <= 4 with bf16 weights on
   // layers that give every compute unit a whole row tile (d / 16 >= 256: 3-5 us per layer); it loses on narrower
   // ones, whose half-tile workgroups fetch two fragment bytes per weight byte, and is level or worse with FP8 weights.  Items = live slots x k-chunks, dealt to 16 waves; every
@@ -231,7 +232,7 @@ Plan plan_for(const moe_shape& s, const int* plan_override, int fused_mode, int 
   bool fuse = false;
   if (tiled && T <= kPackedTokens && slots <= kFusedMaxSlots)
     fuse = combine_rides ? (!fp8 && s.d / 16 >= kFusedHalvesBelow && T <= kFusedMaxTokensRiding)
-                         : T <= (fp8 ? kFusedMaxTokensFp8 : kFusedMaxTokensBf16);
+                         : T <= (fp8 ? kFusedMaxTokensFp8 : kFusedMaxTokensBf16 + (s.d / 16 >= kFusedHalvesBelow ? 1 : 0));
   if (fused_mode >= 0) fuse = fused_mode > 0 && tiled;
   if (fuse) {
     // the split that gives the 16 waves the fewest rounds of the shortest items for the expected union, an item

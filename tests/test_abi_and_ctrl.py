@@ -141,7 +141,8 @@ def test_launch_plan_is_host_arithmetic_with_sane_invariants():
     """moe_plan_query needs no device.  For every benchmark shape, weight type and T: the split-K factor is a power of
     two that leaves every wave at least 4 k-steps, the workspace rule (slabs per slot <= 16) holds, tile counts are
     from the instantiated set, the fused down + combine launch is chosen exactly for tiled weights with few tokens in
-    flight (T <= 5 with bf16, T <= 4 with FP8 weights; unions of at most 32 slots), and the launch count follows from
+    flight (T <= 5 with bf16 — 6 where d gives at least 256 row tiles —, T <= 4 with FP8 weights; unions of at most 32
+    slots), and the launch count follows from
     the choices."""
     from paper_2506_20675_amd import synth
     seen_fused = seen_split = False
@@ -160,8 +161,8 @@ def test_launch_plan_is_host_arithmetic_with_sane_invariants():
                     ks, nsteps = p["dn_split_k"], cfg.ffn // (64 if dtype else 32)
                     assert 1 <= ks <= 16 and ks & (ks - 1) == 0
                     assert ks == 1 or nsteps // (4 * ks) >= 4
-                    want_fused = (layout == binding.MOE_LAYOUT_TILED and T <= (4 if dtype else 5)
-                                  and p["expected_slots"] <= 32)
+                    want_fused = (layout == binding.MOE_LAYOUT_TILED and p["expected_slots"] <= 32
+                                  and T <= (4 if dtype else (6 if cfg.d // 16 >= 256 else 5)))
                     assert (p["dn_fused_chunks"] > 0) == want_fused
                     if p["dn_fused_chunks"] > 0:
                         seen_fused = True
