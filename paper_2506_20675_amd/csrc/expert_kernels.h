@@ -360,13 +360,15 @@ __global__ __launch_bounds__(64 * W) void down_kernel(DownArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Steps 4 + 5 in one launch, for small unions of SMALL experts (a few tens of MB in the whole step), where the
-// step is bound by launch latencies and not by HBM: one workgroup of 16 waves per 16-row tile of d walks ALL live slots.  The waves take (slot, k-chunk)
+// Steps 4 + 5 in one launch, for steps with few tokens in flight: one workgroup of 16 waves per 16-row tile of d
+// walks ALL live slots.  The waves take (slot, k-chunk)
 // items round-robin; because the gate is already folded into H and the columns of unrouted tokens are masked to
 // zero, every item simply adds into the wave's one accumulator tile, so the sum over a token's experts — the
 // combine — happens in registers, the 16 waves meet in LDS in a fixed order, and out[t] is written directly:
-// no slabs, no combine launch.  (On large experts the split-K kernel above streams better: it shares each H
-// fragment among 4 row tiles.)   grid = d / 16.
+// no slabs, no combine launch.  One row tile per wave means one H fragment byte per weight byte where the split-K
+// kernel above shares each fragment among 4 row tiles; that is affordable because this kernel takes H in the compact
+// packed layout (frag_unit_compact: 2 T columns instead of 16), and it is why the kernel is used up to T = 5 or 6
+// only.   grid = d / 16.
 // halves = 2 (when d / 16 alone would leave compute units without a workgroup): two workgroups per tile, each
 // owning 8 of its 16 rows.  A lane whose row belongs to the other workgroup loads the address of its partner lane
 // (row r ^ 8) instead — the same 16 bytes, so the pair costs one request and the workgroup fetches only its own 128-byte

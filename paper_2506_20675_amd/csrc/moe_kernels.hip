@@ -159,7 +159,7 @@ struct moe_ctx {
 
 namespace {
 
-constexpr int kProfMarks = 5;  // events per profiled layer-step: route, gate/up, down, combine
+constexpr int kProfMarks = 5;  // events per profiled layer-step, bracketing route, gate/up, down, combine
 constexpr int kWaves = 4;    // waves per workgroup in the expert kernels (they split K)
 constexpr int kMaxKS = 16;   // largest split-K factor of the down projection
 // The fused down + combine launch is chosen by the number of tokens in flight (see plan_for): with few tokens its
@@ -176,7 +176,7 @@ constexpr int kWideRouterExperts = 32;  // from this many experts on, routing go
 // Chosen from measurements on Mixtral-shaped layers (see plan_for).
 struct Plan {
   int gu_R, dn_R, dn_KS;
-  int dn_fused_C;  // > 0: small experts, down projection and combine in one launch with this many k-chunks per slot
+  int dn_fused_C;  // > 0: few tokens in flight: down projection and combine in one launch with this many k-chunks per slot
 };
 
 int ks_cap_for(const moe_shape& s, bool fp8) {
