@@ -305,7 +305,7 @@ moe_status moe_weight_load_twin(const void* a, const void* b, int32_t slots, int
  *   dn_tiles         16-row tiles of w2 per wavefront in the down kernel
  *   dn_split_k       k-chunks of the down projection across workgroups (slabs per slot)
  *   dn_fused_chunks  > 0: down projection and combine run as one launch with this many k-chunks per slot
- *                    (small unions of small experts); dn_tiles / dn_split_k are then unused
+ *                    (few tokens in flight); dn_tiles / dn_split_k are then unused
  *   launches         kernel launches of one moe_verify_layer call
  * Errors: MOE_ERR_INVALID_ARG for NULL pointers, T outside 1..max_tokens or unknown layout / dtype;
  * MOE_ERR_UNSUPPORTED_SHAPE as moe_ctx_create, and for FP8 when d or ffn is not a multiple of 64. */

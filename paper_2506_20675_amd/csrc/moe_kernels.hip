@@ -13,7 +13,7 @@
 //   gateup_kernel  for each slot of the union: G = w1 X, U = w3 X, H = gate * silu(G) * U   (2/3 of bytes)
 //   down_kernel    split-K partial sums of w2 H over (slot, k-chunk)                        (1/3 of bytes)
 //   combine_kernel out[t] = sum of the slabs of token t's own picks, in pick order (deterministic, no atomics)
-//   down_fused_kernel   steps 4 + 5 in one launch for small unions of small experts
+//   down_fused_kernel   steps 4 + 5 in one launch for steps with few tokens in flight (compact H fragments)
 //   *_ahead_kernel      steps 1 + 2 for a batch of layers at once, where all their inputs are known up front
 //                       (moe_verify_stack); there the slab sum also rides in the next layer's gate/up launch
 //
